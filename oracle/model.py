@@ -1,0 +1,124 @@
+"""Scores, loss and analytic gradients of one chunk (oracle; float64; test infrastructure).
+
+Notation follows Sec. 6 of the paper: the score has the form
+(theta_s (x) theta_r) (+) theta_d, with (+) an inner product for the
+multiplication-based models, so the negative block of a chunk is one real matrix
+product.  u = theta_s (x) theta_r is the paper's "Intermediate Result 1"; its
+mirror for source-side corruption is v = conj(theta_r) (x) theta_d, so that
+f = <u, theta_d> = <theta_s, v>.  Embeddings of dimension d hold ComplEx numbers
+as [real half | imaginary half] (Sec. 6, "first half / last half").
+
+Loss: Eq. 1 as printed (the log-sum-exp runs over the sampled negatives only),
+or a logistic loss.  Both are sums, not means.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+DOT, DISTMULT, COMPLEX = 0, 1, 2
+SOFTMAX, LOGISTIC = 0, 1
+
+
+def _halves(x):
+    h = x.shape[-1] // 2
+    return x[..., :h], x[..., h:]
+
+
+def cmul(a, b):
+    """Complex product a*b on [re | im] rows."""
+    ar, ai = _halves(a)
+    br, bi = _halves(b)
+    return np.concatenate([ar * br - ai * bi, ar * bi + ai * br], axis=-1)
+
+
+def cmul_conj(a, b):
+    """conj(a)*b on [re | im] rows."""
+    ar, ai = _halves(a)
+    br, bi = _halves(b)
+    return np.concatenate([ar * br + ai * bi, ar * bi - ai * br], axis=-1)
+
+
+def compose_u(score, s, r):
+    """u = theta_s (x) theta_r."""
+    if score == DOT:
+        return s.copy()
+    if score == DISTMULT:
+        return s * r
+    return cmul(s, r)
+
+
+def compose_v(score, r, d):
+    """v = conj(theta_r) (x) theta_d  (the operand that meets theta_s)."""
+    if score == DOT:
+        return d.copy()
+    if score == DISTMULT:
+        return r * d
+    return cmul_conj(r, d)
+
+
+def positive_scores(score, s, r, d):
+    return np.sum(compose_u(score, s, r) * d, axis=-1)
+
+
+def side_loss(loss, f, S, neg_weight):
+    """Loss terms and their derivatives for one chunk and one corrupted side.
+
+    f: positive scores [C]; S: negative scores [C, N].
+    Returns (loss_e [C], a_e = dl/df [C], W = dl/dS [C, N])."""
+    if loss == SOFTMAX:
+        m = S.max(axis=1, keepdims=True)
+        ex = np.exp(S - m)
+        z = ex.sum(axis=1, keepdims=True)
+        lse = (m + np.log(z))[:, 0]
+        return -f + lse, -np.ones_like(f), ex / z
+    # logistic: softplus(-f) + w * sum_k softplus(S_k)
+    sp = lambda x: np.logaddexp(0.0, x)
+    sig = lambda x: 0.5 * (1.0 + np.tanh(0.5 * x))
+    l = sp(-f) + neg_weight * sp(S).sum(axis=1)
+    return l, -sig(-f), neg_weight * sig(S)
+
+
+def chain_from_u(score, g_u, s, r):
+    """(g_s, g_r) from the gradient with respect to u = s (x) r."""
+    if score == DOT:
+        return g_u, None
+    if score == DISTMULT:
+        return r * g_u, s * g_u
+    return cmul_conj(r, g_u), cmul_conj(s, g_u)
+
+
+def chain_from_v(score, g_v, r, d):
+    """(g_d, g_r) from the gradient with respect to v = conj(r) (x) d."""
+    if score == DOT:
+        return g_v, None
+    if score == DISTMULT:
+        return r * g_v, d * g_v
+    return cmul(r, g_v), cmul_conj(g_v, d)
+
+
+def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs):
+    """Loss and gradients of one chunk for one corrupted side.
+
+    s, r, d: [C, dim] float64 rows of the chunk's positive edges (r ignored for Dot).
+    negs:    [N, dim] float64 rows of the shared negatives of this side.
+    Returns dict(loss [C], f [C], S [C,N], g_s, g_r (or None), g_d [C,dim], g_neg [N,dim])."""
+    if side_is_dst:
+        q = compose_u(score, s, r)       # meets destination-like rows
+        other = d
+    else:
+        q = compose_v(score, r, d)       # meets source-like rows
+        other = s
+    f = np.sum(q * other, axis=1)
+    S = q @ negs.T
+    l, a, W = side_loss(loss, f, S, neg_weight)
+    g_q = a[:, None] * other + W @ negs
+    g_other = a[:, None] * q
+    g_neg = W.T @ q
+    if side_is_dst:
+        g_s, g_r = chain_from_u(score, g_q, s, r)
+        g_d = g_other
+    else:
+        g_d, g_r = chain_from_v(score, g_q, r, d)
+        g_s = g_other
+    return dict(loss=l, f=f, S=S, W=W, g_s=g_s, g_r=g_r, g_d=g_d, g_neg=g_neg)

@@ -1,0 +1,220 @@
+"""Pins for the oracle's scores, loss and gradients (Eq. 1, Sec. 6 operator structure)."""
+
+import itertools
+
+import numpy as np
+import pytest
+import torch
+from scipy.special import logsumexp
+
+from oracle import model, negatives
+from oracle.bucket import OracleConfig, Tables, batch_gradients
+
+
+# ---------------------------------------------------------------- scores
+
+def test_closed_form_scores_on_three_node_graph():
+    # d = 2, integer-valued rows: every product is exact.
+    a, b, c = np.array([[1., 2.]]), np.array([[3., -1.]]), np.array([[-2., 5.]])
+    r = np.array([[2., 3.]])
+    assert model.positive_scores(model.DOT, a, None, b)[0] == 1 * 3 + 2 * -1
+    assert model.positive_scores(model.DISTMULT, a, r, c)[0] == 1 * 2 * -2 + 2 * 3 * 5
+    # ComplEx with one complex component: a = 1+2i, r = 2+3i, c = -2+5i, Re(a r conj(c))
+    want = ((1 + 2j) * (2 + 3j) * np.conj(-2 + 5j)).real
+    assert model.positive_scores(model.COMPLEX, a, r, c)[0] == want == 43.0
+
+
+def test_complex_matches_numpy_complex_arithmetic():
+    rng = np.random.default_rng(0)
+    h = 5
+    s, r, d = (rng.standard_normal((7, 2 * h)) for _ in range(3))
+    cs, cr, cd = (x[:, :h] + 1j * x[:, h:] for x in (s, r, d))
+    want = np.real(np.sum(cs * cr * np.conj(cd), axis=1))
+    np.testing.assert_allclose(model.positive_scores(model.COMPLEX, s, r, d), want, rtol=1e-13, atol=1e-13)
+    # u = s*r, v = conj(r)*d as complex numbers
+    u = model.compose_u(model.COMPLEX, s, r)
+    v = model.compose_v(model.COMPLEX, r, d)
+    np.testing.assert_allclose(u[:, :h] + 1j * u[:, h:], cs * cr, rtol=1e-13)
+    np.testing.assert_allclose(v[:, :h] + 1j * v[:, h:], np.conj(cr) * cd, rtol=1e-13)
+
+
+@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
+def test_u_dot_d_equals_s_dot_v(score):
+    rng = np.random.default_rng(1)
+    s, r, d = (rng.standard_normal((9, 8)) for _ in range(3))
+    u = model.compose_u(score, s, r)
+    v = model.compose_v(score, r, d)
+    np.testing.assert_allclose(np.sum(u * d, 1), np.sum(s * v, 1), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
+def test_negative_block_is_the_score_of_the_corrupted_triple(score):
+    rng = np.random.default_rng(2)
+    s, r, d = (rng.standard_normal((4, 6)) for _ in range(3))
+    negs = rng.standard_normal((5, 6))
+    out_d = model.chunk_side(score, model.SOFTMAX, 1.0, True, s, r, d, negs)
+    out_s = model.chunk_side(score, model.SOFTMAX, 1.0, False, s, r, d, negs)
+    for e, k in itertools.product(range(4), range(5)):
+        f_d = model.positive_scores(score, s[e:e + 1], r[e:e + 1], negs[k:k + 1])[0]
+        f_s = model.positive_scores(score, negs[k:k + 1], r[e:e + 1], d[e:e + 1])[0]
+        assert abs(out_d["S"][e, k] - f_d) < 1e-12
+        assert abs(out_s["S"][e, k] - f_s) < 1e-12
+
+
+# ---------------------------------------------------------------- loss
+
+def test_softmax_single_and_double_negative_closed_forms():
+    f = np.array([0.25, -1.0])
+    S = np.array([[0.75], [2.0]])
+    l, a, W = model.side_loss(model.SOFTMAX, f, S, 1.0)
+    np.testing.assert_allclose(l, S[:, 0] - f, rtol=0, atol=1e-15)
+    assert (W == 1.0).all() and (a == -1.0).all()
+    S2 = np.repeat(S, 2, axis=1)
+    l2, _, W2 = model.side_loss(model.SOFTMAX, f, S2, 1.0)
+    np.testing.assert_allclose(l2, S[:, 0] - f + np.log(2.0), atol=1e-15)
+    np.testing.assert_allclose(W2, 0.5, atol=1e-15)
+
+
+def test_softmax_matches_scipy_and_is_shift_invariant():
+    rng = np.random.default_rng(3)
+    f = rng.standard_normal(6)
+    S = 5 * rng.standard_normal((6, 11))
+    l, _, W = model.side_loss(model.SOFTMAX, f, S, 1.0)
+    np.testing.assert_allclose(l, -f + logsumexp(S, axis=1), rtol=1e-13)
+    np.testing.assert_allclose(W.sum(1), 1.0, rtol=1e-13)
+    l3, _, W3 = model.side_loss(model.SOFTMAX, f, S + 3.5, 1.0)
+    np.testing.assert_allclose(l3, l + 3.5, rtol=1e-12)
+    np.testing.assert_allclose(W3, W, rtol=1e-12)
+    # large scores do not overflow
+    lbig, _, _ = model.side_loss(model.SOFTMAX, f, S + 800.0, 1.0)
+    assert np.isfinite(lbig).all()
+
+
+def test_logistic_closed_forms():
+    f = np.array([0.0, 2.0])
+    S = np.array([[0.0, 0.0], [-1.0, 3.0]])
+    l, a, W = model.side_loss(model.LOGISTIC, f, S, 0.5)
+    sp = lambda x: np.log1p(np.exp(x))
+    np.testing.assert_allclose(l, sp(-f) + 0.5 * sp(S).sum(1), rtol=1e-13)
+    np.testing.assert_allclose(a, -1 / (1 + np.exp(f)), rtol=1e-13)
+    np.testing.assert_allclose(W, 0.5 / (1 + np.exp(-S)), rtol=1e-13)
+    assert abs(l[0] - (np.log(2) + np.log(2))) < 1e-14
+
+
+# ---------------------------------------------------------------- gradients
+
+def _tiny(score, loss, corrupt, i, j, seed=0, degree_negs=0):
+    cfg = OracleConfig(num_nodes=8, num_relations=3 if score else 0, dim=6, num_partitions=2,
+                       batch_size=5, chunk_size=2, num_negs=3, num_degree_negs=degree_negs,
+                       score=score, loss=loss, corrupt=corrupt, seed=seed, neg_weight=0.4)
+    rng = np.random.default_rng(seed + 10)
+    node = (0.7 * rng.standard_normal((8, 6))).astype(np.float32)
+    rel = (0.7 * rng.standard_normal((3, 6))).astype(np.float32)
+    edges = np.stack([rng.integers(0, 4, 5), rng.integers(0, 3, 5), rng.integers(0, 4, 5)], 1).astype(np.int32)
+    return cfg, node, rel, edges
+
+
+def _loss_only(cfg, node, rel, edges, i, j):
+    tab = Tables(cfg, node.astype(np.float32), rel)
+    # tables hold float32; for differences work in float64 copies
+    tab.E = [node[p * 4:(p + 1) * 4].astype(np.float64) for p in range(2)]
+    tab.RE = rel.astype(np.float64)
+    return batch_gradients(tab, i, j, edges, 0, 0)[0]
+
+
+@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
+@pytest.mark.parametrize("loss", [model.SOFTMAX, model.LOGISTIC])
+@pytest.mark.parametrize("corrupt", [0, 1, 2])
+@pytest.mark.parametrize("bucket", [(0, 0), (0, 1), (1, 0)])
+def test_gradients_match_central_finite_differences(score, loss, corrupt, bucket):
+    i, j = bucket
+    cfg, node32, rel32, edges = _tiny(score, loss, corrupt, i, j, degree_negs=1)
+    node, rel = node32.astype(np.float64), rel32.astype(np.float64)
+    tab = Tables(cfg, node32, rel32)
+    _, gnode, grel = batch_gradients(tab, i, j, edges, 0, 0)
+    dense = np.zeros_like(node)
+    for slot, part in ((0, i), (1, j)):
+        if slot in gnode:
+            rows, g = gnode[slot]
+            dense[part * 4 + rows] += g
+    h = 1e-6
+    fd = np.zeros_like(node)
+    for idx in np.ndindex(*node.shape):
+        up, dn = node.copy(), node.copy()
+        up[idx] += h
+        dn[idx] -= h
+        fd[idx] = (_loss_only(cfg, up, rel, edges, i, j) - _loss_only(cfg, dn, rel, edges, i, j)) / (2 * h)
+    np.testing.assert_allclose(dense, fd, rtol=2e-6, atol=2e-8)
+    if score != model.DOT:
+        drel = np.zeros_like(rel)
+        drel[grel[0]] = grel[1]
+        fdr = np.zeros_like(rel)
+        for idx in np.ndindex(*rel.shape):
+            up, dn = rel.copy(), rel.copy()
+            up[idx] += h
+            dn[idx] -= h
+            fdr[idx] = (_loss_only(cfg, node, up, edges, i, j) - _loss_only(cfg, node, dn, edges, i, j)) / (2 * h)
+        np.testing.assert_allclose(drel, fdr, rtol=2e-6, atol=2e-8)
+    else:
+        assert grel is None
+
+
+def _torch_score(score, s, r, d):
+    if score == model.DOT:
+        return (s * d).sum(-1)
+    if score == model.DISTMULT:
+        return (s * r * d).sum(-1)
+    h = s.shape[-1] // 2
+    cs, cr, cd = (torch.complex(x[..., :h], x[..., h:]) for x in (s, r, d))
+    return (cs * cr * torch.conj(cd)).real.sum(-1)
+
+
+@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
+@pytest.mark.parametrize("bucket", [(0, 0), (1, 0)])
+def test_gradients_match_autograd_on_eq1_written_edge_by_edge(score, bucket):
+    # Eq. 1 with the sampled negatives, written per positive edge and per
+    # corrupted triple with no shared intermediates, differentiated by autograd.
+    i, j = bucket
+    cfg, node32, rel32, edges = _tiny(score, model.SOFTMAX, 2, i, j, seed=4)
+    tab = Tables(cfg, node32, rel32)
+    loss, gnode, grel = batch_gradients(tab, i, j, edges, 0, 0)
+    neg = negatives.batch_negatives(cfg, 0, i, j, 0, edges, edges)
+
+    tn = torch.tensor(node32, dtype=torch.float64, requires_grad=True)
+    tr = torch.tensor(rel32, dtype=torch.float64, requires_grad=True)
+    total = torch.zeros((), dtype=torch.float64)
+    for e_idx, (sl, rl, dl) in enumerate(edges):
+        c = e_idx // cfg.chunk_size
+        s, r, d = tn[i * 4 + sl], tr[rl], tn[j * 4 + dl]
+        f = _torch_score(score, s, r, d)
+        dst_negs = torch.stack([_torch_score(score, s, r, tn[j * 4 + int(k)]) for k in neg[0, c]])
+        src_negs = torch.stack([_torch_score(score, tn[i * 4 + int(k)], r, d) for k in neg[1, c]])
+        total = total - (f - torch.logsumexp(dst_negs, 0)) - (f - torch.logsumexp(src_negs, 0))
+    total.backward()
+    assert abs(float(total) - loss) < 1e-10
+    dense = np.zeros((8, 6))
+    for slot, part in ((0, i), (1, j)):
+        if slot in gnode:
+            rows, g = gnode[slot]
+            dense[part * 4 + rows] += g
+    np.testing.assert_allclose(dense, tn.grad.numpy(), rtol=1e-10, atol=1e-12)
+    if score != model.DOT:
+        drel = np.zeros((3, 6))
+        drel[grel[0]] = grel[1]
+        np.testing.assert_allclose(drel, tr.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_softmax_gradient_invariants():
+    rng = np.random.default_rng(5)
+    s, r, d = (rng.standard_normal((4, 6)) for _ in range(3))
+    negs = rng.standard_normal((7, 6))
+    out = model.chunk_side(model.DISTMULT, model.SOFTMAX, 1.0, True, s, r, d, negs)
+    u = s * r
+    # sum_k W_ek = 1  =>  sum_k g_neg(k) = sum_e u_e
+    np.testing.assert_allclose(out["g_neg"].sum(0), u.sum(0), rtol=1e-12)
+    # g_u + d lies in the convex hull of the negatives: coefficients W >= 0 summing to 1
+    g_u = out["W"] @ negs - d
+    np.testing.assert_allclose(g_u + d, out["W"] @ negs, rtol=1e-12)
+    assert (out["W"] >= 0).all()
+    # g_d = -u for Eq. 1
+    np.testing.assert_allclose(out["g_d"], -u, rtol=1e-15)
