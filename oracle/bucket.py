@@ -95,12 +95,17 @@ def adagrad_rows(theta: np.ndarray, state: np.ndarray, rows: np.ndarray, grad64:
     theta[rows] = theta[rows] - step
 
 
-def _coalesce(keys: List[np.ndarray], grads: List[np.ndarray]):
+def _coalesce(keys: List[np.ndarray], grads: List[np.ndarray], abs_out: Optional[list] = None):
     k = np.concatenate(keys)
     g = np.concatenate(grads, axis=0)
     uniq, inv = np.unique(k, return_inverse=True)
     acc = np.zeros((uniq.size, g.shape[1]), np.float64)
     np.add.at(acc, inv, g)
+    if abs_out is not None:
+        # sum of |terms| per element: lets a test tell which sums nearly cancel
+        mag = np.zeros_like(acc)
+        np.add.at(mag, inv, np.abs(g))
+        abs_out.append(mag)
     return uniq, acc
 
 
@@ -150,9 +155,23 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
             if record is not None:
                 record.setdefault("chunks", []).append((si, c, out))
 
-    node = {slot: _coalesce(node_keys[slot], node_grads[slot]) for slot in (0, 1) if node_keys[slot]}
-    rel = _coalesce(rel_keys, rel_grads) if (uses_rel and rel_keys) else None
+    mags = {}
+    node = {}
+    for slot in (0, 1):
+        if node_keys[slot]:
+            box = [] if record is not None else None
+            node[slot] = _coalesce(node_keys[slot], node_grads[slot], box)
+            if box:
+                mags[slot] = box[0]
+    rel = None
+    if uses_rel and rel_keys:
+        box = [] if record is not None else None
+        rel = _coalesce(rel_keys, rel_grads, box)
+        if box:
+            mags[2] = box[0]
     if record is not None:
+        record["grad_abs_sums"] = mags
+        record["grads"] = (node, rel)
         record["neg_ids"] = neg
         record["touched"] = negatives.touched_rows(cfg, i, j, e, neg)
     return loss, node, rel

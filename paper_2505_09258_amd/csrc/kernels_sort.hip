@@ -1,0 +1,244 @@
+// Stable LSD radix sort of (key, occurrence index) pairs and the segment heads of the
+// sorted keys.  This is what makes the deterministic update mode deterministic: equal
+// keys keep their occurrence order, so the gradient rows of one table row are always
+// summed in the same order (paper Sec. 2.1 stage 6; the sorting itself is this
+// library's design, the paper does not describe its update kernel).
+#include "legend_internal.h"
+#include "device_utils.h"
+
+namespace legend {
+
+constexpr int kSortThreads = 256;
+constexpr int kSortItems = 8;
+constexpr int kSortTile = kSortThreads * kSortItems;   // keys per block
+constexpr int kRadix = 256;
+
+// ------------------------------------------------------------------------------------------
+// generic exclusive scan of uint32 (three kernels), n <= kSortTile * kSortTile
+// MODE 0: value = in[i].  MODE 1: value = head flag of sorted keys in[] (in[i] != in[i-1]).
+// ------------------------------------------------------------------------------------------
+template <int MODE>
+__device__ inline uint32_t scan_value(const uint32_t* __restrict__ in, int64_t i) {
+    if (MODE == 0) return in[i];
+    return (i == 0 || in[i] != in[i - 1]) ? 1u : 0u;
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(kSortThreads)
+k_scan_reduce(const uint32_t* __restrict__ in, int64_t n, uint32_t* __restrict__ block_sums) {
+    __shared__ uint32_t wsum[kSortThreads / kWave];
+    int64_t base = (int64_t)blockIdx.x * kSortTile + (int64_t)threadIdx.x * kSortItems;
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+        int64_t i = base + k;
+        if (i < n) s += scan_value<MODE>(in, i);
+    }
+    for (int off = kWave / 2; off > 0; off >>= 1) s += __shfl_down(s, off, kWave);
+    if (lane_id() == 0) wsum[threadIdx.x / kWave] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int w = 0; w < kSortThreads / kWave; ++w) t += wsum[w];
+        block_sums[blockIdx.x] = t;
+    }
+}
+
+// exclusive scan of the block sums in place by one block; total goes to block_sums[nb]
+__global__ void __launch_bounds__(kSortThreads)
+k_scan_blocksums(uint32_t* __restrict__ block_sums, int nb) {
+    __shared__ uint32_t wsum[kSortThreads / kWave];
+    __shared__ uint32_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int base = 0; base < nb; base += kSortThreads) {
+        int i = base + threadIdx.x;
+        uint32_t v = i < nb ? block_sums[i] : 0u;
+        uint32_t incl = v;
+        for (int off = 1; off < kWave; off <<= 1) {
+            uint32_t t = __shfl_up(incl, off, kWave);
+            if (lane_id() >= off) incl += t;
+        }
+        if (lane_id() == kWave - 1) wsum[threadIdx.x / kWave] = incl;
+        __syncthreads();
+        uint32_t woff = 0;
+        for (int w = 0; w < (int)(threadIdx.x / kWave); ++w) woff += wsum[w];
+        uint32_t carry = carry_s;
+        if (i < nb) block_sums[i] = carry + woff + incl - v;
+        __syncthreads();
+        if (threadIdx.x == kSortThreads - 1) carry_s = carry + woff + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) block_sums[nb] = carry_s;
+}
+
+// MODE 0: out[i] = exclusive prefix.  MODE 1: for head elements write uniq_keys / seg_start.
+template <int MODE>
+__global__ void __launch_bounds__(kSortThreads)
+k_scan_apply(const uint32_t* in, int64_t n, const uint32_t* __restrict__ block_sums,
+             uint32_t* out, uint32_t* __restrict__ seg_start, uint32_t* __restrict__ counters,
+             unsigned long long* __restrict__ uniq_total, int nb) {
+    __shared__ uint32_t wsum[kSortThreads / kWave];
+    int64_t base = (int64_t)blockIdx.x * kSortTile + (int64_t)threadIdx.x * kSortItems;
+    uint32_t v[kSortItems];
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+        int64_t i = base + k;
+        v[k] = i < n ? scan_value<MODE>(in, i) : 0u;
+        s += v[k];
+    }
+    uint32_t incl = s;
+    for (int off = 1; off < kWave; off <<= 1) {
+        uint32_t t = __shfl_up(incl, off, kWave);
+        if (lane_id() >= off) incl += t;
+    }
+    if (lane_id() == kWave - 1) wsum[threadIdx.x / kWave] = incl;
+    __syncthreads();
+    uint32_t run = block_sums[blockIdx.x] + incl - s;
+    for (int w = 0; w < (int)(threadIdx.x / kWave); ++w) run += wsum[w];
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+        int64_t i = base + k;
+        if (i < n) {
+            if (MODE == 0) {
+                out[i] = run;
+            } else if (v[k]) {
+                out[run] = in[i];                 // unique key
+                seg_start[run] = (uint32_t)i;     // first sorted position of its segment
+            }
+        }
+        run += v[k];
+    }
+    if (MODE == 1 && blockIdx.x == 0 && threadIdx.x == 0) {
+        uint32_t total = block_sums[nb];
+        seg_start[total] = (uint32_t)n;
+        counters[0] = total;
+        *uniq_total += total;
+    }
+}
+
+static hipError_t scan_launch(hipStream_t st, int mode, const uint32_t* in, int64_t n, uint32_t* tmp,
+                              uint32_t* out, uint32_t* seg_start, uint32_t* counters,
+                              unsigned long long* uniq_total) {
+    int nb = (int)((n + kSortTile - 1) / kSortTile);
+    if (nb > kSortTile) return hipErrorInvalidValue;
+    if (mode == 0) {
+        hipLaunchKernelGGL(k_scan_reduce<0>, dim3(nb), dim3(kSortThreads), 0, st, in, n, tmp);
+        hipLaunchKernelGGL(k_scan_blocksums, dim3(1), dim3(kSortThreads), 0, st, tmp, nb);
+        hipLaunchKernelGGL(k_scan_apply<0>, dim3(nb), dim3(kSortThreads), 0, st, in, n, tmp, out, seg_start,
+                           counters, uniq_total, nb);
+    } else {
+        hipLaunchKernelGGL(k_scan_reduce<1>, dim3(nb), dim3(kSortThreads), 0, st, in, n, tmp);
+        hipLaunchKernelGGL(k_scan_blocksums, dim3(1), dim3(kSortThreads), 0, st, tmp, nb);
+        hipLaunchKernelGGL(k_scan_apply<1>, dim3(nb), dim3(kSortThreads), 0, st, in, n, tmp, out, seg_start,
+                           counters, uniq_total, nb);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// radix sort pass
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kSortThreads)
+k_radix_hist(const uint32_t* __restrict__ keys, int64_t n, int shift, uint32_t* __restrict__ ghist, int nblk) {
+    __shared__ uint32_t h[kRadix];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+    for (int k = 0; k < kSortItems; ++k) {
+        int64_t i = base + k * kSortThreads + threadIdx.x;
+        if (i < n) atomicAdd(&h[(keys[i] >> shift) & (kRadix - 1)], 1u);
+    }
+    __syncthreads();
+    ghist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+// Stable scatter.  Wave w of a block owns 512 consecutive keys and walks them in 8
+// rounds of 64; the rank of a key among equal digits is (equal digits in earlier
+// waves) + (in earlier rounds of this wave) + (in lower lanes of this round).
+__global__ void __launch_bounds__(kSortThreads)
+k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in,
+                uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out, int64_t n, int shift,
+                const uint32_t* __restrict__ goff, int nblk) {
+    constexpr int kWaves = kSortThreads / kWave;
+    __shared__ uint32_t cnt[kWaves][kRadix];
+    __shared__ uint32_t pos0[kWaves][kRadix];
+    for (int i = threadIdx.x; i < kWaves * kRadix; i += kSortThreads) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    const int w = threadIdx.x / kWave;
+    const int lane = lane_id();
+    volatile uint32_t* mycnt = cnt[w];
+    const int64_t wbase = (int64_t)blockIdx.x * kSortTile + (int64_t)w * (kWave * kSortItems);
+    uint32_t key[kSortItems];
+    uint32_t rank[kSortItems];
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        int64_t i = wbase + r * kWave + lane;
+        bool valid = i < n;
+        key[r] = valid ? keys_in[i] : 0u;
+        uint32_t digit = (key[r] >> shift) & (kRadix - 1);
+        unsigned long long mask = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            bool bit = (digit >> b) & 1u;
+            unsigned long long m = __ballot(bit);
+            mask &= bit ? m : ~m;
+        }
+        unsigned long long lower = mask & ((1ull << lane) - 1ull);
+        uint32_t prefix = 0;
+        if (valid) prefix = mycnt[digit];
+        if (valid && lower == 0ull) mycnt[digit] = prefix + (uint32_t)__popcll(mask);
+        rank[r] = prefix + (uint32_t)__popcll(lower);
+    }
+    __syncthreads();
+    {
+        int d = threadIdx.x;
+        uint32_t run = goff[(int64_t)d * nblk + blockIdx.x];
+#pragma unroll
+        for (int ww = 0; ww < kWaves; ++ww) {
+            pos0[ww][d] = run;
+            run += cnt[ww][d];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        int64_t i = wbase + r * kWave + lane;
+        if (i < n) {
+            uint32_t digit = (key[r] >> shift) & (kRadix - 1);
+            uint32_t p = pos0[w][digit] + rank[r];
+            keys_out[p] = key[r];
+            vals_out[p] = vals_in ? vals_in[i] : (uint32_t)i;
+        }
+    }
+}
+
+hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf) {
+    *out_buf = 0;
+    if (n <= 0) return hipSuccess;
+    int passes = (key_bits + 7) / 8;
+    if (passes < 1) passes = 1;
+    int nblk = (int)((n + kSortTile - 1) / kSortTile);
+    int cur = 0;
+    for (int p = 0; p < passes; ++p) {
+        int shift = 8 * p;
+        hipLaunchKernelGGL(k_radix_hist, dim3(nblk), dim3(kSortThreads), 0, st, ws.keys[cur], n, shift, ws.ghist, nblk);
+        hipError_t e = scan_launch(st, 0, ws.ghist, (int64_t)kRadix * nblk, ws.scan_tmp, ws.ghist, nullptr, nullptr, nullptr);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_radix_scatter, dim3(nblk), dim3(kSortThreads), 0, st, ws.keys[cur],
+                           p == 0 ? (const uint32_t*)nullptr : ws.vals[cur], ws.keys[cur ^ 1], ws.vals[cur ^ 1], n,
+                           shift, ws.ghist, nblk);
+        cur ^= 1;
+    }
+    *out_buf = cur;
+    return hipGetLastError();
+}
+
+hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws) {
+    if (n <= 0) return hipSuccess;
+    return scan_launch(st, 1, sorted_keys, n, ws.scan_tmp, ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total);
+}
+
+}  // namespace legend

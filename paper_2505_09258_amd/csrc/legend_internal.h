@@ -1,0 +1,104 @@
+// Internal declarations shared by the host runtime and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "legend.h"
+
+namespace legend {
+
+// ---- kernel classes for per-kernel event timing --------------------------------------------
+enum KernelClass : int {
+    KC_PREPARE = 0,   // negative ids + sort keys of a batch
+    KC_SORT,          // radix sort passes (histogram, scan, scatter) + segment heads
+    KC_CHUNK,         // fused gather + scores + loss + backward per chunk (MFMA)
+    KC_UPDATE,        // segmented gradient reduce + Adagrad
+    KC_MISC,          // loss reduction, validation, scoring
+    KC_COUNT
+};
+
+// ---- geometry of one batch --------------------------------------------------------------------
+// Occurrence list: every gradient row a batch produces has a fixed position.
+//   per side slot (dst side first, then src side):
+//     [0, P)            gradient rows of the source embeddings of the P positives
+//     [P, 2P)           gradient rows of the destination embeddings
+//     [2P, 3P)          gradient rows of the relation embeddings (only if the score uses them)
+//     then, chunk-major: for chunk c, row tile t, negative k:  ((c * T + t) * N + k)
+struct BatchGeom {
+    int32_t P;            // positives in this batch
+    int32_t C;            // chunk size
+    int32_t N;            // negatives per chunk and side
+    int32_t T;            // row tiles per chunk (workgroups per chunk and side)
+    int32_t rows_tile;    // positives handled by one workgroup (<= 64)
+    int32_t nchunks;
+    int32_t sides;        // 1 or 2
+    int32_t side_id[2];   // 0 = dst corrupted, 1 = src corrupted
+    int32_t roles;        // 2 or 3 (with relation rows)
+    int64_t per_side;     // occurrences per side
+    int64_t n_occ;        // total occurrences
+};
+
+// Everything the per-batch kernels need to know about the bucket and the model.
+struct BucketParams {
+    const int32_t* edges;      // device, [m][3]
+    int64_t m;                 // edges in the bucket
+    int64_t batch_lo;          // first edge of the batch
+    float* E_src; float* S_src;   // slot of partition i
+    float* E_dst; float* S_dst;   // slot of partition j
+    float* E_rel; float* S_rel;   // relation table
+    int32_t rows_valid_src;    // valid rows of partition i
+    int32_t rows_valid_dst;
+    int32_t num_relations;
+    int32_t dim;
+    int32_t score, loss;
+    int32_t same_part;         // i == j
+    uint32_t key_base_dst;     // key offset of table slot 1 (0 when same_part)
+    uint32_t key_base_rel;     // key offset of the relation table
+    int32_t num_degree_negs;
+    float lr, eps, neg_weight;
+    uint64_t hash_prefix;      // hash state after (seed, epoch, i, j, b)
+};
+
+// Per-batch device workspace.
+struct Workspace {
+    int32_t*  neg_ids;        // [sides][nchunks][N]
+    uint32_t* keys[2];        // sort double buffer
+    uint32_t* vals[2];
+    uint32_t* ghist;          // [256][nblocks] radix histogram
+    uint32_t* scan_tmp;       // block sums of the generic scan
+    uint32_t* uniq_keys;      // [n_occ]
+    uint32_t* seg_start;      // [n_occ + 1]
+    uint32_t* counters;       // [0] = unique rows of the batch, [1] = error flag
+    unsigned long long* uniq_total;  // running sum of unique rows
+    float*    grad;           // [n_occ][dim] staged gradient rows
+    double*   loss_partial;   // one per chunk workgroup
+    double*   loss_sum;       // running bucket loss
+    int64_t   cap_occ;
+    int64_t   cap_wg;
+};
+
+// ---- launch wrappers (defined in the kernel translation units) --------------------------------
+hipError_t launch_validate_edges(hipStream_t st, const int32_t* edges, int64_t m, int32_t rows_src,
+                                 int32_t rows_dst, int32_t num_rel, int check_rel, uint32_t* err_flag);
+hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+// sorts ws.keys[0]/vals[0] (n_occ entries); result buffer index returned in *out_buf
+hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
+hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws);
+hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                         const uint32_t* sorted_vals, int32_t rows_per_partition);
+hipError_t launch_loss_reduce(hipStream_t st, int64_t nwg, const Workspace& ws);
+hipError_t launch_score(hipStream_t st, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m,
+                        float* const* part_emb, int32_t rows_per_partition, int32_t num_partitions,
+                        int64_t num_nodes, const float* E_rel, int32_t num_relations, int32_t dim,
+                        int32_t score, float* out, uint32_t* err_flag);
+hipError_t launch_gather_rows(hipStream_t st, const int64_t* ids, int64_t m, float* const* part_base,
+                              int32_t rows_per_partition, int64_t num_rows, int32_t dim, float* out,
+                              uint32_t* err_flag);
+
+int row_tiles_for(int chunk_size);          // T
+int rows_per_tile_for(int chunk_size);      // ceil(C / T)
+int max_dim_supported();
+
+}  // namespace legend

@@ -1,0 +1,819 @@
+// Host runtime behind the C ABI: partition store (pinned host tier + HBM buffer slots),
+// swap scheduling on a side stream, the per-bucket batch loop, reads and diagnostics.
+// Paper: Sec. 3 (storage arrangement, steps 1-8), Sec. 4 (buffer of three, prefetching).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "legend_internal.h"
+#include "device_utils.h"
+
+using namespace legend;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "misc"};
+
+struct ProfSpan {
+    int cls;
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct legend_ctx {
+    legend_config cfg{};
+    int64_t V = 0;
+    int n = 0, cap = 0, d = 0;
+    int64_t Rp = 0;
+    size_t part_floats = 0;                 // 2 * Rp * d
+    int nrel_rows = 1;
+    bool uses_rel = false;
+    std::vector<float*> host_part;          // pinned [E_p | S_p]
+    std::vector<float*> slot_mem;           // device [E | S]
+    std::vector<int> slot_part, part_slot;
+    std::vector<hipEvent_t> slot_ready;
+    std::vector<char> slot_pending;
+    float* E_rel = nullptr;
+    float* S_rel = nullptr;
+    float** d_part_emb = nullptr;           // device: embedding base per partition or null
+    float** d_part_state = nullptr;
+    hipStream_t compute = nullptr, copy = nullptr;
+    bool own_compute = false, own_copy = false;
+    hipEvent_t ev_fence = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
+    Workspace ws{};
+    BatchGeom gmax{};
+    int key_bits = 0;
+    int32_t* edges_dev = nullptr;
+    int64_t edges_cap = 0;
+    void* io_dev = nullptr;                 // scratch for score / read calls
+    size_t io_cap = 0;
+    uint32_t prof_mask = 0;
+    std::vector<ProfSpan> prof_spans;
+    std::vector<hipEvent_t> prof_pool;
+    double prof_ms[KC_COUNT] = {0};
+    int64_t prof_launches[KC_COUNT] = {0};
+    int64_t batches_done = 0;
+    bool part_tables_dirty = false;         // d_part_emb / d_part_state lag behind part_slot
+    bool fatal = false;
+};
+
+namespace {
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t _e = (expr);                                                                   \
+        if (_e != hipSuccess) {                                                                   \
+            if (ctx) (ctx)->fatal = true;                                                         \
+            return fail(LEGEND_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),     \
+                        __FILE__, __LINE__);                                                      \
+        }                                                                                         \
+    } while (0)
+
+int64_t rows_valid(const legend_ctx* c, int part) {
+    int64_t lo = (int64_t)part * c->Rp;
+    return std::max<int64_t>(0, std::min<int64_t>(c->Rp, c->V - lo));
+}
+
+BatchGeom make_geom(const legend_ctx* c, int P) {
+    BatchGeom g{};
+    const legend_config& cf = c->cfg;
+    g.P = P;
+    g.C = cf.chunk_size;
+    g.N = cf.num_negs;
+    g.T = row_tiles_for(cf.chunk_size);
+    g.rows_tile = rows_per_tile_for(cf.chunk_size);
+    g.nchunks = (P + g.C - 1) / g.C;
+    g.sides = cf.corrupt == LEGEND_CORRUPT_BOTH ? 2 : 1;
+    g.side_id[0] = cf.corrupt == LEGEND_CORRUPT_SRC ? 1 : 0;
+    g.side_id[1] = 1;
+    g.roles = c->uses_rel ? 3 : 2;
+    g.per_side = (int64_t)g.roles * P + (int64_t)g.nchunks * g.T * g.N;
+    g.n_occ = g.per_side * g.sides;
+    return g;
+}
+
+// ---- profiling ---------------------------------------------------------------------------------
+hipEvent_t prof_event(legend_ctx* c) {
+    if (!c->prof_pool.empty()) {
+        hipEvent_t e = c->prof_pool.back();
+        c->prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct ProfScope {
+    legend_ctx* c;
+    int cls;
+    hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(legend_ctx* ctx, int k) : c(ctx), cls(k) {
+        if (c->prof_mask & (1u << cls)) {
+            a = prof_event(c);
+            b = prof_event(c);
+            if (a && b) (void)hipEventRecord(a, c->compute);
+        }
+    }
+    ~ProfScope() {
+        if (a && b) {
+            (void)hipEventRecord(b, c->compute);
+            c->prof_spans.push_back({cls, a, b});
+        }
+    }
+};
+
+int prof_collect(legend_ctx* c) {
+    for (auto& s : c->prof_spans) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventSynchronize(s.b));
+        HIP_TRY(c, hipEventElapsedTime(&ms, s.a, s.b));
+        c->prof_ms[s.cls] += ms;
+        c->prof_launches[s.cls] += 1;
+        c->prof_pool.push_back(s.a);
+        c->prof_pool.push_back(s.b);
+    }
+    c->prof_spans.clear();
+    return LEGEND_OK;
+}
+
+int ensure_io(legend_ctx* c, size_t bytes) {
+    if (bytes <= c->io_cap) return LEGEND_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    if (c->io_dev) HIP_TRY(c, hipFree(c->io_dev));
+    c->io_dev = nullptr;
+    c->io_cap = 0;
+    size_t want = std::max<size_t>(bytes, 1 << 20);
+    if (hipMalloc(&c->io_dev, want) != hipSuccess) return fail(LEGEND_E_NOMEM, "device scratch of %zu bytes", want);
+    c->io_cap = want;
+    return LEGEND_OK;
+}
+
+int upload_part_tables(legend_ctx* c) {
+    std::vector<float*> e(c->n, nullptr), s(c->n, nullptr);
+    for (int p = 0; p < c->n; ++p) {
+        int sl = c->part_slot[p];
+        if (sl >= 0) {
+            e[p] = c->slot_mem[sl];
+            s[p] = c->slot_mem[sl] + c->Rp * c->d;
+        }
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->d_part_emb, e.data(), sizeof(float*) * c->n, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(c->d_part_state, s.data(), sizeof(float*) * c->n, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    c->part_tables_dirty = false;
+    return LEGEND_OK;
+}
+
+int wait_slot(legend_ctx* c, int slot) {
+    if (c->slot_pending[slot]) {
+        HIP_TRY(c, hipStreamWaitEvent(c->compute, c->slot_ready[slot], 0));
+        c->slot_pending[slot] = 0;
+    }
+    return LEGEND_OK;
+}
+
+int do_swap(legend_ctx* c, int evict, int load, bool fence_now) {
+    if (evict >= c->n || load >= c->n || evict < -1 || load < -1) return fail(LEGEND_E_INVAL, "partition id out of range");
+    if (evict < 0 && load < 0) return LEGEND_OK;
+    if (evict >= 0 && c->part_slot[evict] < 0) return fail(LEGEND_E_NOT_RESIDENT, "partition %d is not resident", evict);
+    if (load >= 0 && c->part_slot[load] >= 0) return fail(LEGEND_E_STATE, "partition %d is already resident", load);
+    int slot = -1;
+    if (evict >= 0) slot = c->part_slot[evict];
+    else
+        for (int s = 0; s < c->cap; ++s)
+            if (c->slot_part[s] < 0) { slot = s; break; }
+    if (slot < 0) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
+    const size_t bytes = c->part_floats * sizeof(float);
+    if (fence_now) {
+        HIP_TRY(c, hipEventRecord(c->ev_fence, c->compute));
+    }
+    HIP_TRY(c, hipStreamWaitEvent(c->copy, c->ev_fence, 0));
+    if (evict >= 0) {
+        HIP_TRY(c, hipMemcpyAsync(c->host_part[evict], c->slot_mem[slot], bytes, hipMemcpyDeviceToHost, c->copy));
+        c->part_slot[evict] = -1;
+        c->slot_part[slot] = -1;
+    }
+    if (load >= 0) {
+        HIP_TRY(c, hipMemcpyAsync(c->slot_mem[slot], c->host_part[load], bytes, hipMemcpyHostToDevice, c->copy));
+        HIP_TRY(c, hipEventRecord(c->slot_ready[slot], c->copy));
+        c->slot_pending[slot] = 1;
+        c->part_slot[load] = slot;
+        c->slot_part[slot] = load;
+    }
+    c->part_tables_dirty = true;
+    return LEGEND_OK;
+}
+
+void free_ctx(legend_ctx* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->cfg.device);
+    if (c->compute) (void)hipStreamSynchronize(c->compute);
+    if (c->copy) (void)hipStreamSynchronize(c->copy);
+    for (float* p : c->host_part) if (p) (void)hipHostFree(p);
+    for (float* p : c->slot_mem) if (p) (void)hipFree(p);
+    for (hipEvent_t e : c->slot_ready) if (e) (void)hipEventDestroy(e);
+    for (auto& s : c->prof_spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+    for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
+    void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
+                     c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
+                     c->ws.counters, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.loss_sum, c->edges_dev,
+                     c->io_dev};
+    for (void* p : frees) if (p) (void)hipFree(p);
+    if (c->ev_fence) (void)hipEventDestroy(c->ev_fence);
+    if (c->ev_t0) (void)hipEventDestroy(c->ev_t0);
+    if (c->ev_t1) (void)hipEventDestroy(c->ev_t1);
+    if (c->own_compute && c->compute) (void)hipStreamDestroy(c->compute);
+    if (c->own_copy && c->copy) (void)hipStreamDestroy(c->copy);
+    delete c;
+}
+
+template <typename T>
+int dev_alloc(legend_ctx* c, T** p, size_t count) {
+    void* q = nullptr;
+    size_t bytes = std::max<size_t>(count, 1) * sizeof(T);
+    if (hipMalloc(&q, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)c;
+        return fail(LEGEND_E_NOMEM, "device allocation of %zu bytes failed", bytes);
+    }
+    *p = static_cast<T*>(q);
+    return LEGEND_OK;
+}
+
+int check_ctx(legend_ctx* c) {
+    if (!c) return fail(LEGEND_E_INVAL, "null context");
+    if (c->fatal) return fail(LEGEND_E_HIP, "context is unusable after an earlier HIP failure");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(LEGEND_E_HIP, "hipSetDevice(%d) failed", c->cfg.device);
+    return LEGEND_OK;
+}
+
+// Stage a bucket's edges on the device if they are in host memory; validate ids.
+int stage_edges(legend_ctx* c, int i, int j, const int32_t* edges, int64_t m, int mem, const int32_t** dev_out) {
+    const int32_t* dev = edges;
+    if (mem == LEGEND_MEM_HOST) {
+        if (m > c->edges_cap) {
+            HIP_TRY(c, hipStreamSynchronize(c->compute));
+            if (c->edges_dev) HIP_TRY(c, hipFree(c->edges_dev));
+            c->edges_dev = nullptr;
+            c->edges_cap = 0;
+            int64_t want = std::max<int64_t>(m, 1 << 16);
+            int rc = dev_alloc(c, &c->edges_dev, (size_t)want * 3);
+            if (rc) return rc;
+            c->edges_cap = want;
+        }
+        if (m > 0)
+            HIP_TRY(c, hipMemcpyAsync(c->edges_dev, edges, (size_t)m * 3 * sizeof(int32_t), hipMemcpyHostToDevice, c->compute));
+        dev = c->edges_dev;
+    } else if (mem != LEGEND_MEM_DEVICE) {
+        return fail(LEGEND_E_INVAL, "edges_mem must be LEGEND_MEM_HOST or LEGEND_MEM_DEVICE");
+    }
+    uint32_t* flag = c->ws.counters + 1;
+    HIP_TRY(c, hipMemsetAsync(flag, 0, sizeof(uint32_t), c->compute));
+    {
+        ProfScope ps(c, KC_MISC);
+        HIP_TRY(c, launch_validate_edges(c->compute, dev, m, (int32_t)rows_valid(c, i), (int32_t)rows_valid(c, j),
+                                         c->cfg.num_relations, c->uses_rel ? 1 : 0, flag));
+    }
+    uint32_t h = 0;
+    HIP_TRY(c, hipMemcpyAsync(&h, flag, sizeof h, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    if (h) return fail(LEGEND_E_RANGE, "bucket (%d,%d) holds a node or relation id outside its table", i, j);
+    *dev_out = dev;
+    return LEGEND_OK;
+}
+
+int bucket_params(legend_ctx* c, int i, int j, const int32_t* dev_edges, int64_t m, BucketParams* bp) {
+    int si = c->part_slot[i], sj = c->part_slot[j];
+    if (si < 0 || sj < 0) return fail(LEGEND_E_NOT_RESIDENT, "bucket (%d,%d): partition %d is not resident", i, j, si < 0 ? i : j);
+    int rc = wait_slot(c, si);
+    if (rc) return rc;
+    rc = wait_slot(c, sj);
+    if (rc) return rc;
+    const int64_t half = c->Rp * c->d;
+    BucketParams p{};
+    p.edges = dev_edges;
+    p.m = m;
+    p.E_src = c->slot_mem[si]; p.S_src = c->slot_mem[si] + half;
+    p.E_dst = c->slot_mem[sj]; p.S_dst = c->slot_mem[sj] + half;
+    p.E_rel = c->E_rel; p.S_rel = c->S_rel;
+    p.rows_valid_src = (int32_t)rows_valid(c, i);
+    p.rows_valid_dst = (int32_t)rows_valid(c, j);
+    p.num_relations = c->cfg.num_relations;
+    p.dim = c->d;
+    p.score = c->cfg.score;
+    p.loss = c->cfg.loss;
+    p.same_part = i == j;
+    p.key_base_dst = i == j ? 0u : (uint32_t)c->Rp;
+    p.key_base_rel = i == j ? (uint32_t)c->Rp : (uint32_t)(2 * c->Rp);
+    p.num_degree_negs = c->cfg.num_degree_negs;
+    p.lr = c->cfg.lr;
+    p.eps = c->cfg.eps;
+    p.neg_weight = c->cfg.neg_weight >= 0.f ? c->cfg.neg_weight : 1.0f / (float)c->cfg.num_negs;
+    *bp = p;
+    return LEGEND_OK;
+}
+
+uint64_t batch_hash_prefix(const legend_ctx* c, int epoch, int i, int j, int64_t b) {
+    uint64_t h = c->cfg.seed;
+    h = hash_fold(h, (uint64_t)(int64_t)epoch);
+    h = hash_fold(h, (uint64_t)i);
+    h = hash_fold(h, (uint64_t)j);
+    h = hash_fold(h, (uint64_t)b);
+    return h;
+}
+
+// index side of one batch: negatives, keys, sort, segment heads
+int enqueue_index_side(legend_ctx* c, const BatchGeom& g, const BucketParams& bp, int* sorted_buf) {
+    {
+        ProfScope ps(c, KC_PREPARE);
+        HIP_TRY(c, launch_prepare(c->compute, g, bp, c->ws));
+    }
+    {
+        ProfScope ps(c, KC_SORT);
+        HIP_TRY(c, launch_sort(c->compute, g.n_occ, c->key_bits, c->ws, sorted_buf));
+        HIP_TRY(c, launch_segments(c->compute, g.n_occ, c->ws.keys[*sorted_buf], c->ws));
+    }
+    return LEGEND_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* legend_last_error(void) { return g_last_error.c_str(); }
+
+const char* legend_profile_name(int32_t k) { return (k >= 0 && k < KC_COUNT) ? kClassNames[k] : nullptr; }
+
+int legend_init_partitions(const legend_config* cfg, const float* init_node_emb, const float* init_rel_emb,
+                           legend_ctx** out) {
+    if (!cfg || !out) return fail(LEGEND_E_INVAL, "cfg and out must not be NULL");
+    *out = nullptr;
+    if (cfg->struct_size != sizeof(legend_config))
+        return fail(LEGEND_E_INVAL, "legend_config.struct_size is %u, library expects %zu", cfg->struct_size, sizeof(legend_config));
+    if (cfg->num_nodes < 1 || cfg->dim < 1 || cfg->num_partitions < 1 || cfg->num_partitions > cfg->num_nodes)
+        return fail(LEGEND_E_INVAL, "num_nodes, dim, num_partitions must be positive and num_partitions <= num_nodes");
+    if (cfg->dim > max_dim_supported())
+        return fail(LEGEND_E_INVAL, "dim %d is above the supported maximum %d", cfg->dim, max_dim_supported());
+    if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 1 || cfg->corrupt < 0 || cfg->corrupt > 2)
+        return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
+    if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC)
+        return fail(LEGEND_E_INVAL, "update_mode %d is not available", cfg->update_mode);
+    if (cfg->score == LEGEND_SCORE_COMPLEX && (cfg->dim & 1)) return fail(LEGEND_E_INVAL, "ComplEx needs an even dim");
+    if (cfg->score != LEGEND_SCORE_DOT && cfg->num_relations < 1)
+        return fail(LEGEND_E_INVAL, "this score function needs num_relations >= 1");
+    if (cfg->score != LEGEND_SCORE_DOT && !init_rel_emb) return fail(LEGEND_E_INVAL, "init_rel_emb must not be NULL for this score");
+    if (!init_node_emb) return fail(LEGEND_E_INVAL, "init_node_emb must not be NULL");
+    if (cfg->batch_size < 1 || cfg->chunk_size < 1 || cfg->num_negs < 1 || cfg->num_degree_negs < 0 ||
+        cfg->num_degree_negs > cfg->num_negs)
+        return fail(LEGEND_E_INVAL, "batch_size, chunk_size, num_negs must be >= 1 and 0 <= num_degree_negs <= num_negs");
+    if (cfg->buffer_capacity < 1 || cfg->buffer_capacity > cfg->num_partitions)
+        return fail(LEGEND_E_INVAL, "buffer_capacity must be in [1, num_partitions]");
+    if (!(cfg->lr > 0.f) || !(cfg->eps >= 0.f)) return fail(LEGEND_E_INVAL, "lr must be > 0 and eps >= 0");
+    const int64_t Rp = (cfg->num_nodes + cfg->num_partitions - 1) / cfg->num_partitions;
+    if ((int64_t)(cfg->num_partitions - 1) * Rp >= cfg->num_nodes)
+        return fail(LEGEND_E_INVAL, "num_partitions %d leaves an empty partition for %lld nodes", cfg->num_partitions, (long long)cfg->num_nodes);
+    if (2 * Rp + std::max(cfg->num_relations, 1) >= (int64_t)1 << 31) return fail(LEGEND_E_INVAL, "partition too large for 32-bit row keys");
+
+    if (hipSetDevice(cfg->device) != hipSuccess) return fail(LEGEND_E_HIP, "hipSetDevice(%d) failed", cfg->device);
+    legend_ctx* c = new (std::nothrow) legend_ctx();
+    if (!c) return fail(LEGEND_E_NOMEM, "context allocation failed");
+    c->cfg = *cfg;
+    c->V = cfg->num_nodes;
+    c->n = cfg->num_partitions;
+    c->cap = cfg->buffer_capacity;
+    c->d = cfg->dim;
+    c->Rp = Rp;
+    c->part_floats = (size_t)2 * Rp * c->d;
+    c->uses_rel = cfg->score != LEGEND_SCORE_DOT;
+    c->nrel_rows = std::max(cfg->num_relations, 1);
+    c->host_part.assign(c->n, nullptr);
+    c->slot_mem.assign(c->cap, nullptr);
+    c->slot_part.assign(c->cap, -1);
+    c->part_slot.assign(c->n, -1);
+    c->slot_ready.assign(c->cap, nullptr);
+    c->slot_pending.assign(c->cap, 0);
+
+#define INIT_TRY(expr)                                                                                   \
+    do {                                                                                                 \
+        hipError_t _e = (expr);                                                                          \
+        if (_e != hipSuccess) {                                                                          \
+            int _rc = fail(_e == hipErrorOutOfMemory ? LEGEND_E_NOMEM : LEGEND_E_HIP, "%s failed: %s", #expr, \
+                           hipGetErrorString(_e));                                                       \
+            (void)hipGetLastError();                                                                     \
+            free_ctx(c);                                                                                 \
+            return _rc;                                                                                  \
+        }                                                                                                \
+    } while (0)
+#define INIT_RC(expr)                  \
+    do {                               \
+        int _rc = (expr);              \
+        if (_rc) {                     \
+            free_ctx(c);               \
+            return _rc;                \
+        }                              \
+    } while (0)
+
+    if (cfg->compute_stream) c->compute = (hipStream_t)cfg->compute_stream;
+    else { INIT_TRY(hipStreamCreateWithFlags(&c->compute, hipStreamNonBlocking)); c->own_compute = true; }
+    if (cfg->copy_stream) c->copy = (hipStream_t)cfg->copy_stream;
+    else { INIT_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)); c->own_copy = true; }
+    INIT_TRY(hipEventCreateWithFlags(&c->ev_fence, hipEventDisableTiming));
+    INIT_TRY(hipEventCreate(&c->ev_t0));
+    INIT_TRY(hipEventCreate(&c->ev_t1));
+    INIT_TRY(hipEventRecord(c->ev_fence, c->compute));
+
+    // host tier: one pinned block [E_p | S_p] per partition (the paper's contiguous SSD layout)
+    const size_t half = (size_t)Rp * c->d;
+    for (int p = 0; p < c->n; ++p) {
+        void* q = nullptr;
+        INIT_TRY(hipHostMalloc(&q, c->part_floats * sizeof(float), hipHostMallocDefault));
+        c->host_part[p] = static_cast<float*>(q);
+        const int64_t lo = (int64_t)p * Rp;
+        const int64_t rows = std::max<int64_t>(0, std::min<int64_t>(Rp, c->V - lo));
+        std::memcpy(c->host_part[p], init_node_emb + lo * c->d, (size_t)rows * c->d * sizeof(float));
+        std::memset(c->host_part[p] + (size_t)rows * c->d, 0, (c->part_floats - (size_t)rows * c->d) * sizeof(float));
+        (void)half;
+    }
+    for (int s = 0; s < c->cap; ++s) {
+        INIT_RC(dev_alloc(c, &c->slot_mem[s], c->part_floats));
+        INIT_TRY(hipEventCreateWithFlags(&c->slot_ready[s], hipEventDisableTiming));
+    }
+    const size_t rel_floats = (size_t)c->nrel_rows * c->d;
+    INIT_RC(dev_alloc(c, &c->E_rel, rel_floats));
+    INIT_RC(dev_alloc(c, &c->S_rel, rel_floats));
+    INIT_TRY(hipMemset(c->S_rel, 0, rel_floats * sizeof(float)));
+    if (init_rel_emb) INIT_TRY(hipMemcpy(c->E_rel, init_rel_emb, rel_floats * sizeof(float), hipMemcpyHostToDevice));
+    else INIT_TRY(hipMemset(c->E_rel, 0, rel_floats * sizeof(float)));
+    INIT_RC(dev_alloc(c, &c->d_part_emb, (size_t)c->n));
+    INIT_RC(dev_alloc(c, &c->d_part_state, (size_t)c->n));
+    INIT_TRY(hipMemset(c->d_part_emb, 0, sizeof(float*) * c->n));
+    INIT_TRY(hipMemset(c->d_part_state, 0, sizeof(float*) * c->n));
+
+    // per-batch workspace sized for a full batch
+    c->gmax = make_geom(c, cfg->batch_size);
+    const int64_t occ = c->gmax.n_occ;
+    const int64_t nwg = (int64_t)c->gmax.sides * c->gmax.nchunks * c->gmax.T;
+    {
+        uint64_t maxkey = (uint64_t)2 * Rp + c->nrel_rows;
+        int bits = 1;
+        while (bits < 32 && (1ull << bits) <= maxkey) ++bits;
+        c->key_bits = bits;
+    }
+    const int64_t nblk = (occ + 2047) / 2048;
+    if (nblk * 256 > (int64_t)2048 * 2048) { free_ctx(c); return fail(LEGEND_E_INVAL, "batch too large for the sorter"); }
+    Workspace& w = c->ws;
+    w.cap_occ = occ;
+    w.cap_wg = nwg;
+    INIT_RC(dev_alloc(c, &w.neg_ids, (size_t)c->gmax.sides * c->gmax.nchunks * c->gmax.N));
+    for (int k = 0; k < 2; ++k) {
+        INIT_RC(dev_alloc(c, &w.keys[k], (size_t)occ));
+        INIT_RC(dev_alloc(c, &w.vals[k], (size_t)occ));
+    }
+    INIT_RC(dev_alloc(c, &w.ghist, (size_t)nblk * 256));
+    INIT_RC(dev_alloc(c, &w.scan_tmp, (size_t)std::max<int64_t>(nblk, (nblk * 256 + 2047) / 2048) + 2));
+    INIT_RC(dev_alloc(c, &w.uniq_keys, (size_t)occ));
+    INIT_RC(dev_alloc(c, &w.seg_start, (size_t)occ + 1));
+    INIT_RC(dev_alloc(c, &w.counters, 4));
+    INIT_RC(dev_alloc(c, &w.uniq_total, 1));
+    INIT_RC(dev_alloc(c, &w.grad, (size_t)occ * c->d));
+    INIT_RC(dev_alloc(c, &w.loss_partial, (size_t)nwg));
+    INIT_RC(dev_alloc(c, &w.loss_sum, 1));
+    INIT_TRY(hipMemset(w.counters, 0, 4 * sizeof(uint32_t)));
+    INIT_TRY(hipMemset(w.uniq_total, 0, sizeof(unsigned long long)));
+    INIT_TRY(hipMemset(w.loss_sum, 0, sizeof(double)));
+    INIT_TRY(hipDeviceSynchronize());
+#undef INIT_TRY
+#undef INIT_RC
+    *out = c;
+    return LEGEND_OK;
+}
+
+int legend_destroy(legend_ctx* ctx) {
+    free_ctx(ctx);
+    return LEGEND_OK;
+}
+
+int legend_sync(legend_ctx* c) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    return LEGEND_OK;
+}
+
+int legend_swap_partition(legend_ctx* c, int32_t evict, int32_t load) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    return do_swap(c, evict, load, true);
+}
+
+int legend_partition_slot(legend_ctx* c, int32_t part, int32_t* slot) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!slot || part < 0 || part >= c->n) return fail(LEGEND_E_INVAL, "bad partition id or NULL output");
+    *slot = c->part_slot[part];
+    return LEGEND_OK;
+}
+
+int legend_train_bucket(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
+                        int32_t epoch, const legend_prefetch* hint, legend_bucket_stats* stats) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (i < 0 || j < 0 || i >= c->n || j >= c->n) return fail(LEGEND_E_INVAL, "bucket (%d,%d) out of range", i, j);
+    if (m < 0 || (m > 0 && !edges)) return fail(LEGEND_E_INVAL, "edges must not be NULL when m > 0");
+    if (c->part_slot[i] < 0 || c->part_slot[j] < 0)
+        return fail(LEGEND_E_NOT_RESIDENT, "bucket (%d,%d): partition %d is not resident", i, j, c->part_slot[i] < 0 ? i : j);
+    if (hint) {
+        if (hint->evict >= c->n || hint->load >= c->n || hint->evict < -1 || hint->load < -1)
+            return fail(LEGEND_E_INVAL, "prefetch hint out of range");
+        if (hint->evict >= 0 && c->part_slot[hint->evict] < 0)
+            return fail(LEGEND_E_NOT_RESIDENT, "prefetch hint evicts partition %d which is not resident", hint->evict);
+        if (hint->load >= 0 && c->part_slot[hint->load] >= 0)
+            return fail(LEGEND_E_STATE, "prefetch hint loads partition %d which is already resident", hint->load);
+    }
+    const int32_t* dev_edges = nullptr;
+    BucketParams bp{};
+    rc = bucket_params(c, i, j, nullptr, m, &bp);
+    if (rc) return rc;
+    rc = stage_edges(c, i, j, edges, m, edges_mem, &dev_edges);
+    if (rc) return rc;
+    bp.edges = dev_edges;
+
+    // a swap that does not touch this bucket may run while the bucket trains
+    const bool overlap = hint && hint->evict != i && hint->evict != j;
+    if (overlap) {
+        rc = do_swap(c, hint->evict, hint->load, true);
+        if (rc) return rc;
+    }
+    HIP_TRY(c, hipMemsetAsync(c->ws.loss_sum, 0, sizeof(double), c->compute));
+    if (stats) HIP_TRY(c, hipEventRecord(c->ev_t0, c->compute));
+    const int B = c->cfg.batch_size;
+    const int64_t nb = (m + B - 1) / B;
+    for (int64_t b = 0; b < nb; ++b) {
+        const int P = (int)std::min<int64_t>(B, m - b * B);
+        BatchGeom g = make_geom(c, P);
+        bp.batch_lo = b * B;
+        bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, b);
+        int sorted = 0;
+        rc = enqueue_index_side(c, g, bp, &sorted);
+        if (rc) return rc;
+        {
+            ProfScope ps(c, KC_CHUNK);
+            HIP_TRY(c, launch_chunks(c->compute, g, bp, c->ws));
+        }
+        {
+            ProfScope ps(c, KC_MISC);
+            HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, c->ws));
+        }
+        {
+            ProfScope ps(c, KC_UPDATE);
+            HIP_TRY(c, launch_update(c->compute, g, bp, c->ws, c->ws.vals[sorted], (int32_t)c->Rp));
+        }
+        c->batches_done += 1;
+    }
+    if (stats) HIP_TRY(c, hipEventRecord(c->ev_t1, c->compute));
+    if (hint && !overlap) {
+        rc = do_swap(c, hint->evict, hint->load, true);
+        if (rc) return rc;
+    }
+    if (stats) {
+        double loss = 0.0;
+        HIP_TRY(c, hipMemcpyAsync(&loss, c->ws.loss_sum, sizeof loss, hipMemcpyDeviceToHost, c->compute));
+        HIP_TRY(c, hipStreamSynchronize(c->compute));
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
+        stats->loss_sum = loss;
+        stats->batches = nb;
+        stats->edges = m;
+        stats->ms = ms;
+    }
+    return LEGEND_OK;
+}
+
+int legend_debug_batch_indices(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
+                               int32_t epoch, int64_t batch, int32_t* neg_ids, int64_t neg_capacity, int64_t* touched,
+                               int64_t touched_capacity, int64_t* touched_count) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (i < 0 || j < 0 || i >= c->n || j >= c->n) return fail(LEGEND_E_INVAL, "bucket (%d,%d) out of range", i, j);
+    if (m <= 0 || !edges || !neg_ids || !touched || !touched_count) return fail(LEGEND_E_INVAL, "NULL argument or empty bucket");
+    const int B = c->cfg.batch_size;
+    const int64_t nb = (m + B - 1) / B;
+    if (batch < 0 || batch >= nb) return fail(LEGEND_E_INVAL, "batch %lld out of range (bucket has %lld)", (long long)batch, (long long)nb);
+    BucketParams bp{};
+    rc = bucket_params(c, i, j, nullptr, m, &bp);
+    if (rc) return rc;
+    const int32_t* dev_edges = nullptr;
+    rc = stage_edges(c, i, j, edges, m, edges_mem, &dev_edges);
+    if (rc) return rc;
+    bp.edges = dev_edges;
+    const int P = (int)std::min<int64_t>(B, m - batch * B);
+    BatchGeom g = make_geom(c, P);
+    const int64_t nneg = (int64_t)g.sides * g.nchunks * g.N;
+    if (neg_capacity < nneg) return fail(LEGEND_E_INVAL, "neg_capacity %lld < %lld", (long long)neg_capacity, (long long)nneg);
+    bp.batch_lo = batch * B;
+    bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, batch);
+    int sorted = 0;
+    // the unique-row statistic must not count this dry run
+    unsigned long long saved = 0;
+    HIP_TRY(c, hipMemcpyAsync(&saved, c->ws.uniq_total, sizeof saved, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    rc = enqueue_index_side(c, g, bp, &sorted);
+    if (rc) return rc;
+    uint32_t nu = 0;
+    HIP_TRY(c, hipMemcpyAsync(&nu, c->ws.counters, sizeof nu, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(neg_ids, c->ws.neg_ids, (size_t)nneg * sizeof(int32_t), hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(c->ws.uniq_total, &saved, sizeof saved, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    *touched_count = nu;
+    if ((int64_t)nu > touched_capacity) return fail(LEGEND_E_INVAL, "touched_capacity %lld < %u", (long long)touched_capacity, nu);
+    std::vector<uint32_t> keys(nu);
+    if (nu) HIP_TRY(c, hipMemcpy(keys.data(), c->ws.uniq_keys, (size_t)nu * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    for (uint32_t k = 0; k < nu; ++k) {
+        uint32_t key = keys[k];
+        int64_t t, row;
+        if (key >= bp.key_base_rel) { t = 2; row = key - bp.key_base_rel; }
+        else if (bp.key_base_dst > 0 && key >= bp.key_base_dst) { t = 1; row = key - bp.key_base_dst; }
+        else { t = 0; row = key; }
+        touched[k] = (t << 32) + row;
+    }
+    return LEGEND_OK;
+}
+
+int legend_score_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m, float* out) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (m < 0) return fail(LEGEND_E_INVAL, "m < 0");
+    if (m == 0) return LEGEND_OK;
+    if (!src || !dst || !out) return fail(LEGEND_E_INVAL, "NULL argument");
+    if (c->uses_rel && !rel) return fail(LEGEND_E_INVAL, "rel must not be NULL for this score");
+    for (int s = 0; s < c->cap; ++s) {
+        rc = wait_slot(c, s);
+        if (rc) return rc;
+    }
+    if (c->part_tables_dirty) {
+        rc = upload_part_tables(c);
+        if (rc) return rc;
+    }
+    const size_t b_ids = (size_t)m * sizeof(int64_t), b_rel = (size_t)m * sizeof(int32_t), b_out = (size_t)m * sizeof(float);
+    rc = ensure_io(c, 2 * b_ids + b_rel + b_out + 64);
+    if (rc) return rc;
+    char* base = static_cast<char*>(c->io_dev);
+    int64_t* d_src = reinterpret_cast<int64_t*>(base);
+    int64_t* d_dst = reinterpret_cast<int64_t*>(base + b_ids);
+    float* d_out = reinterpret_cast<float*>(base + 2 * b_ids);
+    int32_t* d_rel = reinterpret_cast<int32_t*>(base + 2 * b_ids + b_out);
+    uint32_t* flag = c->ws.counters + 1;
+    HIP_TRY(c, hipMemsetAsync(flag, 0, sizeof(uint32_t), c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d_src, src, b_ids, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d_dst, dst, b_ids, hipMemcpyHostToDevice, c->compute));
+    if (rel) HIP_TRY(c, hipMemcpyAsync(d_rel, rel, b_rel, hipMemcpyHostToDevice, c->compute));
+    {
+        ProfScope ps(c, KC_MISC);
+        HIP_TRY(c, launch_score(c->compute, d_src, rel ? d_rel : nullptr, d_dst, m, c->d_part_emb, (int32_t)c->Rp, c->n,
+                                c->V, c->E_rel, c->cfg.num_relations, c->d, c->cfg.score, d_out, flag));
+    }
+    uint32_t h = 0;
+    HIP_TRY(c, hipMemcpyAsync(&h, flag, sizeof h, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(out, d_out, b_out, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    if (h & 1u) return fail(LEGEND_E_RANGE, "a node or relation id is out of range");
+    if (h & 2u) return fail(LEGEND_E_NOT_RESIDENT, "an edge refers to a partition that is not resident");
+    return LEGEND_OK;
+}
+
+int legend_read_embeddings(legend_ctx* c, int32_t table, const int64_t* ids, int64_t m, float* out) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (table < 0 || table > 3) return fail(LEGEND_E_INVAL, "unknown table %d", table);
+    if (m < 0) return fail(LEGEND_E_INVAL, "m < 0");
+    if (m == 0) return LEGEND_OK;
+    if (!out) return fail(LEGEND_E_INVAL, "out must not be NULL");
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    for (int s = 0; s < c->cap; ++s) c->slot_pending[s] = 0;
+    if (c->part_tables_dirty) {
+        rc = upload_part_tables(c);
+        if (rc) return rc;
+    }
+    const int d = c->d;
+    const size_t rowb = (size_t)d * sizeof(float);
+    if (table >= LEGEND_TABLE_REL_EMB) {
+        const float* base = table == LEGEND_TABLE_REL_EMB ? c->E_rel : c->S_rel;
+        if (!ids) {
+            if (m > c->nrel_rows) return fail(LEGEND_E_RANGE, "m exceeds the relation table");
+            HIP_TRY(c, hipMemcpy(out, base, (size_t)m * rowb, hipMemcpyDeviceToHost));
+            return LEGEND_OK;
+        }
+        std::vector<float> all((size_t)c->nrel_rows * d);
+        HIP_TRY(c, hipMemcpy(all.data(), base, all.size() * sizeof(float), hipMemcpyDeviceToHost));
+        for (int64_t k = 0; k < m; ++k) {
+            if (ids[k] < 0 || ids[k] >= c->nrel_rows) return fail(LEGEND_E_RANGE, "relation id %lld out of range", (long long)ids[k]);
+            std::memcpy(out + k * d, all.data() + ids[k] * d, rowb);
+        }
+        return LEGEND_OK;
+    }
+    const size_t off = table == LEGEND_TABLE_NODE_STATE ? (size_t)c->Rp * d : 0;
+    if (!ids) {
+        if (m > c->V) return fail(LEGEND_E_RANGE, "m exceeds num_nodes");
+        for (int p = 0; p < c->n; ++p) {
+            int64_t lo = (int64_t)p * c->Rp;
+            if (lo >= m) break;
+            int64_t rows = std::min<int64_t>(c->Rp, m - lo);
+            int sl = c->part_slot[p];
+            if (sl >= 0) HIP_TRY(c, hipMemcpy(out + lo * d, c->slot_mem[sl] + off, (size_t)rows * rowb, hipMemcpyDeviceToHost));
+            else std::memcpy(out + lo * d, c->host_part[p] + off, (size_t)rows * rowb);
+        }
+        return LEGEND_OK;
+    }
+    for (int64_t k = 0; k < m; ++k)
+        if (ids[k] < 0 || ids[k] >= c->V) return fail(LEGEND_E_RANGE, "node id %lld out of range", (long long)ids[k]);
+    const size_t b_ids = (size_t)m * sizeof(int64_t), b_out = (size_t)m * rowb;
+    rc = ensure_io(c, b_ids + b_out + 64);
+    if (rc) return rc;
+    int64_t* d_ids = reinterpret_cast<int64_t*>(c->io_dev);
+    float* d_out = reinterpret_cast<float*>(static_cast<char*>(c->io_dev) + b_ids);
+    uint32_t* flag = c->ws.counters + 1;
+    HIP_TRY(c, hipMemsetAsync(flag, 0, sizeof(uint32_t), c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d_ids, ids, b_ids, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, launch_gather_rows(c->compute, d_ids, m, table == LEGEND_TABLE_NODE_EMB ? c->d_part_emb : c->d_part_state,
+                                  (int32_t)c->Rp, c->V, d, d_out, flag));
+    HIP_TRY(c, hipMemcpyAsync(out, d_out, b_out, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    for (int64_t k = 0; k < m; ++k) {
+        int p = (int)(ids[k] / c->Rp);
+        if (c->part_slot[p] < 0) std::memcpy(out + k * d, c->host_part[p] + off + (ids[k] % c->Rp) * d, rowb);
+    }
+    return LEGEND_OK;
+}
+
+int legend_profile_enable(legend_ctx* c, uint32_t mask) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    c->prof_mask = mask & ((1u << KC_COUNT) - 1u);
+    return LEGEND_OK;
+}
+
+int legend_profile_read(legend_ctx* c, double* ms, int64_t* launches, int32_t capacity) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!ms || !launches || capacity < KC_COUNT) return fail(LEGEND_E_INVAL, "need capacity >= %d", (int)KC_COUNT);
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    rc = prof_collect(c);
+    if (rc) return rc;
+    for (int k = 0; k < KC_COUNT; ++k) {
+        ms[k] = c->prof_ms[k];
+        launches[k] = c->prof_launches[k];
+        c->prof_ms[k] = 0.0;
+        c->prof_launches[k] = 0;
+    }
+    return LEGEND_OK;
+}
+
+int legend_batch_shape_of(legend_ctx* c, legend_batch_shape* out) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!out) return fail(LEGEND_E_INVAL, "NULL output");
+    out->occurrences = c->gmax.n_occ;
+    out->neg_rows = (int64_t)c->gmax.sides * c->gmax.nchunks * c->gmax.T * c->gmax.N;
+    out->workspace_bytes = c->gmax.n_occ * (int64_t)(c->d * 4 + 24);
+    out->key_bits = c->key_bits;
+    out->row_tiles = c->gmax.T;
+    return LEGEND_OK;
+}
+
+int legend_unique_rows_read(legend_ctx* c, int64_t* unique_rows, int64_t* batches) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!unique_rows || !batches) return fail(LEGEND_E_INVAL, "NULL output");
+    unsigned long long u = 0;
+    HIP_TRY(c, hipMemcpyAsync(&u, c->ws.uniq_total, sizeof u, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemsetAsync(c->ws.uniq_total, 0, sizeof u, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    *unique_rows = (int64_t)u;
+    *batches = c->batches_done;
+    c->batches_done = 0;
+    return LEGEND_OK;
+}
+
+}  // extern "C"
