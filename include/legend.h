@@ -163,6 +163,18 @@ int legend_train_bucket(legend_ctx* ctx, int32_t src_part, int32_t dst_part,
                         const legend_prefetch* hint, legend_bucket_stats* stats);
 
 /*
+ * The same for batches [batch_begin, batch_end) of the bucket only (batch_end < 0:
+ * up to the last batch).  Batch numbers, negatives and chunking are those of the
+ * whole bucket, so training a bucket in several consecutive ranges gives exactly
+ * the result of one legend_train_bucket call (Sec. 2.1: batches are independent
+ * units of the iteration).  stats, when given, covers the range.
+ */
+int legend_train_bucket_range(legend_ctx* ctx, int32_t src_part, int32_t dst_part,
+                              const int32_t* edges, int64_t m, int32_t edges_mem, int32_t epoch,
+                              int64_t batch_begin, int64_t batch_end,
+                              const legend_prefetch* hint, legend_bucket_stats* stats);
+
+/*
  * f(theta_s, theta_r, theta_d) of m triples with the current embeddings
  * (Sec. 2.1).  src/dst are GLOBAL node ids; rel may be NULL for Dot.  Every
  * partition referenced must be resident.  out: [m] fp32 (host).

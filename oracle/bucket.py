@@ -95,17 +95,12 @@ def adagrad_rows(theta: np.ndarray, state: np.ndarray, rows: np.ndarray, grad64:
     theta[rows] = theta[rows] - step
 
 
-def _coalesce(keys: List[np.ndarray], grads: List[np.ndarray], abs_out: Optional[list] = None):
+def _coalesce(keys: List[np.ndarray], grads: List[np.ndarray]):
     k = np.concatenate(keys)
     g = np.concatenate(grads, axis=0)
     uniq, inv = np.unique(k, return_inverse=True)
     acc = np.zeros((uniq.size, g.shape[1]), np.float64)
     np.add.at(acc, inv, g)
-    if abs_out is not None:
-        # sum of |terms| per element: lets a test tell which sums nearly cancel
-        mag = np.zeros_like(acc)
-        np.add.at(mag, inv, np.abs(g))
-        abs_out.append(mag)
     return uniq, acc
 
 
@@ -132,8 +127,10 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
     ti, tj = 0, (0 if i == j else 1)      # node table slot of each role
     node_keys = [[], []]
     node_grads = [[], []]
-    rel_keys, rel_grads = [], []
+    node_mags = [[], []]
+    rel_keys, rel_grads, rel_mags = [], [], []
     loss = 0.0
+    want_mags = record is not None
 
     # stage 5: batch computation, chunk by chunk, side by side
     nchunks = -(-p // cfg.chunk_size)
@@ -145,8 +142,13 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
             ids = neg[si, c]
             out = model.chunk_side(cfg.score, cfg.loss, cfg.w_neg, is_dst,
                                    s_all[sl], r_all[sl] if uses_rel else None, d_all[sl],
-                                   neg_table[ids].astype(np.float64))
+                                   neg_table[ids].astype(np.float64), with_magnitudes=want_mags)
             loss += float(out["loss"].sum())
+            if want_mags:
+                node_mags[ti].append(out["m_s"]); node_mags[tj].append(out["m_d"])
+                node_mags[neg_slot].append(out["m_neg"])
+                if uses_rel:
+                    rel_mags.append(out["m_r"])
             node_keys[ti].append(e[sl, 0].astype(np.int64)); node_grads[ti].append(out["g_s"])
             node_keys[tj].append(e[sl, 2].astype(np.int64)); node_grads[tj].append(out["g_d"])
             node_keys[neg_slot].append(ids); node_grads[neg_slot].append(out["g_neg"])
@@ -159,18 +161,16 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
     node = {}
     for slot in (0, 1):
         if node_keys[slot]:
-            box = [] if record is not None else None
-            node[slot] = _coalesce(node_keys[slot], node_grads[slot], box)
-            if box:
-                mags[slot] = box[0]
+            node[slot] = _coalesce(node_keys[slot], node_grads[slot])
+            if want_mags:
+                mags[slot] = _coalesce(node_keys[slot], node_mags[slot])[1]
     rel = None
     if uses_rel and rel_keys:
-        box = [] if record is not None else None
-        rel = _coalesce(rel_keys, rel_grads, box)
-        if box:
-            mags[2] = box[0]
+        rel = _coalesce(rel_keys, rel_grads)
+        if want_mags:
+            mags[2] = _coalesce(rel_keys, rel_mags)[1]
     if record is not None:
-        record["grad_abs_sums"] = mags
+        record["grad_magnitudes"] = mags
         record["grads"] = (node, rel)
         record["neg_ids"] = neg
         record["touched"] = negatives.touched_rows(cfg, i, j, e, neg)

@@ -97,12 +97,28 @@ def chain_from_v(score, g_v, r, d):
     return cmul(r, g_v), cmul_conj(g_v, d)
 
 
-def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs):
+def abs_compose(score, a, b):
+    """Sum of the absolute values of the products that form a (x) b (either form):
+    the magnitude against which the rounding error of that product is measured."""
+    if score == DOT:
+        return np.abs(a)
+    a, b = np.abs(a), np.abs(b)
+    if score == DISTMULT:
+        return a * b
+    ar, ai = _halves(a)
+    br, bi = _halves(b)
+    return np.concatenate([ar * br + ai * bi, ar * bi + ai * br], axis=-1)
+
+
+def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitudes=False):
     """Loss and gradients of one chunk for one corrupted side.
 
     s, r, d: [C, dim] float64 rows of the chunk's positive edges (r ignored for Dot).
     negs:    [N, dim] float64 rows of the shared negatives of this side.
-    Returns dict(loss [C], f [C], S [C,N], g_s, g_r (or None), g_d [C,dim], g_neg [N,dim])."""
+    Returns dict(loss [C], f [C], S [C,N], g_s, g_r (or None), g_d [C,dim], g_neg [N,dim]).
+    With with_magnitudes, also m_s, m_r, m_d, m_neg: for every gradient element the sum of
+    the absolute values of the elementary products it is made of (a forward error bound of
+    any floating-point evaluation of that element is a small multiple of roundoff times this)."""
     if side_is_dst:
         q = compose_u(score, s, r)       # meets destination-like rows
         other = d
@@ -121,4 +137,14 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs):
     else:
         g_d, g_r = chain_from_v(score, g_q, r, d)
         g_s = g_other
-    return dict(loss=l, f=f, S=S, W=W, g_s=g_s, g_r=g_r, g_d=g_d, g_neg=g_neg)
+    out = dict(loss=l, f=f, S=S, W=W, g_s=g_s, g_r=g_r, g_d=g_d, g_neg=g_neg)
+    if with_magnitudes:
+        x = s if side_is_dst else d
+        aq = abs_compose(score, x, r)
+        m_q = np.abs(a)[:, None] * np.abs(other) + np.abs(W) @ np.abs(negs)
+        m_other = np.abs(a)[:, None] * aq
+        m_x = m_q if score == DOT else abs_compose(score, r, m_q)
+        m_r = None if score == DOT else abs_compose(score, x, m_q)
+        out.update(m_neg=np.abs(W).T @ aq, m_r=m_r,
+                   m_s=m_x if side_is_dst else m_other, m_d=m_other if side_is_dst else m_x)
+    return out

@@ -27,7 +27,7 @@ TABLE_NODE_EMB, TABLE_NODE_STATE, TABLE_REL_EMB, TABLE_REL_STATE = 0, 1, 2, 3
 
 EXPORTS = [
     "legend_init_partitions", "legend_destroy", "legend_swap_partition", "legend_partition_slot",
-    "legend_train_bucket", "legend_score_edges", "legend_read_embeddings", "legend_debug_batch_indices",
+    "legend_train_bucket", "legend_train_bucket_range", "legend_score_edges", "legend_read_embeddings", "legend_debug_batch_indices",
     "legend_plan_order", "legend_sync", "legend_profile_enable", "legend_profile_read",
     "legend_profile_name", "legend_batch_shape_of", "legend_unique_rows_read", "legend_last_error",
 ]
@@ -75,6 +75,8 @@ def _load() -> C.CDLL:
     lib.legend_partition_slot.argtypes = [vp, i32, C.POINTER(i32)]
     lib.legend_train_bucket.argtypes = [vp, i32, i32, vp, i64, i32, i32, C.POINTER(legend_prefetch),
                                         C.POINTER(legend_bucket_stats)]
+    lib.legend_train_bucket_range.argtypes = [vp, i32, i32, vp, i64, i32, i32, i64, i64, C.POINTER(legend_prefetch),
+                                              C.POINTER(legend_bucket_stats)]
     lib.legend_score_edges.argtypes = [vp, vp, vp, vp, i64, vp]
     lib.legend_read_embeddings.argtypes = [vp, i32, vp, i64, vp]
     lib.legend_debug_batch_indices.argtypes = [vp, i32, i32, vp, i64, i32, i32, i64, vp, i64, vp, i64,
@@ -164,6 +166,13 @@ def legend_partition_slot(ctx, part: int) -> int:
 def legend_train_bucket(ctx, src_part: int, dst_part: int, edges, m: Optional[int] = None, edges_mem: int = MEM_HOST,
                         epoch: int = 0, hint: Optional[Sequence[int]] = None, want_stats: bool = True):
     """edges: int32 [m,3] numpy array (host) or an integer device address with m given."""
+    return legend_train_bucket_range(ctx, src_part, dst_part, edges, m, edges_mem, epoch, 0, -1, hint, want_stats,
+                                     _whole=True)
+
+
+def legend_train_bucket_range(ctx, src_part: int, dst_part: int, edges, m: Optional[int] = None,
+                              edges_mem: int = MEM_HOST, epoch: int = 0, batch_begin: int = 0, batch_end: int = -1,
+                              hint: Optional[Sequence[int]] = None, want_stats: bool = True, _whole: bool = False):
     if edges_mem == MEM_HOST:
         e = _as(edges, np.int32)
         if e.ndim != 2 or e.shape[1] != 3:
@@ -176,9 +185,13 @@ def legend_train_bucket(ctx, src_part: int, dst_part: int, edges, m: Optional[in
     if hint is not None:
         h = legend_prefetch(int(hint[0]), int(hint[1]))
     st = legend_bucket_stats() if want_stats else None
-    _check(_lib.legend_train_bucket(ctx, src_part, dst_part, eptr, m, edges_mem, epoch,
-                                    C.byref(h) if h is not None else None,
-                                    C.byref(st) if st is not None else None))
+    hp = C.byref(h) if h is not None else None
+    sp = C.byref(st) if st is not None else None
+    if _whole:
+        _check(_lib.legend_train_bucket(ctx, src_part, dst_part, eptr, m, edges_mem, epoch, hp, sp))
+    else:
+        _check(_lib.legend_train_bucket_range(ctx, src_part, dst_part, eptr, m, edges_mem, epoch, batch_begin,
+                                              batch_end, hp, sp))
     if st is None:
         return None
     return dict(loss_sum=st.loss_sum, batches=st.batches, edges=st.edges, ms=st.ms)

@@ -537,10 +537,23 @@ int legend_partition_slot(legend_ctx* c, int32_t part, int32_t* slot) {
 
 int legend_train_bucket(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
                         int32_t epoch, const legend_prefetch* hint, legend_bucket_stats* stats) {
+    return legend_train_bucket_range(c, i, j, edges, m, edges_mem, epoch, 0, -1, hint, stats);
+}
+
+int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
+                              int32_t epoch, int64_t batch_begin, int64_t batch_end, const legend_prefetch* hint,
+                              legend_bucket_stats* stats) {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (i < 0 || j < 0 || i >= c->n || j >= c->n) return fail(LEGEND_E_INVAL, "bucket (%d,%d) out of range", i, j);
     if (m < 0 || (m > 0 && !edges)) return fail(LEGEND_E_INVAL, "edges must not be NULL when m > 0");
+    {
+        const int64_t nb_all = (m + c->cfg.batch_size - 1) / c->cfg.batch_size;
+        if (batch_end < 0) batch_end = nb_all;
+        if (batch_begin < 0 || batch_begin > batch_end || batch_end > nb_all)
+            return fail(LEGEND_E_INVAL, "batch range [%lld, %lld) outside [0, %lld]", (long long)batch_begin,
+                        (long long)batch_end, (long long)nb_all);
+    }
     if (c->part_slot[i] < 0 || c->part_slot[j] < 0)
         return fail(LEGEND_E_NOT_RESIDENT, "bucket (%d,%d): partition %d is not resident", i, j, c->part_slot[i] < 0 ? i : j);
     if (hint) {
@@ -568,9 +581,11 @@ int legend_train_bucket(legend_ctx* c, int32_t i, int32_t j, const int32_t* edge
     HIP_TRY(c, hipMemsetAsync(c->ws.loss_sum, 0, sizeof(double), c->compute));
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_t0, c->compute));
     const int B = c->cfg.batch_size;
-    const int64_t nb = (m + B - 1) / B;
-    for (int64_t b = 0; b < nb; ++b) {
+    const int64_t nb = batch_end - batch_begin;
+    int64_t edges_done = 0;
+    for (int64_t b = batch_begin; b < batch_end; ++b) {
         const int P = (int)std::min<int64_t>(B, m - b * B);
+        edges_done += P;
         BatchGeom g = make_geom(c, P);
         bp.batch_lo = b * B;
         bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, b);
@@ -604,7 +619,7 @@ int legend_train_bucket(legend_ctx* c, int32_t i, int32_t j, const int32_t* edge
         HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
         stats->loss_sum = loss;
         stats->batches = nb;
-        stats->edges = m;
+        stats->edges = edges_done;
         stats->ms = ms;
     }
     return LEGEND_OK;

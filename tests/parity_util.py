@@ -8,71 +8,106 @@ from oracle import model
 from oracle.bucket import OracleConfig, Tables, train_batch
 
 # Tolerances (spec: scores 1e-5 relative in fp32, embeddings 1e-5 relative).
-#   embeddings:  |gpu - oracle| <= 1e-5 * max(|oracle|, lr)
-#   state:       |gpu - oracle| <= 3e-5 * |oracle| + 1e-30   (a sum of squares: twice the relative error)
-# An element whose batch gradient nearly cancels, |G| < 1e-4 * sum|terms| in some batch, is
-# ill-conditioned under any reordering of the fp32 arithmetic (Adagrad's first step is
-# lr * G / (|G| + eps), i.e. sign-like); such elements are excluded and counted, and their
-# share must stay below 2e-3.
+#
+#   embeddings:  |gpu - oracle| <= 1e-5 * max(|oracle|, lr) + forward_error
+#   state:       |gpu - oracle| <= 3e-5 * |oracle| + forward_error_state
+#
+# forward_error is the first-order effect, on the Adagrad step, of evaluating the batch
+# gradient G of an element in fp32 in any order: every gradient element is a sum of
+# products whose absolute values add up to M (computed by the oracle next to G), and an
+# fp32 evaluation of it (a length-d dot product behind every softmax weight, then sums over
+# the chunk and over the occurrences of the row) is off by at most KAPPA * M with KAPPA a
+# few dozen roundoffs.  The step theta -= lr * G / (sqrt(S) + eps) then moves by at most
+# lr * KAPPA * M / (sqrt(S) + eps), and the accumulator S += G*G by 2 |G| KAPPA M.  For an
+# element without cancellation (M ~ |G| ~ sqrt(S)) this adds 2e-7 to a tolerance of 1e-6;
+# it only matters where the gradient terms nearly cancel, which no fp32 order can reproduce.
 EMB_RTOL = 1e-5
 STATE_RTOL = 3e-5
-COND = 1e-4
-MAX_EXCLUDED = 2e-3
-
-
-def oracle_config(**kw) -> OracleConfig:
-    return OracleConfig(**kw)
+KAPPA = 32 * 2.0 ** -24        # ~1.9e-6
 
 
 class OracleRun:
-    """Trains batches with the oracle and tracks ill-conditioned elements per table."""
+    """Trains batches with the oracle and accumulates the forward-error allowance per element."""
 
     def __init__(self, cfg: OracleConfig, node: np.ndarray, rel):
         self.cfg = cfg
         self.tab = Tables(cfg, node, rel)
         rp, d = cfg.rows_per_partition, cfg.dim
-        self.bad_node = [np.zeros((rp, d), bool) for _ in range(cfg.num_partitions)]
-        self.bad_rel = np.zeros_like(self.tab.RE, dtype=bool)
-        self.touched_node = [np.zeros(rp, bool) for _ in range(cfg.num_partitions)]
+        n = cfg.num_partitions
+        self.fe_node = [np.zeros((rp, d)) for _ in range(n)]      # allowance on embeddings
+        self.fs_node = [np.zeros((rp, d)) for _ in range(n)]      # allowance on optimiser state
+        self.fe_rel = np.zeros(self.tab.RE.shape)
+        self.fs_rel = np.zeros(self.tab.RE.shape)
+        self.touched_node = [np.zeros(rp, bool) for _ in range(n)]
         self.touched_rel = np.zeros(self.tab.RE.shape[0], bool)
         self.loss = 0.0
 
-    def train_bucket(self, i, j, edges, epoch, max_batches=None):
+    def _allow(self, fe, fs, state, rows, g, mag):
+        lr, eps = self.cfg.lr, self.cfg.eps
+        s_new = state[rows].astype(np.float64)               # after the update
+        fe[rows] += lr * KAPPA * mag / (np.sqrt(s_new) + eps)
+        fs[rows] += 2.0 * np.abs(g) * KAPPA * mag
+
+    def set_state(self, node_E, node_S, rel_E=None, rel_S=None):
+        """Restart from given tables (global node order) and clear the allowances."""
+        cfg = self.cfg
+        rp = cfg.rows_per_partition
+        for p in range(cfg.num_partitions):
+            lo, hi = p * rp, min(cfg.num_nodes, (p + 1) * rp)
+            self.tab.E[p][: hi - lo] = node_E[lo:hi]
+            self.tab.S[p][: hi - lo] = node_S[lo:hi]
+            self.fe_node[p][:] = 0
+            self.fs_node[p][:] = 0
+            self.touched_node[p][:] = False
+        if rel_E is not None:
+            self.tab.RE[:] = rel_E
+            self.tab.RS[:] = rel_S
+        self.fe_rel[:] = 0
+        self.fs_rel[:] = 0
+        self.touched_rel[:] = False
+
+    def train_bucket(self, i, j, edges, epoch, max_batches=None, batch_begin=0):
         cfg = self.cfg
         nb = -(-edges.shape[0] // cfg.batch_size)
         if max_batches is not None:
-            nb = min(nb, max_batches)
+            nb = min(nb, batch_begin + max_batches)
         loss = 0.0
-        for b in range(nb):
+        for b in range(batch_begin, nb):
             rec = {}
             loss += train_batch(self.tab, i, j, edges, b, epoch, record=rec)
             node, rel = rec["grads"]
-            mags = rec["grad_abs_sums"]
+            mags = rec["grad_magnitudes"]
             for slot, part in ((0, i), (1, j)):
                 if slot in node:
                     rows, g = node[slot]
-                    self.bad_node[part][rows] |= np.abs(g) < COND * mags[slot]
+                    self._allow(self.fe_node[part], self.fs_node[part], self.tab.S[part], rows, g, mags[slot])
                     self.touched_node[part][rows] = True
             if rel is not None:
                 rows, g = rel
-                self.bad_rel[rows] |= np.abs(g) < COND * mags[2]
+                self._allow(self.fe_rel, self.fs_rel, self.tab.RS, rows, g, mags[2])
                 self.touched_rel[rows] = True
         self.loss += loss
         return loss
 
+    def node_allowance(self, which):
+        src = self.fe_node if which == 0 else self.fs_node
+        return np.concatenate(src, 0)[: self.cfg.num_nodes]
 
-def compare_table(name, got, want, bad, rtol, floor, atol=0.0):
-    """Element-wise comparison; returns the excluded fraction."""
+
+def compare_table(name, got, want, allowance, rtol, floor):
+    """Element-wise comparison: |got - want| <= rtol * max(|want|, floor) + allowance."""
     assert got.shape == want.shape, (name, got.shape, want.shape)
     got64, want64 = got.astype(np.float64), want.astype(np.float64)
-    tol = rtol * np.maximum(np.abs(want64), floor) + atol
+    tol = rtol * np.maximum(np.abs(want64), floor) + allowance
     err = np.abs(got64 - want64)
-    viol = (err > tol) & ~bad
+    viol = err > tol
     if viol.any():
         idx = np.argwhere(viol)[:5]
-        lines = [f"{tuple(k)}: gpu={got64[tuple(k)]!r} oracle={want64[tuple(k)]!r}" for k in idx]
+        lines = [f"{tuple(int(x) for x in k)}: gpu={got64[tuple(k)]!r} oracle={want64[tuple(k)]!r} tol={tol[tuple(k)]:.3e}"
+                 for k in idx]
         raise AssertionError(f"{name}: {int(viol.sum())} of {viol.size} elements outside tolerance; first: " + "; ".join(lines))
-    return float(bad.mean())
+    # how much of the comparison ran at the plain north-star tolerance
+    return float((allowance > rtol * np.maximum(np.abs(want64), floor)).mean())
 
 
 def check_scores(got, want, s64, r64, d64, score):
