@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the bucket-training hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--no-cpu-baseline]
+
+A step is one batch (B positive edges) through the whole path: negative sampling, gather,
+scores, loss, backward, sparse Adagrad.  Edges and partitions are resident in HBM before
+the timed region.  Prints one JSON line.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--scale", type=int, default=1, help="divide nodes and edges of the workload (for quick checks)")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-batches", type=int, default=1)
+    ap.add_argument("--profile-only", action="store_true", help="skip the CPU baseline and the per-kernel pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2505_09258_amd import binding as L
+    from workloads import graphs
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 2
+    w = graphs.WORKLOADS[args.workload]
+    if args.scale > 1:
+        w = graphs.scaled(w, args.scale)
+    if w.dim > 128:
+        log(f"bench.py: workload {w.name} needs dim {w.dim}, not supported by the chunk kernel yet")
+        return 2
+
+    t0 = time.time()
+    src, rel_ids, dst = graphs.generate_edges(w, args.seed)
+    buckets = graphs.bucket_edges(w, src, rel_ids, dst)
+    del src, rel_ids, dst
+    node, rel = graphs.init_tables(w, args.seed)
+    log(f"[bench] generated {w.name}: {w.num_nodes} nodes, {w.num_edges} edges, {len(buckets)} buckets in {time.time() - t0:.1f}s")
+
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    n = w.num_partitions
+    capacity = n if 2 * w.num_nodes * w.dim * 4 < 64e9 else 3
+    cfg = L.make_config(num_nodes=w.num_nodes, dim=w.dim, num_partitions=n, buffer_capacity=capacity,
+                        num_relations=w.num_relations, score=w.score, loss=w.loss, corrupt=w.corrupt,
+                        batch_size=w.batch_size, chunk_size=w.chunk_size, num_negs=w.num_negs,
+                        num_degree_negs=w.num_degree_negs, lr=w.lr, eps=w.eps, seed=args.seed,
+                        compute_stream=stream.cuda_stream)
+    uses_rel = w.score != graphs.SCORE_DOT
+    ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
+    log(f"[bench] context ready after {time.time() - t0:.1f}s")
+    B = w.batch_size
+    K, W = args.steps, args.warmup
+
+    # bucket order of the paper's planner; all partitions of the chosen buckets resident
+    states, order, begin, overlap = L.legend_plan_order(n)
+    if capacity == n:
+        for p in range(n):
+            L.legend_swap_partition(ctx, -1, p)
+        seq = [tuple(map(int, b)) for b in order]
+    else:
+        for p in states[0]:
+            L.legend_swap_partition(ctx, -1, int(p))
+        seq = [tuple(map(int, b)) for b in order[begin[0]:begin[1]]]
+
+    # work list: (bucket, first batch, last batch) covering W then K full batches
+    work, need, first_timed = [], W + K, None
+    dev_edges = {}
+    for (i, j) in seq:
+        e = buckets[(i, j)]
+        full = e.shape[0] // B
+        if full == 0:
+            continue
+        dev_edges[(i, j)] = torch.from_numpy(e).cuda()
+        b = 0
+        while b < full and need > 0:
+            if need > K:                      # still in warm-up
+                take = min(full - b, need - K)
+            else:
+                take = min(full - b, need)
+                if first_timed is None:
+                    first_timed = len(work)
+            work.append((i, j, b, b + take))
+            b += take
+            need -= take
+        if need == 0:
+            break
+    if need > 0:
+        log(f"[bench] workload has too few full batches for {W}+{K} steps")
+        return 2
+    torch.cuda.synchronize()
+
+    def run(items):
+        for (i, j, b0, b1) in items:
+            t = dev_edges[(i, j)]
+            L.legend_train_bucket_range(ctx, i, j, t.data_ptr(), m=t.shape[0], edges_mem=L.MEM_DEVICE, epoch=0,
+                                        batch_begin=b0, batch_end=b1, want_stats=False)
+
+    names = []
+    k = 0
+    while L.legend_profile_name(k) is not None:
+        names.append(L.legend_profile_name(k))
+        k += 1
+    chunk_bit = 1 << names.index("chunk")
+
+    run(work[:first_timed])
+    L.legend_sync(ctx)
+    L.legend_unique_rows_read(ctx)
+    L.legend_profile_enable(ctx, chunk_bit)          # HIP events around the dominant kernel only
+    L.legend_profile_read(ctx)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_start = time.perf_counter()
+    ev0.record(stream)
+    run(work[first_timed:])
+    ev1.record(stream)
+    L.legend_sync(ctx)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    dev_ms = ev0.elapsed_time(ev1)
+    prof = L.legend_profile_read(ctx)
+    uniq, nbatches = L.legend_unique_rows_read(ctx)
+    assert nbatches == K, (nbatches, K)
+    edges_per_s = K * B / wall
+    log(f"[bench] {K} steps: wall {wall * 1e3:.1f} ms, device {dev_ms:.1f} ms, {edges_per_s:.3e} edges/s")
+
+    # ---- roofline of the dominant kernel (the fused chunk kernel): three contractions per side
+    sides = w.sides
+    P, N, d = B, w.num_negs, w.dim
+    flops_per_launch = sides * 3 * 2 * P * N * d
+    chunk_ms = prof["chunk"]["ms"] / max(prof["chunk"]["launches"], 1)
+    achieved_tflops = flops_per_launch / (chunk_ms * 1e-3) / 1e12
+    shape = L.legend_batch_shape_of(ctx)
+    Q = sides * (-(-P // w.chunk_size)) * N
+    u_b = uniq / max(nbatches, 1)
+    alg_bytes = 12 * P + 4 * Q + 4 * d * (2 * P + Q) + 16 * d * u_b
+    roofline = {"kernel": "k_chunk (gather + scores + loss + backward, fp32 MFMA)", "bound": "mfma",
+                "achieved": round(achieved_tflops, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": flops_per_launch, "avg_launch_ms": round(chunk_ms, 4)}
+
+    # ---- second pass with every kernel class event-timed (separate from the timed region) ----
+    kernels = {}
+    if not args.profile_only:
+        extra = []
+        need2 = min(K, 40)
+        for (i, j, b0, b1) in work[first_timed:]:
+            take = min(need2, b1 - b0)
+            if take <= 0:
+                break
+            extra.append((i, j, b0, b0 + take))
+            need2 -= take
+        L.legend_profile_enable(ctx, (1 << len(names)) - 1)
+        L.legend_profile_read(ctx)
+        L.legend_unique_rows_read(ctx)
+        run(extra)
+        L.legend_sync(ctx)
+        prof2 = L.legend_profile_read(ctx)
+        uniq2, nb2 = L.legend_unique_rows_read(ctx)
+        L.legend_profile_enable(ctx, 0)
+        ub2 = uniq2 / max(nb2, 1)
+        for name in names:
+            if prof2[name]["launches"]:
+                kernels[name] = {"ms_per_batch": round(prof2[name]["ms"] / nb2, 4)}
+        if "update" in kernels:
+            upd_bytes = 16 * d * ub2                       # read E,S and write E,S of every unique row
+            stage_bytes = 4 * d * shape["occurrences"]     # staged gradient rows re-read (overhead, not algorithmic)
+            ms = kernels["update"]["ms_per_batch"]
+            kernels["update"].update({"bound": "hbm", "algorithmic_GBs": round(upd_bytes / ms / 1e6, 1),
+                                      "with_staging_GBs": round((upd_bytes + stage_bytes) / ms / 1e6, 1),
+                                      "peak_GBs": HBM_PEAK_GBS, "unique_rows_per_batch": round(ub2)})
+        if "chunk" in kernels:
+            gather_bytes = 4 * d * (2 * P + Q)
+            ms = kernels["chunk"]["ms_per_batch"]
+            kernels["chunk"].update({"bound": "mfma", "TFLOPs": round(flops_per_launch / ms / 1e9, 2),
+                                     "gather_GBs": round(gather_bytes / ms / 1e6, 1)})
+
+    out = {
+        "metric": "edges/sec trained (1 GPU)", "value": round(edges_per_s, 1), "unit": "edges/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(wall * 1e3 / K, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
+                               f"{n} partitions, B={B}, C={w.chunk_size}, N={w.num_negs} ({w.num_degree_negs} degree-weighted), "
+                               f"sides={sides}, score={['dot', 'distmult', 'complex'][w.score]}",
+                   "update_mode": "deterministic", "resident_partitions": capacity},
+        "device_ms_per_step": round(dev_ms / K, 4),
+        "algorithmic_bytes_per_step": int(alg_bytes), "unique_rows_per_step": round(u_b),
+        "hbm_GBs_whole_step": round(alg_bytes / (wall / K) / 1e9, 1),
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    # ---- the oracle, as it stands, on this machine's host cores (a baseline, not the target) ------
+    if not args.no_cpu_baseline and not args.profile_only:
+        from oracle.bucket import OracleConfig, Tables, train_batch
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        ocfg = OracleConfig.from_workload(w, seed=args.seed)
+        tab = Tables(ocfg, node, rel if uses_rel else None)
+        (i, j, b0, _) = work[first_timed]
+        e = buckets[(i, j)]
+        t1 = time.perf_counter()
+        nb = 0
+        while nb < args.cpu_batches or (time.perf_counter() - t1 < 10 and nb < 8):
+            train_batch(tab, i, j, e, b0 + nb, 0)
+            nb += 1
+        cpu_s = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": round(nb * B / cpu_s, 1), "unit": "edges/s", "cores": cores, "kind": "oracle",
+                               "sample": f"{nb} batch(es) of {B} edges of bucket ({i},{j}) of the same workload, "
+                                         f"numpy float64, {cpu_s:.1f} s"}
+    L.legend_destroy(ctx)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -22,7 +22,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kChunkThreads = 256;
 constexpr int kRowTile = 64;    // positives per workgroup (padded)
 constexpr int kNegTile = 64;    // negatives per LDS tile
-constexpr int kWS = kNegTile + 1;
+constexpr int kWS = kNegTile + 4;   // row stride of the W tile: a multiple of 4 that is 4 mod 8
+constexpr int kIdsLds = 1024;   // negative ids of a chunk kept in LDS (more than that: read from global)
 
 int row_tiles_for(int chunk_size) { return (chunk_size + kRowTile - 1) / kRowTile; }
 int rows_per_tile_for(int chunk_size) {
@@ -30,6 +31,11 @@ int rows_per_tile_for(int chunk_size) {
     return (chunk_size + t - 1) / t;
 }
 int max_dim_supported() { return 128; }
+
+// LDS row stride of the Q and negative tiles: dim rounded up to 8, plus 4.  It is a multiple
+// of 4 (rows stay 16-byte aligned for 128-bit LDS accesses) and 4 mod 8 (32 rows read at the
+// same column fall into distinct bank groups).
+__host__ __device__ inline int chunk_row_stride(int d) { return ((d + 7) & ~7) + 4; }
 
 __device__ inline f32x16 mfma32(float a, float b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
@@ -41,6 +47,14 @@ __device__ inline float softplusf(float x) {
 }
 __device__ inline float sigmoidf(float x) { return 1.f / (1.f + expf(-x)); }
 
+__device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+
+// MFMA operand mapping used everywhere below: the contraction index runs in groups of 8;
+// in a group the lanes 0-31 (kk = 0) supply k = 8g + s and lanes 32-63 (kk = 1) supply
+// k = 8g + 4 + s to the s-th of four consecutive 32x32x2 MFMAs (s = 0..3).  Both operands
+// use the same mapping, so the sum over k is complete and every lane can fetch its four
+// values of a row-major operand with one 128-bit LDS read.
+
 // NB: number of 32-wide column blocks covering the embedding dimension (dim <= 32 * NB).
 template <int NB, int SCORE, int LOSS>
 __global__ void __launch_bounds__(kChunkThreads)
@@ -51,16 +65,18 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     constexpr int STEPS = 16 / RPS;         // each wave gathers 16 of the 64 tile rows
     constexpr int NBW = (2 * NB + 3) / 4;   // 32x32 output blocks per wave in the gradient products
 
-    extern __shared__ float smem[];
+    extern __shared__ __align__(16) float smem[];
     const int d = bp.dim;
-    const int QS = (d + 1) | 1;             // odd LDS row stride >= dim rounded up to even
-    const int KD = (d + 1) & ~1;
+    const int QS = chunk_row_stride(d);
+    const int G_d = (d + 7) >> 3;           // contraction groups over the embedding dimension
     const int tile_floats = kRowTile * QS + 32 * NB;
     float* Qs = smem;                       // [64][QS]  Q rows of this workgroup
     float* Ns = Qs + tile_floats;           // [64][QS]  current negative tile (later: G_Q)
-    float* Ws = Ns + tile_floats;           // [64][65]  S, then W, of the current tile
+    float* Ws = Ns + tile_floats;           // [64][68]  W of the current tile (also reduction scratch)
     float* pos_s = Ws + kRowTile * kWS;     // [64]
-    float* rowloss_s = pos_s + kRowTile;    // [64]
+    float* lse_s = pos_s + kRowTile;        // [64]
+    float* rowloss_s = lse_s + kRowTile;    // [64]
+    int32_t* ids_s = reinterpret_cast<int32_t*>(rowloss_s + kRowTile);   // [kIdsLds]
 
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -90,7 +106,8 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     const int64_t neg_base = side_base + (int64_t)g.roles * g.P + ((int64_t)c * g.T + t) * N;
     const bool vec4 = (d & 3) == 0;
 
-    // ---- zero the pad columns [d, QS) of both row tiles (never written again) -------------
+    // ---- negative ids of the chunk, and zero pad columns [d, QS) of both row tiles -----------
+    for (int k = tid; k < min(N, kIdsLds); k += kChunkThreads) ids_s[k] = my_negs[k];
     for (int idx = tid; idx < kRowTile * (QS - d); idx += kChunkThreads) {
         int r = idx / (QS - d), cc = d + idx % (QS - d);
         Qs[r * QS + cc] = 0.f;
@@ -131,6 +148,7 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
         partial += wave_shfl_xor(partial, 2);
         if (ppart == 0) pos_s[prow] = partial;
     }
+    __syncthreads();                          // ids_s, Qs, pos_s complete
 
     // ---- negative tile gather: registers first, LDS after the previous tile is done -------
     float4 pf[STEPS];
@@ -144,7 +162,8 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             int c0 = gcol4 * 4;
             if (k < N && c0 < d) {
-                const float* p = En + (int64_t)my_negs[k] * d + c0;
+                const int32_t id = k < kIdsLds ? ids_s[k] : my_negs[k];
+                const float* p = En + (int64_t)id * d + c0;
                 if (vec4) {
                     v = *reinterpret_cast<const float4*>(p);
                 } else {
@@ -163,60 +182,109 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             int rt = w * 16 + s * RPS + grow_lane;
             int c0 = gcol4 * 4;
             float* dst = Ns + rt * QS + c0;
-            if (c0 < d) dst[0] = pf[s].x;
-            if (c0 + 1 < d) dst[1] = pf[s].y;
-            if (c0 + 2 < d) dst[2] = pf[s].z;
-            if (c0 + 3 < d) dst[3] = pf[s].w;
+            if (vec4) {
+                if (c0 < d) *reinterpret_cast<float4*>(dst) = pf[s];
+            } else {
+                if (c0 < d) dst[0] = pf[s].x;
+                if (c0 + 1 < d) dst[1] = pf[s].y;
+                if (c0 + 2 < d) dst[2] = pf[s].z;
+                if (c0 + 3 < d) dst[3] = pf[s].w;
+            }
         }
     };
 
-    const int rbA = w & 1, cbA = w >> 1;      // this wave's 32x32 block of the score tile
-    auto scores_to_lds = [&]() {
+    // ---- S block of this wave: rows rbA*32.., negatives cbA*32.. of the current tile --------
+    const int rbA = w & 1, cbA = w >> 1;
+    auto score_block = [&]() -> f32x16 {
         f32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        const float* qa = Qs + (rbA * 32 + i32) * QS + kk;
-        const float* nb = Ns + (cbA * 32 + i32) * QS + kk;
-        for (int k0 = 0; k0 < KD; k0 += 2) acc = mfma32(qa[k0], nb[k0], acc);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            int row = rbA * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
-            Ws[row * kWS + cbA * 32 + i32] = acc[v];
+        const float* qa = Qs + (rbA * 32 + i32) * QS + 4 * kk;
+        const float* nb = Ns + (cbA * 32 + i32) * QS + 4 * kk;
+        float4 a = lds4(qa), b = lds4(nb);
+        for (int gi = 0; gi < G_d; ++gi) {
+            float4 an = a, bn = b;
+            if (gi + 1 < G_d) {
+                an = lds4(qa + 8 * (gi + 1));
+                bn = lds4(nb + 8 * (gi + 1));
+            }
+            acc = mfma32(a.x, b.x, acc);
+            acc = mfma32(a.y, b.y, acc);
+            acc = mfma32(a.z, b.z, acc);
+            acc = mfma32(a.w, b.w, acc);
+            a = an;
+            b = bn;
         }
+        return acc;
     };
+    // row of accumulator element v of a 32x32 block with row block rb
+    auto acc_row = [&](int rb, int v) { return rb * 32 + 8 * (v >> 2) + 4 * kk + (v & 3); };
 
     const int ntiles = (N + kNegTile - 1) / kNegTile;
-    const int srow = tid >> 2;                // softmax bookkeeping: 4 threads per row
+    const int srow = tid >> 2;                // 4 threads per row for the row-wise reductions
     const int sq = tid & 3;
-    float lse = 0.f;
-    float neg_loss = 0.f;                     // logistic: sum of weighted softplus terms
+    float lse_r[16];                          // log-sum-exp of the 16 rows this lane sees in a score block
+#pragma unroll
+    for (int v = 0; v < 16; ++v) lse_r[v] = 0.f;
+    float neg_loss = 0.f;                     // logistic: this lane's share of the weighted softplus terms
 
     gather_issue(0);
-    __syncthreads();                          // Qs, pos_s complete
 
     if (LOSS == LEGEND_LOSS_SOFTMAX) {
-        // ---- sweep 1: running max and sum of exp per row ------------------------------------
-        float m_run = -INFINITY, l_run = 0.f;
+        // ---- sweep 1: running max and sum of exp, per lane over its own columns -------------
+        float m_l[16], s_l[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { m_l[v] = -INFINITY; s_l[v] = 0.f; }
         for (int tile = 0; tile < ntiles; ++tile) {
             const int n0 = tile * kNegTile;
             gather_commit();
             __syncthreads();
             gather_issue(tile + 1 < ntiles ? n0 + kNegTile : 0);   // next tile, or first tile of sweep 2
-            scores_to_lds();
+            f32x16 acc = score_block();
+            if (n0 + cbA * 32 + i32 < N) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float sv = acc[v];
+                    float mn = fmaxf(m_l[v], sv);
+                    s_l[v] = s_l[v] * expf(m_l[v] - mn) + expf(sv - mn);
+                    m_l[v] = mn;
+                }
+            }
             __syncthreads();
+        }
+        // combine the 64 per-lane partials of every row (two waves x 32 lanes): max, then sum
+        const int pcol = cbA * 32 + i32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Ws[acc_row(rbA, v) * kWS + pcol] = m_l[v];
+        __syncthreads();
+        {
             const float* wr = Ws + srow * kWS + sq * 16;
-            const int ncol = min(16, N - n0 - sq * 16);            // valid columns of my 16
-            float tmax = -INFINITY;
-            for (int j = 0; j < ncol; ++j) tmax = fmaxf(tmax, wr[j]);
-            tmax = fmaxf(tmax, wave_shfl_xor(tmax, 1));
-            tmax = fmaxf(tmax, wave_shfl_xor(tmax, 2));
-            float m_new = fmaxf(m_run, tmax);
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, wr[j]);
+            mx = fmaxf(mx, wave_shfl_xor(mx, 1));
+            mx = fmaxf(mx, wave_shfl_xor(mx, 2));
+            if (sq == 0) lse_s[srow] = mx;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = acc_row(rbA, v);
+            Ws[r * kWS + pcol] = s_l[v] * expf(m_l[v] - lse_s[r]);   // a lane without columns has s_l = 0
+        }
+        __syncthreads();
+        {
+            const float* wr = Ws + srow * kWS + sq * 16;
             float sum = 0.f;
-            for (int j = 0; j < ncol; ++j) sum += expf(wr[j] - m_new);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sum += wr[j];
             sum += wave_shfl_xor(sum, 1);
             sum += wave_shfl_xor(sum, 2);
-            l_run = l_run * expf(m_run - m_new) + sum;
-            m_run = m_new;
+            const float mx = lse_s[srow];
+            __syncthreads();                  // every thread has read the row maxima
+            if (sq == 0) lse_s[srow] = mx + logf(sum);
         }
-        lse = m_run + logf(l_run);
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) lse_r[v] = lse_s[acc_row(rbA, v)];
     }
 
     // ---- sweep 2: gradients ----------------------------------------------------------------
@@ -226,7 +294,9 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
 #pragma unroll
         for (int v = 0; v < 16; ++v) accB[j][v] = 0.f;
     const int rbG = w & 1;
-    const int rows2 = (nrows + 1) & ~1;
+    const int cb0 = w >> 1;                   // first column block of this wave; the j-th is cb0 + 2j
+    const bool active = cb0 < NB;             // NB = 1: only two waves have an output block
+    const int G_rows = (nrows + 7) >> 3;
     const float wneg = bp.neg_weight;
 
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -234,67 +304,81 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
         gather_commit();
         __syncthreads();
         if (tile + 1 < ntiles) gather_issue(n0 + kNegTile);
-        scores_to_lds();
-        __syncthreads();
         {
-            float* wr = Ws + srow * kWS + sq * 16;
-            const int ncol = srow < nrows ? min(16, N - n0 - sq * 16) : 0;
+            f32x16 acc = score_block();
+            const bool col_ok = n0 + cbA * 32 + i32 < N;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                float s = wr[j];
+            for (int v = 0; v < 16; ++v) {
+                const int r = acc_row(rbA, v);
                 float wv = 0.f;
-                if (j < ncol) {
+                if (col_ok && r < nrows) {
                     if (LOSS == LEGEND_LOSS_SOFTMAX) {
-                        wv = expf(s - lse);
+                        wv = expf(acc[v] - lse_r[v]);
                     } else {
-                        wv = wneg * sigmoidf(s);
-                        neg_loss += wneg * softplusf(s);
+                        wv = wneg * sigmoidf(acc[v]);
+                        neg_loss += wneg * softplusf(acc[v]);
                     }
                 }
-                wr[j] = wv;
+                Ws[r * kWS + cbA * 32 + i32] = wv;
             }
         }
         __syncthreads();
-        const int kmax = min(kNegTile, (N - n0 + 1) & ~1);
-        // G_Q += W * Neg
-        {
-            const float* wa = Ws + (rbG * 32 + i32) * kWS + kk;
-            const float* nb = Ns + kk * QS + i32;
-            for (int k0 = 0; k0 < kmax; k0 += 2) {
-                float a = wa[k0];
+        if (active) {
+            const int G_n = (min(kNegTile, N - n0) + 7) >> 3;
+            // G_Q += W * Neg : contraction over the negatives of the tile
+            {
+                const float* wa = Ws + (rbG * 32 + i32) * kWS + 4 * kk;
+                const float* nb = Ns + (4 * kk) * QS + cb0 * 32 + i32;
+                for (int gi = 0; gi < G_n; ++gi) {
+                    const float4 a = lds4(wa + 8 * gi);
+                    const float* nbg = nb + 8 * gi * QS;
+                    float b[NBW][4];
 #pragma unroll
-                for (int j = 0; j < NBW; ++j) {
-                    int cb = (w >> 1) + 2 * j;
-                    if (cb < NB) accB[j] = mfma32(a, nb[k0 * QS + cb * 32], accB[j]);
+                    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) b[j][s] = nbg[s * QS + 64 * j];
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j) {
+                        accB[j] = mfma32(a.x, b[j][0], accB[j]);
+                        accB[j] = mfma32(a.y, b[j][1], accB[j]);
+                        accB[j] = mfma32(a.z, b[j][2], accB[j]);
+                        accB[j] = mfma32(a.w, b[j][3], accB[j]);
+                    }
                 }
             }
-        }
-        // G_neg = W^T * Q, written straight to the staged gradient rows
-        {
-            f32x16 accC[NBW];
+            // G_neg = W^T * Q : contraction over the positives, written to the staged gradient rows
+            {
+                f32x16 accC[NBW];
 #pragma unroll
-            for (int j = 0; j < NBW; ++j)
+                for (int j = 0; j < NBW; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) accC[j][v] = 0.f;
-            const float* wa = Ws + kk * kWS + rbG * 32 + i32;
-            const float* qb = Qs + kk * QS + i32;
-            for (int k0 = 0; k0 < rows2; k0 += 2) {
-                float a = wa[k0 * kWS];
+                    for (int v = 0; v < 16; ++v) accC[j][v] = 0.f;
+                const float* wa = Ws + (4 * kk) * kWS + rbG * 32 + i32;
+                const float* qb = Qs + (4 * kk) * QS + cb0 * 32 + i32;
+                for (int gi = 0; gi < G_rows; ++gi) {
+                    const float* wag = wa + 8 * gi * kWS;
+                    const float* qbg = qb + 8 * gi * QS;
+                    float a[4], b[NBW][4];
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) a[s] = wag[s * kWS];
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) b[j][s] = qbg[s * QS + 64 * j];
+#pragma unroll
+                    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+                        for (int s = 0; s < 4; ++s) accC[j] = mfma32(a[s], b[j][s], accC[j]);
+                }
 #pragma unroll
                 for (int j = 0; j < NBW; ++j) {
-                    int cb = (w >> 1) + 2 * j;
-                    if (cb < NB) accC[j] = mfma32(a, qb[k0 * QS + cb * 32], accC[j]);
-                }
-            }
+                    const int col = (cb0 + 2 * j) * 32 + i32;
+                    if (col < d) {
 #pragma unroll
-            for (int j = 0; j < NBW; ++j) {
-                int cb = (w >> 1) + 2 * j;
-                int col = cb * 32 + i32;
-                if (cb < NB && col < d) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int neg = n0 + rbG * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
-                        if (neg < N) grad[(neg_base + neg) * d + col] = accC[j][v];
+                        for (int v = 0; v < 16; ++v) {
+                            const int neg = n0 + acc_row(rbG, v);
+                            if (neg < N) grad[(neg_base + neg) * d + col] = accC[j][v];
+                        }
                     }
                 }
             }
@@ -304,30 +388,29 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
 
     // ---- epilogue: G_Q to LDS, chain rule, gradient rows of the positives -------------------
     float* Gs = Ns;
+    if (active) {
 #pragma unroll
-    for (int j = 0; j < NBW; ++j) {
-        int cb = (w >> 1) + 2 * j;
-        int col = cb * 32 + i32;
-        if (cb < NB && col < d) {
+        for (int j = 0; j < NBW; ++j) {
+            const int col = (cb0 + 2 * j) * 32 + i32;
+            if (col < d) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = rbG * 32 + 8 * (v >> 2) + 4 * kk + (v & 3);
-                Gs[row * QS + col] = accB[j][v];
+                for (int v = 0; v < 16; ++v) Gs[acc_row(rbG, v) * QS + col] = accB[j][v];
             }
         }
+    }
+    if (LOSS == LEGEND_LOSS_LOGISTIC) {
+        // workgroup total of the negative terms: lanes -> wave -> LDS
+        for (int off = kWave / 2; off > 0; off >>= 1) neg_loss += __shfl_down(neg_loss, off, kWave);
+        if (lane == 0) lse_s[w] = neg_loss;
     }
     __syncthreads();
     {
         float row_loss = 0.f;
-        if (LOSS == LEGEND_LOSS_LOGISTIC) {
-            neg_loss += wave_shfl_xor(neg_loss, 1);
-            neg_loss += wave_shfl_xor(neg_loss, 2);
-        }
         if (prow < nrows) {
             const float f = pos_s[prow];
             float a;
-            if (LOSS == LEGEND_LOSS_SOFTMAX) { a = -1.f; row_loss = lse - f; }
-            else { a = -sigmoidf(-f); row_loss = softplusf(-f) + neg_loss; }
+            if (LOSS == LEGEND_LOSS_SOFTMAX) { a = -1.f; row_loss = lse_s[prow] - f; }
+            else { a = -sigmoidf(-f); row_loss = softplusf(-f); }
             const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;
             const float* y = Ey + (int64_t)eb[prow * 3 + ycol] * d;
             const float* r = SCORE == LEGEND_SCORE_DOT ? x : bp.E_rel + (int64_t)eb[prow * 3 + 1] * d;
@@ -371,13 +454,15 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     if (tid == 0) {
         double s = 0.0;
         for (int r = 0; r < kRowTile; ++r) s += (double)rowloss_s[r];
+        if (LOSS == LEGEND_LOSS_LOGISTIC)
+            for (int ww = 0; ww < kChunkThreads / kWave; ++ww) s += (double)lse_s[ww];
         loss_partial[blockIdx.x] = s;
     }
 }
 
 static size_t chunk_lds_bytes(int d, int nb) {
-    int QS = (d + 1) | 1;
-    size_t floats = 2 * ((size_t)kRowTile * QS + 32 * nb) + (size_t)kRowTile * kWS + 2 * kRowTile;
+    int QS = chunk_row_stride(d);
+    size_t floats = 2 * ((size_t)kRowTile * QS + 32 * nb) + (size_t)kRowTile * kWS + 3 * kRowTile + kIdsLds;
     return floats * sizeof(float);
 }
 
