@@ -114,6 +114,8 @@ k_scan_apply(const uint32_t* in, int64_t n, const uint32_t* __restrict__ block_s
         uint32_t total = block_sums[nb];
         seg_start[total] = (uint32_t)n;
         counters[0] = total;
+        counters[2] = 0;                      // the update kernels count long rows and their units here
+        counters[3] = 0;
         *uniq_total += total;
     }
 }

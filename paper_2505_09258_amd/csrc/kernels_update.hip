@@ -26,12 +26,77 @@ __device__ inline void adagrad_elem(float g, float& theta, float& state, float l
     theta = theta - step;
 }
 
-// LPR lanes (a float4 each) own one table row.
+constexpr int kLongLen = 32;    // table rows with more gradient rows than this take the two-level path
+constexpr int kUnit = 256;      // gradient rows per unit of the two-level path (8 groups x 32)
+
+__device__ inline int table_of_key(const UpdateTables& tb, uint32_t key) {
+    return key >= tb.key_base[2] ? 2 : (key >= tb.key_base[1] && tb.key_base[1] > 0 ? 1 : 0);
+}
+
+// Sum of gradient rows sorted_vals[lo..hi) (columns c0..c0+3) in that order, in fp64.
+__device__ inline void sum_rows(const float* __restrict__ grad, const uint32_t* __restrict__ sorted_vals,
+                                uint32_t lo, uint32_t hi, int d, int c0, bool vec4, double acc[4]) {
+    uint32_t p = lo;
+    if (vec4) {
+        for (; p + 4 <= hi; p += 4) {           // four independent loads in flight, added in order
+            const uint32_t o0 = sorted_vals[p], o1 = sorted_vals[p + 1], o2 = sorted_vals[p + 2], o3 = sorted_vals[p + 3];
+            const float4 v0 = *reinterpret_cast<const float4*>(grad + (int64_t)o0 * d + c0);
+            const float4 v1 = *reinterpret_cast<const float4*>(grad + (int64_t)o1 * d + c0);
+            const float4 v2 = *reinterpret_cast<const float4*>(grad + (int64_t)o2 * d + c0);
+            const float4 v3 = *reinterpret_cast<const float4*>(grad + (int64_t)o3 * d + c0);
+            acc[0] += (double)v0.x; acc[1] += (double)v0.y; acc[2] += (double)v0.z; acc[3] += (double)v0.w;
+            acc[0] += (double)v1.x; acc[1] += (double)v1.y; acc[2] += (double)v1.z; acc[3] += (double)v1.w;
+            acc[0] += (double)v2.x; acc[1] += (double)v2.y; acc[2] += (double)v2.z; acc[3] += (double)v2.w;
+            acc[0] += (double)v3.x; acc[1] += (double)v3.y; acc[2] += (double)v3.z; acc[3] += (double)v3.w;
+        }
+        for (; p < hi; ++p) {
+            const float4 v = *reinterpret_cast<const float4*>(grad + (int64_t)sorted_vals[p] * d + c0);
+            acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
+        }
+    } else {
+        for (; p < hi; ++p) {
+            const float* gp = grad + (int64_t)sorted_vals[p] * d + c0;
+            acc[0] += (double)gp[0];
+            if (c0 + 1 < d) acc[1] += (double)gp[1];
+            if (c0 + 2 < d) acc[2] += (double)gp[2];
+            if (c0 + 3 < d) acc[3] += (double)gp[3];
+        }
+    }
+}
+
+__device__ inline void apply_row(const UpdateTables& tb, uint32_t key, const double acc[4], int d, int c0, bool vec4,
+                                 float lr, float eps) {
+    const int t = table_of_key(tb, key);
+    const int64_t row = (int64_t)(key - tb.key_base[t]);
+    float* ep = tb.E[t] + row * d + c0;
+    float* sp = tb.S[t] + row * d + c0;
+    if (vec4) {
+        float4 th = *reinterpret_cast<float4*>(ep);
+        float4 st = *reinterpret_cast<float4*>(sp);
+        adagrad_elem((float)acc[0], th.x, st.x, lr, eps);
+        adagrad_elem((float)acc[1], th.y, st.y, lr, eps);
+        adagrad_elem((float)acc[2], th.z, st.z, lr, eps);
+        adagrad_elem((float)acc[3], th.w, st.w, lr, eps);
+        *reinterpret_cast<float4*>(ep) = th;
+        *reinterpret_cast<float4*>(sp) = st;
+    } else {
+        for (int j = 0; j < 4 && c0 + j < d; ++j) {
+            float th = ep[j], st = sp[j];
+            adagrad_elem((float)acc[j], th, st, lr, eps);
+            ep[j] = th;
+            sp[j] = st;
+        }
+    }
+}
+
+// LPR lanes (a float4 each) own one table row.  Rows with many gradient rows are only
+// recorded here (counters[2] = how many, long_list = which) and handled by the kernels below.
 template <int LPR>
 __global__ void __launch_bounds__(256)
-k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
+k_update(uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
          const uint32_t* __restrict__ seg_start, const uint32_t* __restrict__ sorted_vals,
-         const float* __restrict__ grad, UpdateTables tb, int d, float lr, float eps) {
+         const float* __restrict__ grad, UpdateTables tb, int d, float lr, float eps,
+         uint32_t* __restrict__ long_list) {
     const int groups_per_block = 256 / LPR;
     const int gl = threadIdx.x / LPR;
     const int col4 = threadIdx.x % LPR;
@@ -39,46 +104,144 @@ k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uni
     const bool vec4 = (d & 3) == 0;
     const uint32_t n_unique = counters[0];
     for (uint32_t u = blockIdx.x * groups_per_block + gl; u < n_unique; u += gridDim.x * groups_per_block) {
-        if (c0 >= d) continue;
-        const uint32_t key = uniq_keys[u];
-        const int t = key >= tb.key_base[2] ? 2 : (key >= tb.key_base[1] && tb.key_base[1] > 0 ? 1 : 0);
-        const int64_t row = (int64_t)(key - tb.key_base[t]);
         const uint32_t lo = seg_start[u], hi = seg_start[u + 1];
-        double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-        for (uint32_t p = lo; p < hi; ++p) {
-            const float* gp = grad + (int64_t)sorted_vals[p] * d + c0;
-            if (vec4) {
-                float4 v = *reinterpret_cast<const float4*>(gp);
-                a0 += (double)v.x; a1 += (double)v.y; a2 += (double)v.z; a3 += (double)v.w;
-            } else {
-                a0 += (double)gp[0];
-                if (c0 + 1 < d) a1 += (double)gp[1];
-                if (c0 + 2 < d) a2 += (double)gp[2];
-                if (c0 + 3 < d) a3 += (double)gp[3];
-            }
+        if (hi - lo > (uint32_t)kLongLen) {
+            if (col4 == 0) long_list[atomicAdd(&counters[2], 1u)] = u;
+            continue;
         }
-        float* ep = tb.E[t] + row * d + c0;
-        float* sp = tb.S[t] + row * d + c0;
-        if (vec4) {
-            float4 th = *reinterpret_cast<float4*>(ep);
-            float4 st = *reinterpret_cast<float4*>(sp);
-            adagrad_elem((float)a0, th.x, st.x, lr, eps);
-            adagrad_elem((float)a1, th.y, st.y, lr, eps);
-            adagrad_elem((float)a2, th.z, st.z, lr, eps);
-            adagrad_elem((float)a3, th.w, st.w, lr, eps);
-            *reinterpret_cast<float4*>(ep) = th;
-            *reinterpret_cast<float4*>(sp) = st;
-        } else {
-            double acc[4] = {a0, a1, a2, a3};
-            for (int j = 0; j < 4 && c0 + j < d; ++j) {
-                float th = ep[j], st = sp[j];
-                adagrad_elem((float)acc[j], th, st, lr, eps);
-                ep[j] = th;
-                sp[j] = st;
-            }
-        }
+        if (c0 >= d) continue;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        sum_rows(grad, sorted_vals, lo, hi, d, c0, vec4, acc);
+        apply_row(tb, uniq_keys[u], acc, d, c0, vec4, lr, eps);
     }
 }
+
+// Units of the two-level path: long row r owns ceil(len / kUnit) consecutive units;
+// unit_start = exclusive prefix of those counts (one block, sequential over blocks of 256).
+__global__ void __launch_bounds__(256)
+k_long_plan(uint32_t* __restrict__ counters, const uint32_t* __restrict__ long_list,
+            const uint32_t* __restrict__ seg_start, uint32_t* __restrict__ unit_start) {
+    __shared__ uint32_t wsum[4];
+    __shared__ uint32_t carry_s;
+    const uint32_t n_long = counters[2];
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < n_long; base += 256) {
+        const uint32_t r = base + threadIdx.x;
+        uint32_t v = 0;
+        if (r < n_long) {
+            const uint32_t u = long_list[r];
+            v = (seg_start[u + 1] - seg_start[u] + kUnit - 1) / kUnit;
+        }
+        uint32_t incl = v;
+        for (int off = 1; off < kWave; off <<= 1) {
+            uint32_t t = __shfl_up(incl, off, kWave);
+            if (lane_id() >= off) incl += t;
+        }
+        if (lane_id() == kWave - 1) wsum[threadIdx.x / kWave] = incl;
+        __syncthreads();
+        uint32_t woff = 0;
+        for (int w = 0; w < (int)(threadIdx.x / kWave); ++w) woff += wsum[w];
+        const uint32_t carry = carry_s;
+        if (r < n_long) unit_start[r] = carry + woff + incl - v;
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = carry + woff + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        unit_start[n_long] = carry_s;
+        counters[3] = carry_s;
+    }
+}
+
+// One block per unit: eight groups sum 32 consecutive gradient rows each, the eight partial
+// sums are added in group order; the result is an fp64 row in `partial`.
+template <int LPR>
+__global__ void __launch_bounds__(256)
+k_long_partial(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ long_list,
+               const uint32_t* __restrict__ unit_start, const uint32_t* __restrict__ seg_start,
+               const uint32_t* __restrict__ sorted_vals, const float* __restrict__ grad, int d,
+               double* __restrict__ partial) {
+    constexpr int GROUPS = 256 / LPR;
+    constexpr int PER_GROUP = kUnit / GROUPS;
+    extern __shared__ double psum[];          // [GROUPS][4 * LPR]
+    const int gl = threadIdx.x / LPR;
+    const int col4 = threadIdx.x % LPR;
+    const int c0 = col4 * 4;
+    const bool vec4 = (d & 3) == 0;
+    const uint32_t n_long = counters[2], n_units = counters[3];
+    for (uint32_t unit = blockIdx.x; unit < n_units; unit += gridDim.x) {
+        uint32_t a = 0, b = n_long;           // last r with unit_start[r] <= unit
+        while (b - a > 1) {
+            uint32_t mid = (a + b) >> 1;
+            if (unit_start[mid] <= unit) a = mid; else b = mid;
+        }
+        const uint32_t u = long_list[a];
+        const uint32_t seg_lo = seg_start[u], seg_hi = seg_start[u + 1];
+        const uint32_t lo = seg_lo + (unit - unit_start[a]) * kUnit + gl * PER_GROUP;
+        const uint32_t hi = min(seg_hi, lo + PER_GROUP);
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        if (c0 < d && lo < hi) sum_rows(grad, sorted_vals, lo, hi, d, c0, vec4, acc);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) psum[(gl * LPR + col4) * 4 + j] = acc[j];
+        __syncthreads();
+        if (gl == 0 && c0 < d) {
+            double tot[4] = {0.0, 0.0, 0.0, 0.0};
+            for (int gq = 0; gq < GROUPS; ++gq)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) tot[j] += psum[(gq * LPR + col4) * 4 + j];
+            for (int j = 0; j < 4 && c0 + j < d; ++j) partial[(int64_t)unit * d + c0 + j] = tot[j];
+        }
+        __syncthreads();
+    }
+}
+
+// One group per long row: its units' partial rows are added in unit order, then Adagrad.
+template <int LPR>
+__global__ void __launch_bounds__(256)
+k_long_final(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ long_list,
+             const uint32_t* __restrict__ unit_start, const uint32_t* __restrict__ uniq_keys,
+             const double* __restrict__ partial, UpdateTables tb, int d, float lr, float eps) {
+    const int groups_per_block = 256 / LPR;
+    const int gl = threadIdx.x / LPR;
+    const int col4 = threadIdx.x % LPR;
+    const int c0 = col4 * 4;
+    const bool vec4 = (d & 3) == 0;
+    const uint32_t n_long = counters[2];
+    for (uint32_t r = blockIdx.x * groups_per_block + gl; r < n_long; r += gridDim.x * groups_per_block) {
+        if (c0 >= d) continue;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        for (uint32_t unit = unit_start[r]; unit < unit_start[r + 1]; ++unit) {
+            const double* pp = partial + (int64_t)unit * d + c0;
+            for (int j = 0; j < 4 && c0 + j < d; ++j) acc[j] += pp[j];
+        }
+        apply_row(tb, uniq_keys[long_list[r]], acc, d, c0, vec4, lr, eps);
+    }
+}
+
+template <int LPR>
+static hipError_t launch_update_lpr(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                                    const uint32_t* sorted_vals, const UpdateTables& tb) {
+    const int d = bp.dim;
+    const int groups = 256 / LPR;
+    int64_t blocks = (g.n_occ + groups - 1) / groups;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_update<LPR>, dim3((unsigned)blocks), dim3(256), 0, st, ws.counters, ws.uniq_keys, ws.seg_start,
+                       sorted_vals, ws.grad, tb, d, bp.lr, bp.eps, ws.long_list);
+    hipLaunchKernelGGL(k_long_plan, dim3(1), dim3(256), 0, st, ws.counters, ws.long_list, ws.seg_start, ws.unit_start);
+    int64_t max_units = g.n_occ / kUnit + g.n_occ / (kLongLen + 1) + 1;
+    int64_t ublocks = max_units < 2048 ? max_units : 2048;
+    hipLaunchKernelGGL(k_long_partial<LPR>, dim3((unsigned)ublocks), dim3(256), sizeof(double) * 4 * 256, st, ws.counters,
+                       ws.long_list, ws.unit_start, ws.seg_start, sorted_vals, ws.grad, d, ws.long_partial);
+    int64_t fblocks = (g.n_occ / (kLongLen + 1) + groups) / groups;
+    if (fblocks > 1024) fblocks = 1024;
+    hipLaunchKernelGGL(k_long_final<LPR>, dim3((unsigned)fblocks), dim3(256), 0, st, ws.counters, ws.long_list,
+                       ws.unit_start, ws.uniq_keys, ws.long_partial, tb, d, bp.lr, bp.eps);
+    return hipGetLastError();
+}
+
+int64_t update_long_rows_capacity(int64_t n_occ) { return n_occ / (kLongLen + 1) + 2; }
+int64_t update_long_units_capacity(int64_t n_occ) { return n_occ / kUnit + n_occ / (kLongLen + 1) + 2; }
 
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, int32_t rows_per_partition) {
@@ -90,18 +253,10 @@ hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams&
     tb.E[2] = bp.E_rel; tb.S[2] = bp.S_rel;
     tb.key_base[0] = 0; tb.key_base[1] = bp.key_base_dst; tb.key_base[2] = bp.key_base_rel;
     const int d = bp.dim;
-    int lpr = d <= 32 ? 8 : d <= 64 ? 16 : d <= 128 ? 32 : 64;
-    int groups = 256 / lpr;
-    int64_t blocks = (g.n_occ + groups - 1) / groups;
-    if (blocks > 8192) blocks = 8192;
-    dim3 grid((unsigned)blocks), block(256);
-    switch (lpr) {
-        case 8:  hipLaunchKernelGGL(k_update<8>, grid, block, 0, st, ws.counters, ws.uniq_keys, ws.seg_start, sorted_vals, ws.grad, tb, d, bp.lr, bp.eps); break;
-        case 16: hipLaunchKernelGGL(k_update<16>, grid, block, 0, st, ws.counters, ws.uniq_keys, ws.seg_start, sorted_vals, ws.grad, tb, d, bp.lr, bp.eps); break;
-        case 32: hipLaunchKernelGGL(k_update<32>, grid, block, 0, st, ws.counters, ws.uniq_keys, ws.seg_start, sorted_vals, ws.grad, tb, d, bp.lr, bp.eps); break;
-        default: hipLaunchKernelGGL(k_update<64>, grid, block, 0, st, ws.counters, ws.uniq_keys, ws.seg_start, sorted_vals, ws.grad, tb, d, bp.lr, bp.eps); break;
-    }
-    return hipGetLastError();
+    if (d <= 32) return launch_update_lpr<8>(st, g, bp, ws, sorted_vals, tb);
+    if (d <= 64) return launch_update_lpr<16>(st, g, bp, ws, sorted_vals, tb);
+    if (d <= 128) return launch_update_lpr<32>(st, g, bp, ws, sorted_vals, tb);
+    return launch_update_lpr<64>(st, g, bp, ws, sorted_vals, tb);
 }
 
 // ---- f(theta_s, theta_r, theta_d) for global ids: one wavefront per triple ------------------

@@ -69,7 +69,10 @@ struct Workspace {
     uint32_t* scan_tmp;       // block sums of the generic scan
     uint32_t* uniq_keys;      // [n_occ]
     uint32_t* seg_start;      // [n_occ + 1]
-    uint32_t* counters;       // [0] = unique rows of the batch, [1] = error flag
+    uint32_t* counters;       // [0] unique rows of the batch, [1] error flag, [2] long rows, [3] units of long rows
+    uint32_t* long_list;      // unique-row indices of rows with many gradient rows
+    uint32_t* unit_start;     // first unit of each long row (+ total)
+    double*   long_partial;   // [units][dim] fp64 partial sums
     unsigned long long* uniq_total;  // running sum of unique rows
     float*    grad;           // [n_occ][dim] staged gradient rows
     double*   loss_partial;   // one per chunk workgroup
@@ -97,6 +100,8 @@ hipError_t launch_gather_rows(hipStream_t st, const int64_t* ids, int64_t m, flo
                               int32_t rows_per_partition, int64_t num_rows, int32_t dim, float* out,
                               uint32_t* err_flag);
 
+int64_t update_long_rows_capacity(int64_t n_occ);
+int64_t update_long_units_capacity(int64_t n_occ);
 int row_tiles_for(int chunk_size);          // T
 int rows_per_tile_for(int chunk_size);      // ceil(C / T)
 int max_dim_supported();

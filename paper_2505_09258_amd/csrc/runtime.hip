@@ -236,7 +236,7 @@ void free_ctx(legend_ctx* c) {
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
-                     c->ws.counters, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.loss_sum, c->edges_dev,
+                     c->ws.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.loss_sum, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
     if (c->ev_fence) (void)hipEventDestroy(c->ev_fence);
@@ -494,6 +494,9 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     INIT_RC(dev_alloc(c, &w.uniq_keys, (size_t)occ));
     INIT_RC(dev_alloc(c, &w.seg_start, (size_t)occ + 1));
     INIT_RC(dev_alloc(c, &w.counters, 4));
+    INIT_RC(dev_alloc(c, &w.long_list, (size_t)update_long_rows_capacity(occ)));
+    INIT_RC(dev_alloc(c, &w.unit_start, (size_t)update_long_rows_capacity(occ) + 1));
+    INIT_RC(dev_alloc(c, &w.long_partial, (size_t)update_long_units_capacity(occ) * c->d));
     INIT_RC(dev_alloc(c, &w.uniq_total, 1));
     INIT_RC(dev_alloc(c, &w.grad, (size_t)occ * c->d));
     INIT_RC(dev_alloc(c, &w.loss_partial, (size_t)nwg));
