@@ -47,6 +47,19 @@ __device__ inline float softplusf(float x) {
 }
 __device__ inline float sigmoidf(float x) { return 1.f / (1.f + expf(-x)); }
 
+// exp(x) for finite x from the hardware 2^x instruction: the product x * log2(e) is formed in
+// two pieces (head, and rounding error + low part of the constant) so that the result is good
+// to about two ulp for any magnitude of x, at six VALU instructions.
+__device__ inline float fast_exp(float x) {
+    const float L2E_HI = 1.44269502162933349609375f;
+    const float L2E_LO = 1.925963033500011e-8f;
+    const float hi = x * L2E_HI;
+    float lo = fmaf(x, L2E_HI, -hi);
+    lo = fmaf(x, L2E_LO, lo);
+    const float r = __builtin_amdgcn_exp2f(hi);
+    return fmaf(r, lo * 0.6931471805599453f, r);
+}
+
 __device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 
 // MFMA operand mapping used everywhere below: the contraction index runs in groups of 8;
@@ -56,8 +69,10 @@ __device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const f
 // values of a row-major operand with one 128-bit LDS read.
 
 // NB: number of 32-wide column blocks covering the embedding dimension (dim <= 32 * NB).
-template <int NB, int SCORE, int LOSS>
-__global__ void __launch_bounds__(kChunkThreads)
+// DFIX: the embedding dimension when it is known at compile time (strides, trip counts and
+// the float4 path fold to constants), or 0 to take it from the arguments.
+template <int NB, int SCORE, int LOSS, int DFIX>
+__global__ void __launch_bounds__(kChunkThreads, 2)     // two waves per SIMD: two workgroups share a compute unit
 k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float* __restrict__ grad,
         double* __restrict__ loss_partial) {
     constexpr int LPR = NB * 8;             // lanes that cooperate on one gathered row (float4 each)
@@ -66,7 +81,7 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     constexpr int NBW = (2 * NB + 3) / 4;   // 32x32 output blocks per wave in the gradient products
 
     extern __shared__ __align__(16) float smem[];
-    const int d = bp.dim;
+    const int d = DFIX ? DFIX : bp.dim;
     const int QS = chunk_row_stride(d);
     const int G_d = (d + 7) >> 3;           // contraction groups over the embedding dimension
     const int tile_floats = kRowTile * QS + 32 * NB;
@@ -230,9 +245,13 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
 
     if (LOSS == LEGEND_LOSS_SOFTMAX) {
         // ---- sweep 1: running max and sum of exp, per lane over its own columns -------------
+        // Each lane keeps, per row, a reference score m and sum of exp(S - m) over the columns it
+        // has seen.  The reference only moves when a score exceeds it by more than 16 (the sum
+        // then stays far inside the fp32 range), so the common case costs one exp per score.
         float m_l[16], s_l[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) { m_l[v] = -INFINITY; s_l[v] = 0.f; }
+        bool seeded = false;
         for (int tile = 0; tile < ntiles; ++tile) {
             const int n0 = tile * kNegTile;
             gather_commit();
@@ -240,12 +259,21 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             gather_issue(tile + 1 < ntiles ? n0 + kNegTile : 0);   // next tile, or first tile of sweep 2
             f32x16 acc = score_block();
             if (n0 + cbA * 32 + i32 < N) {
+                if (!seeded) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float sv = acc[v];
-                    float mn = fmaxf(m_l[v], sv);
-                    s_l[v] = s_l[v] * expf(m_l[v] - mn) + expf(sv - mn);
-                    m_l[v] = mn;
+                    for (int v = 0; v < 16; ++v) { m_l[v] = acc[v]; s_l[v] = 1.f; }
+                    seeded = true;
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float tdiff = acc[v] - m_l[v];
+                        if (tdiff > 16.f) {
+                            s_l[v] = fmaf(s_l[v], fast_exp(-tdiff), 1.f);
+                            m_l[v] = acc[v];
+                        } else {
+                            s_l[v] += fast_exp(tdiff);
+                        }
+                    }
                 }
             }
             __syncthreads();
@@ -313,7 +341,7 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                 float wv = 0.f;
                 if (col_ok && r < nrows) {
                     if (LOSS == LEGEND_LOSS_SOFTMAX) {
-                        wv = expf(acc[v] - lse_r[v]);
+                        wv = fast_exp(acc[v] - lse_r[v]);
                     } else {
                         wv = wneg * sigmoidf(acc[v]);
                         neg_loss += wneg * softplusf(acc[v]);
@@ -466,7 +494,7 @@ static size_t chunk_lds_bytes(int d, int nb) {
     return floats * sizeof(float);
 }
 
-template <int NB>
+template <int NB, int DFIX>
 static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     dim3 grid((unsigned)(g.sides * g.nchunks * g.T)), block(kChunkThreads);
     size_t lds = chunk_lds_bytes(bp.dim, NB);
@@ -474,12 +502,12 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
     if (bp.score == SC && bp.loss == LO) {                                                                     \
         static size_t lds_allowed = 0; /* dynamic LDS above 64 KB has to be requested per kernel */            \
         if (lds > lds_allowed) {                                                                               \
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chunk<NB, SC, LO>),            \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chunk<NB, SC, LO, DFIX>),      \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (e != hipSuccess) return e;                                                                     \
             lds_allowed = lds;                                                                                 \
         }                                                                                                      \
-        hipLaunchKernelGGL((k_chunk<NB, SC, LO>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,            \
+        hipLaunchKernelGGL((k_chunk<NB, SC, LO, DFIX>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,      \
                            ws.loss_partial);                                                                   \
         return hipGetLastError();                                                                              \
     }
@@ -495,9 +523,12 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
 
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     if (g.P <= 0) return hipSuccess;
-    if (bp.dim <= 32) return launch_chunks_nb<1>(st, g, bp, ws);
-    if (bp.dim <= 64) return launch_chunks_nb<2>(st, g, bp, ws);
-    if (bp.dim <= 128) return launch_chunks_nb<4>(st, g, bp, ws);
+    // the dimensions of the paper's workloads get kernels with the dimension folded in
+    if (bp.dim == 100) return launch_chunks_nb<4, 100>(st, g, bp, ws);
+    if (bp.dim == 32) return launch_chunks_nb<1, 32>(st, g, bp, ws);
+    if (bp.dim <= 32) return launch_chunks_nb<1, 0>(st, g, bp, ws);
+    if (bp.dim <= 64) return launch_chunks_nb<2, 0>(st, g, bp, ws);
+    if (bp.dim <= 128) return launch_chunks_nb<4, 0>(st, g, bp, ws);
     return hipErrorInvalidValue;
 }
 
