@@ -13,7 +13,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblegend_hip.so")
+# LEGEND_HIP_LIB selects another build of the same library (e.g. one compiled with debug flags)
+LIB_PATH = os.environ.get("LEGEND_HIP_LIB") or os.path.join(_HERE, "liblegend_hip.so")
 
 LEGEND_OK = 0
 LEGEND_E_INVAL, LEGEND_E_NOMEM, LEGEND_E_NOT_RESIDENT = -1, -2, -3

@@ -12,6 +12,8 @@
 // CDNA4 compute unit, so for Eq. 1 the sweep runs twice (log-sum-exp first, then the
 // gradients with S recomputed) and nothing but gradient rows is ever written to HBM.
 // Wavefronts are 64 wide: a 64x64 score tile is four 32x32 MFMA blocks, one per wave.
+#include <type_traits>
+
 #include "legend_internal.h"
 #include "device_utils.h"
 
@@ -165,48 +167,69 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     }
     __syncthreads();                          // ids_s, Qs, pos_s complete
 
-    // ---- negative tile gather: registers first, LDS after the previous tile is done -------
-    float4 pf[STEPS];
+    // ---- negative tile gather: rows travel through registers (up to three tiles in flight) and
+    // are committed to LDS when the previous tile is done.  Buffer indices are compile-time
+    // (the tile loops are unrolled by the number of buffers) so the buffers stay in registers.
+    float4 pf[3][STEPS];
     const int grow_lane = lane / LPR;         // row within a step
     const int gcol4 = lane % LPR;             // float4 column
-    auto gather_issue = [&](int n0) {
+    const int gc0 = gcol4 * 4;
+    // Straight-line code on purpose: rows past the end of the chunk's negatives and lanes past
+    // the end of a row load some valid address and are zeroed when the tile is committed, so
+    // that all loads of a tile are issued back to back and nothing waits on them here.
+    const bool ids_in_lds = N <= kIdsLds;     // uniform: all ids of the chunk sit in LDS
+    const int gcol_ld = gc0 < d ? gc0 : 0;
+    auto gather_issue = [&](auto BUF, int n0) {
+        constexpr int B = decltype(BUF)::value;
+        int32_t idv[STEPS];
+        if (ids_in_lds) {
+            // explicit LDS address space: keeps these reads apart from the global path below
+            typedef __attribute__((address_space(3))) const int32_t* lds_ids_t;
+            lds_ids_t ids_l = (lds_ids_t)ids_s;
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            int rt = w * 16 + s * RPS + grow_lane;
-            int k = n0 + rt;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            int c0 = gcol4 * 4;
-            if (k < N && c0 < d) {
-                const int32_t id = k < kIdsLds ? ids_s[k] : my_negs[k];
-                const float* p = En + (int64_t)id * d + c0;
-                if (vec4) {
-                    v = *reinterpret_cast<const float4*>(p);
-                } else {
-                    v.x = p[0];
-                    if (c0 + 1 < d) v.y = p[1];
-                    if (c0 + 2 < d) v.z = p[2];
-                    if (c0 + 3 < d) v.w = p[3];
-                }
+            for (int s = 0; s < STEPS; ++s) idv[s] = ids_l[min(n0 + w * 16 + s * RPS + grow_lane, N - 1)];
+        } else {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) idv[s] = my_negs[min(n0 + w * 16 + s * RPS + grow_lane, N - 1)];
+        }
+        if (vec4) {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s)
+                pf[B][s] = *reinterpret_cast<const float4*>(En + (int64_t)idv[s] * d + gcol_ld);
+        } else {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const float* p = En + (int64_t)idv[s] * d + gcol_ld;
+                float4 v = make_float4(p[0], 0.f, 0.f, 0.f);
+                if (gcol_ld + 1 < d) v.y = p[1];
+                if (gcol_ld + 2 < d) v.z = p[2];
+                if (gcol_ld + 3 < d) v.w = p[3];
+                pf[B][s] = v;
             }
-            pf[s] = v;
         }
     };
-    auto gather_commit = [&]() {
+    auto gather_commit = [&](auto BUF, int n0) {
+        constexpr int B = decltype(BUF)::value;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
-            int rt = w * 16 + s * RPS + grow_lane;
-            int c0 = gcol4 * 4;
-            float* dst = Ns + rt * QS + c0;
+            const int rt = w * 16 + s * RPS + grow_lane;
+            const bool row_ok = n0 + rt < N;
+            float4 v = pf[B][s];
+            if (!row_ok) v = make_float4(0.f, 0.f, 0.f, 0.f);
+            float* dst = Ns + rt * QS + gc0;
             if (vec4) {
-                if (c0 < d) *reinterpret_cast<float4*>(dst) = pf[s];
+                if (gc0 < d) *reinterpret_cast<float4*>(dst) = v;
             } else {
-                if (c0 < d) dst[0] = pf[s].x;
-                if (c0 + 1 < d) dst[1] = pf[s].y;
-                if (c0 + 2 < d) dst[2] = pf[s].z;
-                if (c0 + 3 < d) dst[3] = pf[s].w;
+                if (gc0 < d) dst[0] = v.x;
+                if (gc0 + 1 < d) dst[1] = v.y;
+                if (gc0 + 2 < d) dst[2] = v.z;
+                if (gc0 + 3 < d) dst[3] = v.w;
             }
         }
     };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
 
     // ---- S block of this wave: rows rbA*32.., negatives cbA*32.. of the current tile --------
     const int rbA = w & 1, cbA = w >> 1;
@@ -217,14 +240,16 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
         float4 a = lds4(qa), b = lds4(nb);
         for (int gi = 0; gi < G_d; ++gi) {
             float4 an = a, bn = b;
-            if (gi + 1 < G_d) {
+            if (gi + 1 < G_d) {               // operands of the next group travel while this group multiplies
                 an = lds4(qa + 8 * (gi + 1));
                 bn = lds4(nb + 8 * (gi + 1));
             }
+            __builtin_amdgcn_sched_barrier(0);
             acc = mfma32(a.x, b.x, acc);
             acc = mfma32(a.y, b.y, acc);
             acc = mfma32(a.z, b.z, acc);
             acc = mfma32(a.w, b.w, acc);
+            __builtin_amdgcn_sched_barrier(0);
             a = an;
             b = bn;
         }
@@ -236,27 +261,24 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     const int ntiles = (N + kNegTile - 1) / kNegTile;
     const int srow = tid >> 2;                // 4 threads per row for the row-wise reductions
     const int sq = tid & 3;
-    float lse_r[16];                          // log-sum-exp of the 16 rows this lane sees in a score block
-#pragma unroll
-    for (int v = 0; v < 16; ++v) lse_r[v] = 0.f;
     float neg_loss = 0.f;                     // logistic: this lane's share of the weighted softplus terms
-
-    gather_issue(0);
 
     if (LOSS == LEGEND_LOSS_SOFTMAX) {
         // ---- sweep 1: running max and sum of exp, per lane over its own columns -------------
         // Each lane keeps, per row, a reference score m and sum of exp(S - m) over the columns it
         // has seen.  The reference only moves when a score exceeds it by more than 16 (the sum
         // then stays far inside the fp32 range), so the common case costs one exp per score.
+        // This sweep has little arithmetic per gathered byte, so three tiles are kept in flight.
         float m_l[16], s_l[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) { m_l[v] = -INFINITY; s_l[v] = 0.f; }
         bool seeded = false;
-        for (int tile = 0; tile < ntiles; ++tile) {
+        auto sweep1_tile = [&](auto BUF, auto NEXT, int tile) {
+            if (tile >= ntiles) return;
             const int n0 = tile * kNegTile;
-            gather_commit();
+            gather_commit(BUF, n0);
             __syncthreads();
-            gather_issue(tile + 1 < ntiles ? n0 + kNegTile : 0);   // next tile, or first tile of sweep 2
+            if (tile + 2 < ntiles) gather_issue(NEXT, n0 + 2 * kNegTile);
             f32x16 acc = score_block();
             if (n0 + cbA * 32 + i32 < N) {
                 if (!seeded) {
@@ -277,6 +299,13 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                 }
             }
             __syncthreads();
+        };
+        gather_issue(I0{}, 0);
+        if (ntiles > 1) gather_issue(I1{}, kNegTile);
+        for (int tile = 0; tile < ntiles; tile += 3) {
+            sweep1_tile(I0{}, I2{}, tile);
+            sweep1_tile(I1{}, I0{}, tile + 1);
+            sweep1_tile(I2{}, I1{}, tile + 2);
         }
         // combine the 64 per-lane partials of every row (two waves x 32 lanes): max, then sum
         const int pcol = cbA * 32 + i32;
@@ -311,8 +340,6 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             if (sq == 0) lse_s[srow] = mx + logf(sum);
         }
         __syncthreads();
-#pragma unroll
-        for (int v = 0; v < 16; ++v) lse_r[v] = lse_s[acc_row(rbA, v)];
     }
 
     // ---- sweep 2: gradients ----------------------------------------------------------------
@@ -327,11 +354,12 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     const int G_rows = (nrows + 7) >> 3;
     const float wneg = bp.neg_weight;
 
-    for (int tile = 0; tile < ntiles; ++tile) {
+    auto sweep2_tile = [&](auto BUF, int tile) {
+        if (tile >= ntiles) return;
         const int n0 = tile * kNegTile;
-        gather_commit();
+        gather_commit(BUF, n0);
         __syncthreads();
-        if (tile + 1 < ntiles) gather_issue(n0 + kNegTile);
+        if (tile + 2 < ntiles) gather_issue(BUF, n0 + 2 * kNegTile);   // this buffer is free again
         {
             f32x16 acc = score_block();
             const bool col_ok = n0 + cbA * 32 + i32 < N;
@@ -341,7 +369,7 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                 float wv = 0.f;
                 if (col_ok && r < nrows) {
                     if (LOSS == LEGEND_LOSS_SOFTMAX) {
-                        wv = fast_exp(acc[v] - lse_r[v]);
+                        wv = fast_exp(acc[v] - lse_s[r]);
                     } else {
                         wv = wneg * sigmoidf(acc[v]);
                         neg_loss += wneg * softplusf(acc[v]);
@@ -351,6 +379,11 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             }
         }
         __syncthreads();
+        f32x16 accC[NBW];
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) accC[j][v] = 0.f;
         if (active) {
             const int G_n = (min(kNegTile, N - n0) + 7) >> 3;
             // G_Q += W * Neg : contraction over the negatives of the tile
@@ -374,13 +407,8 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                     }
                 }
             }
-            // G_neg = W^T * Q : contraction over the positives, written to the staged gradient rows
+            // G_neg = W^T * Q : contraction over the positives
             {
-                f32x16 accC[NBW];
-#pragma unroll
-                for (int j = 0; j < NBW; ++j)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) accC[j][v] = 0.f;
                 const float* wa = Ws + (4 * kk) * kWS + rbG * 32 + i32;
                 const float* qb = Qs + (4 * kk) * QS + cb0 * 32 + i32;
                 for (int gi = 0; gi < G_rows; ++gi) {
@@ -398,20 +426,45 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
 #pragma unroll
                         for (int s = 0; s < 4; ++s) accC[j] = mfma32(a[s], b[j][s], accC[j]);
                 }
+            }
+        }
+        __syncthreads();                      // the negative tile is not read any more
+        // G_neg goes through the tile buffer so that whole gradient rows leave as 16-byte stores
+        if (active) {
 #pragma unroll
-                for (int j = 0; j < NBW; ++j) {
-                    const int col = (cb0 + 2 * j) * 32 + i32;
-                    if (col < d) {
+            for (int j = 0; j < NBW; ++j) {
+                const int col = (cb0 + 2 * j) * 32 + i32;
+                if (col < d) {
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int neg = n0 + acc_row(rbG, v);
-                            if (neg < N) grad[(neg_base + neg) * d + col] = accC[j][v];
-                        }
-                    }
+                    for (int v = 0; v < 16; ++v) Ns[acc_row(rbG, v) * QS + col] = accC[j][v];
                 }
             }
         }
         __syncthreads();
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int rt = w * 16 + s * RPS + grow_lane;
+            const int neg = n0 + rt;
+            if (neg < N && gc0 < d) {
+                const float* src = Ns + rt * QS + gc0;
+                float* dst = grad + (neg_base + neg) * d + gc0;
+                if (vec4) {
+                    *reinterpret_cast<float4*>(dst) = lds4(src);
+                } else {
+                    dst[0] = src[0];
+                    if (gc0 + 1 < d) dst[1] = src[1];
+                    if (gc0 + 2 < d) dst[2] = src[2];
+                    if (gc0 + 3 < d) dst[3] = src[3];
+                }
+            }
+        }
+        __syncthreads();                      // staged rows are read; the next tile may be committed
+    };
+    gather_issue(I0{}, 0);
+    if (ntiles > 1) gather_issue(I1{}, kNegTile);
+    for (int tile = 0; tile < ntiles; tile += 2) {
+        sweep2_tile(I0{}, tile);
+        sweep2_tile(I1{}, tile + 1);
     }
 
     // ---- epilogue: G_Q to LDS, chain rule, gradient rows of the positives -------------------
