@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
+# HBM bytes per k_chunk launch from the rocprofv3 counter runs summarised in
+# profiles/c2_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB, calibrated on a copy)
+CHUNK_TRAFFIC_BYTES = {"c2": int((485520.2 * 2.0 + 439878.7) * 1024)}
 
 
 def log(*a):
@@ -133,6 +136,20 @@ def main() -> int:
         k += 1
     chunk_bit = 1 << names.index("chunk")
 
+    # a plain device copy of known size: the streaming ceiling of this machine, and the kernel the
+    # rocprofv3 FETCH_SIZE / WRITE_SIZE counters are calibrated against (1 GiB read + 1 GiB written)
+    cal_src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    cal_dst.copy_(cal_src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * cal_src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del cal_src, cal_dst
+
     run(work[:first_timed])
     L.legend_sync(ctx)
     L.legend_unique_rows_read(ctx)
@@ -166,7 +183,8 @@ def main() -> int:
     alg_bytes = 12 * P + 4 * Q + 4 * d * (2 * P + Q) + 16 * d * u_b
     roofline = {"kernel": "k_chunk (gather + scores + loss + backward, fp32 MFMA)", "bound": "mfma",
                 "achieved": round(achieved_tflops, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4),
+                "traffic": CHUNK_TRAFFIC_BYTES.get(w.name),
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": round(chunk_ms, 4)}
 
     # ---- second pass with every kernel class event-timed (separate from the timed region) ----
@@ -215,7 +233,7 @@ def main() -> int:
                    "update_mode": "deterministic", "resident_partitions": capacity},
         "device_ms_per_step": round(dev_ms / K, 4),
         "algorithmic_bytes_per_step": int(alg_bytes), "unique_rows_per_step": round(u_b),
-        "hbm_GBs_whole_step": round(alg_bytes / (wall / K) / 1e9, 1),
+        "hbm_GBs_whole_step": round(alg_bytes / (wall / K) / 1e9, 1), "copy_GBs_measured": round(copy_gbs, 1),
         "roofline": roofline, "kernels": kernels,
     }
 
