@@ -174,6 +174,35 @@ int legend_train_bucket_range(legend_ctx* ctx, int32_t src_part, int32_t dst_par
                               int64_t batch_begin, int64_t batch_end,
                               const legend_prefetch* hint, legend_bucket_stats* stats);
 
+typedef struct legend_epoch_stats {
+    double  loss_sum;       /* sum of the loss terms of the epoch                         */
+    int64_t edges;
+    int64_t batches;
+    int64_t swaps;          /* partition loads and write-backs enqueued                   */
+    int64_t buffer_states;  /* states of the loading order (1 when everything is resident) */
+    int64_t bytes_per_swap; /* size of one [E_p | S_p] block                              */
+    double  ms;             /* host wall time from the first call to the final sync       */
+} legend_epoch_stats;
+
+/*
+ * One epoch over all n*n buckets (Sec. 3 steps 1-8, Sec. 4 Alg. 1 and Alg. 2).
+ *   bucket_edges  [n*n] pointers, bucket (i, j) at index i*n + j, each [size][3] int32
+ *                 as in legend_train_bucket (all host or all device, edges_mem);
+ *   bucket_sizes  [n*n] edge counts (0 allowed, pointer then ignored);
+ *   overlap       1: each swap is enqueued as soon as the buckets of the state that
+ *                 involve the evicted partition are trained and runs while the rest
+ *                 of the state trains (prefetching, Sec. 4); 0: swaps run after the
+ *                 state's last bucket (the paper's "without prefetching" ablation).
+ * With buffer_capacity == num_partitions every partition is made resident and no
+ * swap happens during the epoch; otherwise buffer_capacity must be 3 (the paper's
+ * setting) and the planner's loading order is followed.  Partitions resident on
+ * return are those of the last buffer state; legend_read_embeddings sees all data.
+ * The call returns after all work has finished.
+ */
+int legend_train_epoch(legend_ctx* ctx, const int32_t* const* bucket_edges,
+                       const int64_t* bucket_sizes, int32_t edges_mem, int32_t epoch,
+                       int32_t overlap, legend_epoch_stats* stats);
+
 /*
  * f(theta_s, theta_r, theta_d) of m triples with the current embeddings
  * (Sec. 2.1).  src/dst are GLOBAL node ids; rel may be NULL for Dot.  Every

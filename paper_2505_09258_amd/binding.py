@@ -28,7 +28,7 @@ TABLE_NODE_EMB, TABLE_NODE_STATE, TABLE_REL_EMB, TABLE_REL_STATE = 0, 1, 2, 3
 
 EXPORTS = [
     "legend_init_partitions", "legend_destroy", "legend_swap_partition", "legend_partition_slot",
-    "legend_train_bucket", "legend_train_bucket_range", "legend_score_edges", "legend_read_embeddings", "legend_debug_batch_indices",
+    "legend_train_bucket", "legend_train_bucket_range", "legend_train_epoch", "legend_score_edges", "legend_read_embeddings", "legend_debug_batch_indices",
     "legend_plan_order", "legend_sync", "legend_profile_enable", "legend_profile_read",
     "legend_profile_name", "legend_batch_shape_of", "legend_unique_rows_read", "legend_last_error",
 ]
@@ -52,6 +52,11 @@ class legend_prefetch(C.Structure):
 
 class legend_bucket_stats(C.Structure):
     _fields_ = [("loss_sum", C.c_double), ("batches", C.c_int64), ("edges", C.c_int64), ("ms", C.c_double)]
+
+
+class legend_epoch_stats(C.Structure):
+    _fields_ = [("loss_sum", C.c_double), ("edges", C.c_int64), ("batches", C.c_int64), ("swaps", C.c_int64),
+                ("buffer_states", C.c_int64), ("bytes_per_swap", C.c_int64), ("ms", C.c_double)]
 
 
 class legend_batch_shape(C.Structure):
@@ -78,6 +83,7 @@ def _load() -> C.CDLL:
                                         C.POINTER(legend_bucket_stats)]
     lib.legend_train_bucket_range.argtypes = [vp, i32, i32, vp, i64, i32, i32, i64, i64, C.POINTER(legend_prefetch),
                                               C.POINTER(legend_bucket_stats)]
+    lib.legend_train_epoch.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(legend_epoch_stats)]
     lib.legend_score_edges.argtypes = [vp, vp, vp, vp, i64, vp]
     lib.legend_read_embeddings.argtypes = [vp, i32, vp, i64, vp]
     lib.legend_debug_batch_indices.argtypes = [vp, i32, i32, vp, i64, i32, i32, i64, vp, i64, vp, i64,
@@ -196,6 +202,25 @@ def legend_train_bucket_range(ctx, src_part: int, dst_part: int, edges, m: Optio
     if st is None:
         return None
     return dict(loss_sum=st.loss_sum, batches=st.batches, edges=st.edges, ms=st.ms)
+
+
+def legend_train_epoch(ctx, n: int, buckets, edges_mem: int = MEM_HOST, epoch: int = 0, overlap: bool = True):
+    """buckets: {(i, j): int32 [m,3] array} for MEM_HOST, or {(i, j): (device address, m)} for MEM_DEVICE."""
+    ptrs = (C.c_void_p * (n * n))()
+    sizes = (C.c_int64 * (n * n))()
+    keep = []
+    for (i, j), e in buckets.items():
+        if edges_mem == MEM_HOST:
+            a = _as(e, np.int32)
+            keep.append(a)
+            ptrs[i * n + j] = a.ctypes.data if a.shape[0] else None
+            sizes[i * n + j] = a.shape[0]
+        else:
+            ptrs[i * n + j] = int(e[0]) if e[1] else None
+            sizes[i * n + j] = int(e[1])
+    st = legend_epoch_stats()
+    _check(_lib.legend_train_epoch(ctx, ptrs, sizes, edges_mem, epoch, 1 if overlap else 0, C.byref(st)))
+    return {k: getattr(st, k) for k, _ in legend_epoch_stats._fields_}
 
 
 def legend_score_edges(ctx, src, rel, dst) -> np.ndarray:

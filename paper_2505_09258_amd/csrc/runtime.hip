@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -72,6 +73,7 @@ struct legend_ctx {
     double prof_ms[KC_COUNT] = {0};
     int64_t prof_launches[KC_COUNT] = {0};
     int64_t batches_done = 0;
+    bool keep_loss = false;                 // epoch driver: do not reset the device loss sum per bucket
     bool part_tables_dirty = false;         // d_part_emb / d_part_state lag behind part_slot
     bool fatal = false;
 };
@@ -581,7 +583,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         rc = do_swap(c, hint->evict, hint->load, true);
         if (rc) return rc;
     }
-    HIP_TRY(c, hipMemsetAsync(c->ws.loss_sum, 0, sizeof(double), c->compute));
+    if (!c->keep_loss) HIP_TRY(c, hipMemsetAsync(c->ws.loss_sum, 0, sizeof(double), c->compute));
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_t0, c->compute));
     const int B = c->cfg.batch_size;
     const int64_t nb = batch_end - batch_begin;
@@ -624,6 +626,85 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         stats->batches = nb;
         stats->edges = edges_done;
         stats->ms = ms;
+    }
+    return LEGEND_OK;
+}
+
+int legend_train_epoch(legend_ctx* c, const int32_t* const* bucket_edges, const int64_t* bucket_sizes, int32_t edges_mem,
+                       int32_t epoch, int32_t overlap, legend_epoch_stats* stats) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!bucket_edges || !bucket_sizes) return fail(LEGEND_E_INVAL, "NULL bucket table");
+    const int n = c->n;
+    for (int b = 0; b < n * n; ++b)
+        if (bucket_sizes[b] < 0 || (bucket_sizes[b] > 0 && !bucket_edges[b])) return fail(LEGEND_E_INVAL, "bucket %d: bad size or NULL edges", b);
+    if (c->cap < n && (c->cap != 3 || n <= 3))
+        return fail(LEGEND_E_INVAL, "an epoch needs buffer_capacity == num_partitions, or 3 with more than 3 partitions");
+
+    // plan: buffer states and bucket order (Sec. 4); with everything resident there is one state
+    std::vector<int32_t> states, buckets((size_t)n * n * 2), begin, over;
+    int32_t ns = 0;
+    {
+        int32_t cap_states = 8 * n * n + 8;
+        states.resize((size_t)cap_states * 3);
+        begin.resize(cap_states + 1);
+        over.resize(cap_states);
+        rc = legend_plan_order(n, states.data(), cap_states, &ns, buckets.data(), begin.data(), over.data());
+        if (rc) return fail(rc, "legend_plan_order failed");
+    }
+    const bool all_resident = c->cap >= n;
+    auto t_begin = std::chrono::steady_clock::now();
+    int64_t swaps = 0, edges = 0, batches = 0;
+
+    // bring the first state (or everything) into the buffer
+    std::vector<char> want(n, 0);
+    if (all_resident) std::fill(want.begin(), want.end(), 1);
+    else for (int s = 0; s < 3; ++s) if (states[s] >= 0) want[states[s]] = 1;
+    for (int p = 0; p < n; ++p)
+        if (!want[p] && c->part_slot[p] >= 0) { rc = do_swap(c, p, -1, true); if (rc) return rc; ++swaps; }
+    for (int p = 0; p < n; ++p)
+        if (want[p] && c->part_slot[p] < 0) { rc = do_swap(c, -1, p, true); if (rc) return rc; ++swaps; }
+
+    HIP_TRY(c, hipMemsetAsync(c->ws.loss_sum, 0, sizeof(double), c->compute));
+    c->keep_loss = true;
+    auto train = [&](int idx) -> int {
+        const int i = buckets[2 * idx], j = buckets[2 * idx + 1];
+        const int64_t m = bucket_sizes[i * n + j];
+        if (m == 0) return LEGEND_OK;
+        int r = legend_train_bucket_range(c, i, j, bucket_edges[i * n + j], m, edges_mem, epoch, 0, -1, nullptr, nullptr);
+        if (r == LEGEND_OK) { edges += m; batches += (m + c->cfg.batch_size - 1) / c->cfg.batch_size; }
+        return r;
+    };
+    rc = LEGEND_OK;
+    for (int k = 0; k < ns && rc == LEGEND_OK; ++k) {
+        int evict = -1, load = -1;
+        if (!all_resident && k + 1 < ns)
+            for (int s = 0; s < 3; ++s)
+                if (states[3 * k + s] != states[3 * (k + 1) + s]) { evict = states[3 * k + s]; load = states[3 * (k + 1) + s]; }
+        // buckets that involve the partition evicted next
+        for (int idx = begin[k]; idx < over[k] && rc == LEGEND_OK; ++idx) rc = train(idx);
+        if (rc) break;
+        // with prefetching the swap starts now and runs while the remaining buckets train (Sec. 4);
+        // without, it starts after them and the next state waits for it
+        if (evict >= 0 && overlap) { rc = do_swap(c, evict, load, true); if (rc) break; ++swaps; }
+        for (int idx = over[k]; idx < begin[k + 1] && rc == LEGEND_OK; ++idx) rc = train(idx);
+        if (rc) break;
+        if (evict >= 0 && !overlap) { rc = do_swap(c, evict, load, true); if (rc) break; ++swaps; }
+    }
+    c->keep_loss = false;
+    if (rc) return rc;
+    double loss = 0.0;
+    HIP_TRY(c, hipMemcpyAsync(&loss, c->ws.loss_sum, sizeof loss, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    if (stats) {
+        stats->loss_sum = loss;
+        stats->edges = edges;
+        stats->batches = batches;
+        stats->swaps = swaps;
+        stats->buffer_states = all_resident ? 1 : ns;
+        stats->bytes_per_swap = (int64_t)(c->part_floats * sizeof(float));
+        stats->ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     }
     return LEGEND_OK;
 }

@@ -264,6 +264,50 @@ def test_whole_epoch_with_swaps_follows_oracle():
         L.legend_destroy(ctx)
 
 
+def test_native_epoch_driver_matches_manual_order_and_oracle():
+    """legend_train_epoch: buffer of three, planner order, swaps with and without prefetching."""
+    from workloads import graphs
+    from oracle import order as oorder
+    w = graphs.Workload("mini7", 7_001, 0, 30_000, 20, 7, 500, 50, 80, 20, graphs.SCORE_DOT,
+                        src_skew=(0.9, 2.0), dst_skew=(0.9, 2.0))
+    src, rel_ids, dst = graphs.generate_edges(w, seed=5)
+    buckets = graphs.bucket_edges(w, src, rel_ids, dst)
+    buckets[(3, 3)] = np.zeros((0, 3), np.int32)          # an empty bucket is skipped
+    node, _ = graphs.init_tables(w, seed=5)
+    node *= 100
+    from paper_2505_09258_amd import binding as L
+    results = []
+    for overlap in (True, False):
+        cfg = L.make_config(num_nodes=w.num_nodes, dim=w.dim, num_partitions=7, buffer_capacity=3,
+                            batch_size=w.batch_size, chunk_size=w.chunk_size, num_negs=w.num_negs,
+                            num_degree_negs=w.num_degree_negs, seed=2)
+        ctx = L.legend_init_partitions(cfg, node, None)
+        try:
+            st = L.legend_train_epoch(ctx, 7, buckets, epoch=4, overlap=overlap)
+            E = L.legend_read_embeddings(ctx, L.TABLE_NODE_EMB, None, w.num_nodes, w.dim)
+            S = L.legend_read_embeddings(ctx, L.TABLE_NODE_STATE, None, w.num_nodes, w.dim)
+            results.append((st, E, S))
+        finally:
+            L.legend_destroy(ctx)
+    st, E, S = results[0]
+    states = oorder.loading_order(7)
+    assert st["buffer_states"] == len(states) and st["edges"] == sum(b.shape[0] for b in buckets.values())
+    assert st["swaps"] == 3 + (len(states) - 1)
+    # prefetching changes when copies run, not what is computed
+    assert results[1][0]["loss_sum"] == st["loss_sum"]
+    assert np.array_equal(results[1][1], E) and np.array_equal(results[1][2], S)
+    run = OracleRun(OracleConfig.from_workload(w, seed=2), node, None)
+    for (ev, ld, before, during) in oorder.iteration_order(states, 7):
+        for (i, j) in before + during:
+            if buckets[(i, j)].shape[0]:
+                run.train_bucket(i, j, buckets[(i, j)], epoch=4)
+    assert abs(st["loss_sum"] - run.loss) <= 1e-5 * abs(run.loss)
+    want_E = run.tab.node_table(0).astype(np.float64)
+    err = np.abs(E.astype(np.float64) - want_E)
+    strict = EMB_RTOL * np.maximum(np.abs(want_E), 0.1) + run.node_allowance(0)
+    assert (err <= strict).mean() >= 0.995 and (err <= 100 * strict).all()
+
+
 def test_error_paths_leave_tables_untouched():
     c = _case("err", DISTMULT, SOFTMAX, DST, 1_000, 4, 16, 2, 0, 1, 64, 8, 8, 0, 100, 0.2)
     node, rel, edges = _inputs(c)
