@@ -31,6 +31,46 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
+    """Whole epochs with edges in host memory and partitions staged through the HBM buffer."""
+    n = w.num_partitions
+    capacity = args.capacity if args.capacity else n
+    uses_rel = w.score != graphs.SCORE_DOT
+    cfg = L.make_config(num_nodes=w.num_nodes, dim=w.dim, num_partitions=n, buffer_capacity=capacity,
+                        num_relations=w.num_relations, score=w.score, loss=w.loss, corrupt=w.corrupt,
+                        batch_size=w.batch_size, chunk_size=w.chunk_size, num_negs=w.num_negs,
+                        num_degree_negs=w.num_degree_negs, lr=w.lr, eps=w.eps, seed=args.seed,
+                        update_mode=L.UPDATE_ATOMIC if args.update_mode == "atomic" else L.UPDATE_DETERMINISTIC)
+    ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
+    K, W = max(args.steps, 1), args.warmup
+    stats = None
+    for ep in range(W):
+        L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=not args.no_overlap)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    edges = 0
+    for ep in range(W, W + K):
+        stats = L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=not args.no_overlap)
+        edges += stats["edges"]
+    L.legend_sync(ctx)
+    wall = time.perf_counter() - t0
+    out = {
+        "metric": "edges/sec trained (1 GPU)", "value": round(edges / wall, 1), "unit": "edges/s", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": round(wall * 1e3 / K, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
+                               f"{n} partitions, B={w.batch_size}, C={w.chunk_size}, N={w.num_negs}, sides={w.sides}, "
+                               f"score={['dot', 'distmult', 'complex'][w.score]}; one step = one epoch, edges in host memory",
+                   "update_mode": args.update_mode, "resident_partitions": capacity,
+                   "prefetch": not args.no_overlap},
+        "epoch": {"batches": stats["batches"], "swaps": stats["swaps"], "buffer_states": stats["buffer_states"],
+                  "bytes_per_swap": stats["bytes_per_swap"], "loss_sum": stats["loss_sum"]},
+    }
+    L.legend_destroy(ctx)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +82,12 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-batches", type=int, default=1)
     ap.add_argument("--profile-only", action="store_true", help="skip the CPU baseline and the per-kernel pass")
+    ap.add_argument("--update-mode", choices=["deterministic", "atomic"], default="deterministic")
+    ap.add_argument("--epoch", action="store_true",
+                    help="time whole epochs through legend_train_epoch (host-resident edges, partition swaps) "
+                         "instead of K resident batches; --steps then counts epochs")
+    ap.add_argument("--capacity", type=int, default=0, help="buffer slots for --epoch (0: all partitions resident)")
+    ap.add_argument("--no-overlap", action="store_true", help="--epoch: serialize swaps (the paper's 'without prefetching')")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -71,6 +117,8 @@ def main() -> int:
     log(f"[bench] generated {w.name}: {w.num_nodes} nodes, {w.num_edges} edges, {len(buckets)} buckets in {time.time() - t0:.1f}s")
 
     torch.cuda.set_device(0)
+    if args.epoch:
+        return run_epochs(args, w, buckets, node, rel, L, graphs, torch)
     stream = torch.cuda.Stream()
     n = w.num_partitions
     capacity = n if 2 * w.num_nodes * w.dim * 4 < 64e9 else 3
@@ -78,6 +126,7 @@ def main() -> int:
                         num_relations=w.num_relations, score=w.score, loss=w.loss, corrupt=w.corrupt,
                         batch_size=w.batch_size, chunk_size=w.chunk_size, num_negs=w.num_negs,
                         num_degree_negs=w.num_degree_negs, lr=w.lr, eps=w.eps, seed=args.seed,
+                        update_mode=L.UPDATE_ATOMIC if args.update_mode == "atomic" else L.UPDATE_DETERMINISTIC,
                         compute_stream=stream.cuda_stream)
     uses_rel = w.score != graphs.SCORE_DOT
     ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
@@ -230,7 +279,7 @@ def main() -> int:
         "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
                                f"{n} partitions, B={B}, C={w.chunk_size}, N={w.num_negs} ({w.num_degree_negs} degree-weighted), "
                                f"sides={sides}, score={['dot', 'distmult', 'complex'][w.score]}",
-                   "update_mode": "deterministic", "resident_partitions": capacity},
+                   "update_mode": args.update_mode, "resident_partitions": capacity},
         "device_ms_per_step": round(dev_ms / K, 4),
         "algorithmic_bytes_per_step": int(alg_bytes), "unique_rows_per_step": round(u_b),
         "hbm_GBs_whole_step": round(alg_bytes / (wall / K) / 1e9, 1), "copy_GBs_measured": round(copy_gbs, 1),

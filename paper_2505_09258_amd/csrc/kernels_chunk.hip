@@ -441,20 +441,39 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             }
         }
         __syncthreads();
+        if (bp.atomic_mode) {
+            // atomic mode: add the rows to the accumulator of the negatives' table
+            float* Gn = side == 0 ? bp.G_dst : bp.G_src;
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const int rt = w * 16 + s * RPS + grow_lane;
-            const int neg = n0 + rt;
-            if (neg < N && gc0 < d) {
-                const float* src = Ns + rt * QS + gc0;
-                float* dst = grad + (neg_base + neg) * d + gc0;
-                if (vec4) {
-                    *reinterpret_cast<float4*>(dst) = lds4(src);
-                } else {
-                    dst[0] = src[0];
-                    if (gc0 + 1 < d) dst[1] = src[1];
-                    if (gc0 + 2 < d) dst[2] = src[2];
-                    if (gc0 + 3 < d) dst[3] = src[3];
+            for (int s = 0; s < STEPS; ++s) {
+                const int rt = w * 16 + s * RPS + grow_lane;
+                const int neg = n0 + rt;
+                if (neg < N && gc0 < d) {
+                    const int32_t id = neg < kIdsLds ? ids_s[neg] : my_negs[neg];
+                    const float* src = Ns + rt * QS + gc0;
+                    float* dst = Gn + (int64_t)id * d + gc0;
+                    unsafeAtomicAdd(dst, src[0]);
+                    if (gc0 + 1 < d) unsafeAtomicAdd(dst + 1, src[1]);
+                    if (gc0 + 2 < d) unsafeAtomicAdd(dst + 2, src[2]);
+                    if (gc0 + 3 < d) unsafeAtomicAdd(dst + 3, src[3]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const int rt = w * 16 + s * RPS + grow_lane;
+                const int neg = n0 + rt;
+                if (neg < N && gc0 < d) {
+                    const float* src = Ns + rt * QS + gc0;
+                    float* dst = grad + (neg_base + neg) * d + gc0;
+                    if (vec4) {
+                        *reinterpret_cast<float4*>(dst) = lds4(src);
+                    } else {
+                        dst[0] = src[0];
+                        if (gc0 + 1 < d) dst[1] = src[1];
+                        if (gc0 + 2 < d) dst[2] = src[2];
+                        if (gc0 + 3 < d) dst[3] = src[3];
+                    }
                 }
             }
         }
@@ -469,6 +488,11 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
 
     // ---- epilogue: G_Q to LDS, chain rule, gradient rows of the positives -------------------
     float* Gs = Ns;
+    const bool atomic = bp.atomic_mode != 0;
+    auto emit = [&](float* p, float v) {
+        if (atomic) unsafeAtomicAdd(p, v);
+        else *p = v;
+    };
     if (active) {
 #pragma unroll
         for (int j = 0; j < NBW; ++j) {
@@ -499,6 +523,11 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             float* gx = grad + (side_base + (side == 0 ? 0 : g.P) + e) * d;        // source rows first
             float* gy = grad + (side_base + (side == 0 ? g.P : 0) + e) * d;
             float* gr = grad + (side_base + 2 * (int64_t)g.P + e) * d;
+            if (atomic) {                     // straight into the per-table gradient accumulators
+                gx = (side == 0 ? bp.G_src : bp.G_dst) + (int64_t)eb[prow * 3 + xcol] * d;
+                gy = (side == 0 ? bp.G_dst : bp.G_src) + (int64_t)eb[prow * 3 + ycol] * d;
+                gr = bp.G_rel + (int64_t)eb[prow * 3 + 1] * d;
+            }
             const float* gq = Gs + prow * QS;
             const float* q = Qs + prow * QS;
             if (SCORE == LEGEND_SCORE_COMPLEX) {
@@ -506,25 +535,25 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                 for (int k = ppart; k < h; k += 4) {
                     float gre = gq[k] + a * y[k], gim = gq[k + h] + a * y[k + h];
                     float xr = x[k], xi = x[k + h], rr = r[k], ri = r[k + h];
-                    gy[k] = a * q[k];
-                    gy[k + h] = a * q[k + h];
+                    emit(gy + k, a * q[k]);
+                    emit(gy + k + h, a * q[k + h]);
                     if (side == 0) {
-                        gx[k] = rr * gre + ri * gim;      gx[k + h] = rr * gim - ri * gre;   // conj(r) g
-                        gr[k] = xr * gre + xi * gim;      gr[k + h] = xr * gim - xi * gre;   // conj(x) g
+                        emit(gx + k, rr * gre + ri * gim);      emit(gx + k + h, rr * gim - ri * gre);   // conj(r) g
+                        emit(gr + k, xr * gre + xi * gim);      emit(gr + k + h, xr * gim - xi * gre);   // conj(x) g
                     } else {
-                        gx[k] = rr * gre - ri * gim;      gx[k + h] = rr * gim + ri * gre;   // r g
-                        gr[k] = gre * xr + gim * xi;      gr[k + h] = gre * xi - gim * xr;   // conj(g) x
+                        emit(gx + k, rr * gre - ri * gim);      emit(gx + k + h, rr * gim + ri * gre);   // r g
+                        emit(gr + k, gre * xr + gim * xi);      emit(gr + k + h, gre * xi - gim * xr);   // conj(g) x
                     }
                 }
             } else {
                 for (int k = ppart; k < d; k += 4) {
                     float gv = gq[k] + a * y[k];
-                    gy[k] = a * q[k];
+                    emit(gy + k, a * q[k]);
                     if (SCORE == LEGEND_SCORE_DOT) {
-                        gx[k] = gv;
+                        emit(gx + k, gv);
                     } else {
-                        gx[k] = r[k] * gv;
-                        gr[k] = x[k] * gv;
+                        emit(gx + k, r[k] * gv);
+                        emit(gr + k, x[k] * gv);
                     }
                 }
             }

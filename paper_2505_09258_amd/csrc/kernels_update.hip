@@ -259,6 +259,59 @@ hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams&
     return launch_update_lpr<64>(st, g, bp, ws, sorted_vals, tb);
 }
 
+// Atomic mode: the batch gradient of every table row already sits in a dense fp32 accumulator
+// (summed by hardware float atomics in arrival order); one group per unique row applies
+// Adagrad and clears the accumulator row for the next batch.
+template <int LPR>
+__global__ void __launch_bounds__(256)
+k_update_atomic(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys, UpdateTables tb,
+                float* G0, float* G1, float* G2, int d, float lr, float eps) {
+    const int groups_per_block = 256 / LPR;
+    const int gl = threadIdx.x / LPR;
+    const int col4 = threadIdx.x % LPR;
+    const int c0 = col4 * 4;
+    const bool vec4 = (d & 3) == 0;
+    const uint32_t n_unique = counters[0];
+    for (uint32_t u = blockIdx.x * groups_per_block + gl; u < n_unique; u += gridDim.x * groups_per_block) {
+        if (c0 >= d) continue;
+        const uint32_t key = uniq_keys[u];
+        const int t = table_of_key(tb, key);
+        const int64_t row = (int64_t)(key - tb.key_base[t]);
+        float* gp = (t == 0 ? G0 : t == 1 ? G1 : G2) + row * d + c0;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        if (vec4) {
+            const float4 v = *reinterpret_cast<const float4*>(gp);
+            acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+            *reinterpret_cast<float4*>(gp) = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            for (int j = 0; j < 4 && c0 + j < d; ++j) { acc[j] = gp[j]; gp[j] = 0.f; }
+        }
+        apply_row(tb, key, acc, d, c0, vec4, lr, eps);
+    }
+}
+
+hipError_t launch_update_atomic(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    if (g.n_occ <= 0) return hipSuccess;
+    UpdateTables tb;
+    tb.E[0] = bp.E_src; tb.S[0] = bp.S_src;
+    tb.E[1] = bp.E_dst; tb.S[1] = bp.S_dst;
+    tb.E[2] = bp.E_rel; tb.S[2] = bp.S_rel;
+    tb.key_base[0] = 0; tb.key_base[1] = bp.key_base_dst; tb.key_base[2] = bp.key_base_rel;
+    const int d = bp.dim;
+    const int lpr = d <= 32 ? 8 : d <= 64 ? 16 : d <= 128 ? 32 : 64;
+    const int groups = 256 / lpr;
+    int64_t blocks = (g.n_occ + groups - 1) / groups;
+    if (blocks > 8192) blocks = 8192;
+    dim3 grid((unsigned)blocks), block(256);
+    switch (lpr) {
+        case 8:  hipLaunchKernelGGL(k_update_atomic<8>, grid, block, 0, st, ws.counters, ws.uniq_keys, tb, bp.G_src, bp.G_dst, bp.G_rel, d, bp.lr, bp.eps); break;
+        case 16: hipLaunchKernelGGL(k_update_atomic<16>, grid, block, 0, st, ws.counters, ws.uniq_keys, tb, bp.G_src, bp.G_dst, bp.G_rel, d, bp.lr, bp.eps); break;
+        case 32: hipLaunchKernelGGL(k_update_atomic<32>, grid, block, 0, st, ws.counters, ws.uniq_keys, tb, bp.G_src, bp.G_dst, bp.G_rel, d, bp.lr, bp.eps); break;
+        default: hipLaunchKernelGGL(k_update_atomic<64>, grid, block, 0, st, ws.counters, ws.uniq_keys, tb, bp.G_src, bp.G_dst, bp.G_rel, d, bp.lr, bp.eps); break;
+    }
+    return hipGetLastError();
+}
+
 // ---- f(theta_s, theta_r, theta_d) for global ids: one wavefront per triple ------------------
 __global__ void __launch_bounds__(256)
 k_score(const int64_t* __restrict__ src, const int32_t* __restrict__ rel, const int64_t* __restrict__ dst,

@@ -47,6 +47,8 @@ struct BucketParams {
     float* E_src; float* S_src;   // slot of partition i
     float* E_dst; float* S_dst;   // slot of partition j
     float* E_rel; float* S_rel;   // relation table
+    float* G_src; float* G_dst; float* G_rel;   // atomic mode: dense gradient accumulators (zero between batches)
+    int32_t atomic_mode;
     int32_t rows_valid_src;    // valid rows of partition i
     int32_t rows_valid_dst;
     int32_t num_relations;
@@ -91,6 +93,7 @@ hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_key
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, int32_t rows_per_partition);
+hipError_t launch_update_atomic(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_loss_reduce(hipStream_t st, int64_t nwg, const Workspace& ws);
 hipError_t launch_score(hipStream_t st, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m,
                         float* const* part_emb, int32_t rows_per_partition, int32_t num_partitions,

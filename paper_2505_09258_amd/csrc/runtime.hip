@@ -50,6 +50,8 @@ struct legend_ctx {
     bool uses_rel = false;
     std::vector<float*> host_part;          // pinned [E_p | S_p]
     std::vector<float*> slot_mem;           // device [E | S]
+    std::vector<float*> slot_grad;          // atomic mode: device gradient accumulator per slot [Rp * d]
+    float* G_rel = nullptr;
     std::vector<int> slot_part, part_slot;
     std::vector<hipEvent_t> slot_ready;
     std::vector<char> slot_pending;
@@ -233,6 +235,8 @@ void free_ctx(legend_ctx* c) {
     if (c->copy) (void)hipStreamSynchronize(c->copy);
     for (float* p : c->host_part) if (p) (void)hipHostFree(p);
     for (float* p : c->slot_mem) if (p) (void)hipFree(p);
+    for (float* p : c->slot_grad) if (p) (void)hipFree(p);
+    if (c->G_rel) (void)hipFree(c->G_rel);
     for (hipEvent_t e : c->slot_ready) if (e) (void)hipEventDestroy(e);
     for (auto& s : c->prof_spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
@@ -318,6 +322,8 @@ int bucket_params(legend_ctx* c, int i, int j, const int32_t* dev_edges, int64_t
     p.E_src = c->slot_mem[si]; p.S_src = c->slot_mem[si] + half;
     p.E_dst = c->slot_mem[sj]; p.S_dst = c->slot_mem[sj] + half;
     p.E_rel = c->E_rel; p.S_rel = c->S_rel;
+    p.atomic_mode = c->cfg.update_mode == LEGEND_UPDATE_ATOMIC ? 1 : 0;
+    p.G_src = c->slot_grad[si]; p.G_dst = c->slot_grad[sj]; p.G_rel = c->G_rel;
     p.rows_valid_src = (int32_t)rows_valid(c, i);
     p.rows_valid_dst = (int32_t)rows_valid(c, j);
     p.num_relations = c->cfg.num_relations;
@@ -378,8 +384,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "dim %d is above the supported maximum %d", cfg->dim, max_dim_supported());
     if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 1 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
-    if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC)
-        return fail(LEGEND_E_INVAL, "update_mode %d is not available", cfg->update_mode);
+    if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)
+        return fail(LEGEND_E_INVAL, "unknown update_mode %d", cfg->update_mode);
     if (cfg->score == LEGEND_SCORE_COMPLEX && (cfg->dim & 1)) return fail(LEGEND_E_INVAL, "ComplEx needs an even dim");
     if (cfg->score != LEGEND_SCORE_DOT && cfg->num_relations < 1)
         return fail(LEGEND_E_INVAL, "this score function needs num_relations >= 1");
@@ -410,6 +416,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     c->nrel_rows = std::max(cfg->num_relations, 1);
     c->host_part.assign(c->n, nullptr);
     c->slot_mem.assign(c->cap, nullptr);
+    c->slot_grad.assign(c->cap, nullptr);
     c->slot_part.assign(c->cap, -1);
     c->part_slot.assign(c->n, -1);
     c->slot_ready.assign(c->cap, nullptr);
@@ -459,11 +466,19 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     for (int s = 0; s < c->cap; ++s) {
         INIT_RC(dev_alloc(c, &c->slot_mem[s], c->part_floats));
         INIT_TRY(hipEventCreateWithFlags(&c->slot_ready[s], hipEventDisableTiming));
+        if (cfg->update_mode == LEGEND_UPDATE_ATOMIC) {
+            INIT_RC(dev_alloc(c, &c->slot_grad[s], (size_t)Rp * c->d));
+            INIT_TRY(hipMemset(c->slot_grad[s], 0, (size_t)Rp * c->d * sizeof(float)));
+        }
     }
     const size_t rel_floats = (size_t)c->nrel_rows * c->d;
     INIT_RC(dev_alloc(c, &c->E_rel, rel_floats));
     INIT_RC(dev_alloc(c, &c->S_rel, rel_floats));
     INIT_TRY(hipMemset(c->S_rel, 0, rel_floats * sizeof(float)));
+    if (cfg->update_mode == LEGEND_UPDATE_ATOMIC) {
+        INIT_RC(dev_alloc(c, &c->G_rel, rel_floats));
+        INIT_TRY(hipMemset(c->G_rel, 0, rel_floats * sizeof(float)));
+    }
     if (init_rel_emb) INIT_TRY(hipMemcpy(c->E_rel, init_rel_emb, rel_floats * sizeof(float), hipMemcpyHostToDevice));
     else INIT_TRY(hipMemset(c->E_rel, 0, rel_floats * sizeof(float)));
     INIT_RC(dev_alloc(c, &c->d_part_emb, (size_t)c->n));
@@ -607,7 +622,8 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         }
         {
             ProfScope ps(c, KC_UPDATE);
-            HIP_TRY(c, launch_update(c->compute, g, bp, c->ws, c->ws.vals[sorted], (int32_t)c->Rp));
+            if (bp.atomic_mode) HIP_TRY(c, launch_update_atomic(c->compute, g, bp, c->ws));
+            else HIP_TRY(c, launch_update(c->compute, g, bp, c->ws, c->ws.vals[sorted], (int32_t)c->Rp));
         }
         c->batches_done += 1;
     }
