@@ -14,61 +14,24 @@
 // Wavefronts are 64 wide: a 64x64 score tile is four 32x32 MFMA blocks, one per wave.
 #include <type_traits>
 
-#include "legend_internal.h"
-#include "device_utils.h"
+#include "chunk_common.h"
 
 namespace legend {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int kChunkThreads = 256;
 constexpr int kRowTile = 64;    // positives per workgroup (padded)
 constexpr int kNegTile = 64;    // negatives per LDS tile
 constexpr int kWS = kNegTile + 4;   // row stride of the W tile: a multiple of 4 that is 4 mod 8
-constexpr int kIdsLds = 1024;   // negative ids of a chunk kept in LDS (more than that: read from global)
 
-int row_tiles_for(int chunk_size) { return (chunk_size + kRowTile - 1) / kRowTile; }
-int rows_per_tile_for(int chunk_size) {
-    int t = row_tiles_for(chunk_size);
+int row_tiles_for(int chunk_size, int dim) {
+    const int tile = dim > kNarrowMaxDim ? kWideRowTile : kRowTile;
+    return (chunk_size + tile - 1) / tile;
+}
+int rows_per_tile_for(int chunk_size, int dim) {
+    int t = row_tiles_for(chunk_size, dim);
     return (chunk_size + t - 1) / t;
 }
-int max_dim_supported() { return 128; }
-
-// LDS row stride of the Q and negative tiles: dim rounded up to 8, plus 4.  It is a multiple
-// of 4 (rows stay 16-byte aligned for 128-bit LDS accesses) and 4 mod 8 (32 rows read at the
-// same column fall into distinct bank groups).
-__host__ __device__ inline int chunk_row_stride(int d) { return ((d + 7) & ~7) + 4; }
-
-__device__ inline f32x16 mfma32(float a, float b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
-}
-
-__device__ inline float softplusf(float x) {
-    // log(1 + exp(x)) without overflow
-    return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
-}
-__device__ inline float sigmoidf(float x) { return 1.f / (1.f + expf(-x)); }
-
-// exp(x) for finite x from the hardware 2^x instruction: the product x * log2(e) is formed in
-// two pieces (head, and rounding error + low part of the constant) so that the result is good
-// to about two ulp for any magnitude of x, at six VALU instructions.
-__device__ inline float fast_exp(float x) {
-    const float L2E_HI = 1.44269502162933349609375f;
-    const float L2E_LO = 1.925963033500011e-8f;
-    const float hi = x * L2E_HI;
-    float lo = fmaf(x, L2E_HI, -hi);
-    lo = fmaf(x, L2E_LO, lo);
-    const float r = __builtin_amdgcn_exp2f(hi);
-    return fmaf(r, lo * 0.6931471805599453f, r);
-}
-
-__device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-
-// MFMA operand mapping used everywhere below: the contraction index runs in groups of 8;
-// in a group the lanes 0-31 (kk = 0) supply k = 8g + s and lanes 32-63 (kk = 1) supply
-// k = 8g + 4 + s to the s-th of four consecutive 32x32x2 MFMAs (s = 0..3).  Both operands
-// use the same mapping, so the sum over k is complete and every lane can fetch its four
-// values of a row-major operand with one 128-bit LDS read.
+int max_dim_supported() { return kWideMaxDim; }
+bool dim_supported(int dim) { return dim >= 1 && (dim <= kNarrowMaxDim || (dim <= kWideMaxDim && dim % 4 == 0)); }
 
 // NB: number of 32-wide column blocks covering the embedding dimension (dim <= 32 * NB).
 // DFIX: the embedding dimension when it is known at compile time (strides, trip counts and
@@ -611,7 +574,7 @@ hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams&
     if (bp.dim <= 32) return launch_chunks_nb<1, 0>(st, g, bp, ws);
     if (bp.dim <= 64) return launch_chunks_nb<2, 0>(st, g, bp, ws);
     if (bp.dim <= 128) return launch_chunks_nb<4, 0>(st, g, bp, ws);
-    return hipErrorInvalidValue;
+    return launch_chunks_wide(st, g, bp, ws);
 }
 
 // Sum of the per-workgroup losses in a fixed order, added to the running bucket loss.

@@ -109,10 +109,11 @@ k_update(uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys
             if (col4 == 0) long_list[atomicAdd(&counters[2], 1u)] = u;
             continue;
         }
-        if (c0 >= d) continue;
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        sum_rows(grad, sorted_vals, lo, hi, d, c0, vec4, acc);
-        apply_row(tb, uniq_keys[u], acc, d, c0, vec4, lr, eps);
+        for (int cc = c0; cc < d; cc += 4 * LPR) {     // rows wider than 4*LPR floats take several passes
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            sum_rows(grad, sorted_vals, lo, hi, d, cc, vec4, acc);
+            apply_row(tb, uniq_keys[u], acc, d, cc, vec4, lr, eps);
+        }
     }
 }
 
@@ -180,19 +181,22 @@ k_long_partial(const uint32_t* __restrict__ counters, const uint32_t* __restrict
         const uint32_t seg_lo = seg_start[u], seg_hi = seg_start[u + 1];
         const uint32_t lo = seg_lo + (unit - unit_start[a]) * kUnit + gl * PER_GROUP;
         const uint32_t hi = min(seg_hi, lo + PER_GROUP);
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        if (c0 < d && lo < hi) sum_rows(grad, sorted_vals, lo, hi, d, c0, vec4, acc);
+        for (int cbase = 0; cbase < d; cbase += 4 * LPR) {     // uniform trip count across the block
+            const int cc = cbase + c0;
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            if (cc < d && lo < hi) sum_rows(grad, sorted_vals, lo, hi, d, cc, vec4, acc);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) psum[(gl * LPR + col4) * 4 + j] = acc[j];
-        __syncthreads();
-        if (gl == 0 && c0 < d) {
-            double tot[4] = {0.0, 0.0, 0.0, 0.0};
-            for (int gq = 0; gq < GROUPS; ++gq)
+            for (int j = 0; j < 4; ++j) psum[(gl * LPR + col4) * 4 + j] = acc[j];
+            __syncthreads();
+            if (gl == 0 && cc < d) {
+                double tot[4] = {0.0, 0.0, 0.0, 0.0};
+                for (int gq = 0; gq < GROUPS; ++gq)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) tot[j] += psum[(gq * LPR + col4) * 4 + j];
-            for (int j = 0; j < 4 && c0 + j < d; ++j) partial[(int64_t)unit * d + c0 + j] = tot[j];
+                    for (int j = 0; j < 4; ++j) tot[j] += psum[(gq * LPR + col4) * 4 + j];
+                for (int j = 0; j < 4 && cc + j < d; ++j) partial[(int64_t)unit * d + cc + j] = tot[j];
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
@@ -209,13 +213,14 @@ k_long_final(const uint32_t* __restrict__ counters, const uint32_t* __restrict__
     const bool vec4 = (d & 3) == 0;
     const uint32_t n_long = counters[2];
     for (uint32_t r = blockIdx.x * groups_per_block + gl; r < n_long; r += gridDim.x * groups_per_block) {
-        if (c0 >= d) continue;
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        for (uint32_t unit = unit_start[r]; unit < unit_start[r + 1]; ++unit) {
-            const double* pp = partial + (int64_t)unit * d + c0;
-            for (int j = 0; j < 4 && c0 + j < d; ++j) acc[j] += pp[j];
+        for (int cc = c0; cc < d; cc += 4 * LPR) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            for (uint32_t unit = unit_start[r]; unit < unit_start[r + 1]; ++unit) {
+                const double* pp = partial + (int64_t)unit * d + cc;
+                for (int j = 0; j < 4 && cc + j < d; ++j) acc[j] += pp[j];
+            }
+            apply_row(tb, uniq_keys[long_list[r]], acc, d, cc, vec4, lr, eps);
         }
-        apply_row(tb, uniq_keys[long_list[r]], acc, d, c0, vec4, lr, eps);
     }
 }
 
@@ -273,20 +278,21 @@ k_update_atomic(const uint32_t* __restrict__ counters, const uint32_t* __restric
     const bool vec4 = (d & 3) == 0;
     const uint32_t n_unique = counters[0];
     for (uint32_t u = blockIdx.x * groups_per_block + gl; u < n_unique; u += gridDim.x * groups_per_block) {
-        if (c0 >= d) continue;
         const uint32_t key = uniq_keys[u];
         const int t = table_of_key(tb, key);
         const int64_t row = (int64_t)(key - tb.key_base[t]);
-        float* gp = (t == 0 ? G0 : t == 1 ? G1 : G2) + row * d + c0;
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        if (vec4) {
-            const float4 v = *reinterpret_cast<const float4*>(gp);
-            acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
-            *reinterpret_cast<float4*>(gp) = make_float4(0.f, 0.f, 0.f, 0.f);
-        } else {
-            for (int j = 0; j < 4 && c0 + j < d; ++j) { acc[j] = gp[j]; gp[j] = 0.f; }
+        for (int cc = c0; cc < d; cc += 4 * LPR) {
+            float* gp = (t == 0 ? G0 : t == 1 ? G1 : G2) + row * d + cc;
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            if (vec4) {
+                const float4 v = *reinterpret_cast<const float4*>(gp);
+                acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+                *reinterpret_cast<float4*>(gp) = make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                for (int j = 0; j < 4 && cc + j < d; ++j) { acc[j] = gp[j]; gp[j] = 0.f; }
+            }
+            apply_row(tb, key, acc, d, cc, vec4, lr, eps);
         }
-        apply_row(tb, key, acc, d, c0, vec4, lr, eps);
     }
 }
 

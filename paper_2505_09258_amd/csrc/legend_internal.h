@@ -105,8 +105,9 @@ hipError_t launch_gather_rows(hipStream_t st, const int64_t* ids, int64_t m, flo
 
 int64_t update_long_rows_capacity(int64_t n_occ);
 int64_t update_long_units_capacity(int64_t n_occ);
-int row_tiles_for(int chunk_size);          // T
-int rows_per_tile_for(int chunk_size);      // ceil(C / T)
+int row_tiles_for(int chunk_size, int dim);          // T
+int rows_per_tile_for(int chunk_size, int dim);      // ceil(C / T)
 int max_dim_supported();
+bool dim_supported(int dim);
 
 }  // namespace legend

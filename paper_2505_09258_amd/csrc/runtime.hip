@@ -103,8 +103,8 @@ BatchGeom make_geom(const legend_ctx* c, int P) {
     g.P = P;
     g.C = cf.chunk_size;
     g.N = cf.num_negs;
-    g.T = row_tiles_for(cf.chunk_size);
-    g.rows_tile = rows_per_tile_for(cf.chunk_size);
+    g.T = row_tiles_for(cf.chunk_size, c->d);
+    g.rows_tile = rows_per_tile_for(cf.chunk_size, c->d);
     g.nchunks = (P + g.C - 1) / g.C;
     g.sides = cf.corrupt == LEGEND_CORRUPT_BOTH ? 2 : 1;
     g.side_id[0] = cf.corrupt == LEGEND_CORRUPT_SRC ? 1 : 0;
@@ -380,8 +380,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "legend_config.struct_size is %u, library expects %zu", cfg->struct_size, sizeof(legend_config));
     if (cfg->num_nodes < 1 || cfg->dim < 1 || cfg->num_partitions < 1 || cfg->num_partitions > cfg->num_nodes)
         return fail(LEGEND_E_INVAL, "num_nodes, dim, num_partitions must be positive and num_partitions <= num_nodes");
-    if (cfg->dim > max_dim_supported())
-        return fail(LEGEND_E_INVAL, "dim %d is above the supported maximum %d", cfg->dim, max_dim_supported());
+    if (!dim_supported(cfg->dim))
+        return fail(LEGEND_E_INVAL, "dim %d is not supported (1..128, or a multiple of 4 up to %d)", cfg->dim, max_dim_supported());
     if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 1 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
     if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)

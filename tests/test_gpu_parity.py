@@ -31,6 +31,10 @@ CASES = [
     _case("distmult_d6", DISTMULT, SOFTMAX, BOTH, 500, 3, 6, 2, 0, 1, 64, 7, 5, 2, 130, 0.5),
     _case("dot_d70_single_negative", DOT, SOFTMAX, DST, 900, 0, 70, 1, 0, 0, 100, 1, 1, 0, 150, 0.3),
     _case("complex_d34", COMPLEX, SOFTMAX, DST, 900, 4, 34, 1, 0, 0, 120, 33, 65, 0, 250, 0.4),
+    # dimensions above 128 take the wide kernel (32-row tiles, contraction split across waves)
+    _case("distmult_d400_both", DISTMULT, SOFTMAX, BOTH, 3_000, 45, 400, 1, 0, 0, 400, 100, 130, 0, 900, 0.15),
+    _case("complex_d132_offdiag", COMPLEX, SOFTMAX, BOTH, 2_000, 7, 132, 2, 1, 0, 150, 40, 33, 8, 320, 0.3),
+    _case("dot_d512_logistic", DOT, LOGISTIC, SRC, 800, 0, 512, 1, 0, 0, 96, 32, 64, 0, 200, 0.1),
 ]
 
 
@@ -142,7 +146,10 @@ def test_every_batch_matches_oracle(c):
         L.legend_destroy(ctx)
 
 
-@pytest.mark.parametrize("c", CASES[:5] + CASES[6:7], ids=[c["name"] for c in CASES[:5] + CASES[6:7]])
+_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11]
+
+
+@pytest.mark.parametrize("c", _ATOMIC_CASES, ids=[c["name"] for c in _ATOMIC_CASES])
 def test_atomic_mode_every_batch_matches_oracle(c):
     """The atomic update mode computes the same batch step; its gradient sums are fp32 in
     arrival order instead of fp64 in a fixed order, so the rounding allowance is four times
