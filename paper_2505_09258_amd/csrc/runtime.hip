@@ -62,6 +62,8 @@ struct legend_ctx {
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
     hipEvent_t ev_fence = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
+    hipStream_t aux = nullptr;              // sorts the batch's keys while the chunk kernel runs
+    hipEvent_t ev_keys = nullptr, ev_sorted = nullptr;
     Workspace ws{};
     BatchGeom gmax{};
     int key_bits = 0;
@@ -130,17 +132,18 @@ hipEvent_t prof_event(legend_ctx* c) {
 struct ProfScope {
     legend_ctx* c;
     int cls;
+    hipStream_t st;
     hipEvent_t a = nullptr, b = nullptr;
-    ProfScope(legend_ctx* ctx, int k) : c(ctx), cls(k) {
+    ProfScope(legend_ctx* ctx, int k, hipStream_t stream = nullptr) : c(ctx), cls(k), st(stream ? stream : ctx->compute) {
         if (c->prof_mask & (1u << cls)) {
             a = prof_event(c);
             b = prof_event(c);
-            if (a && b) (void)hipEventRecord(a, c->compute);
+            if (a && b) (void)hipEventRecord(a, st);
         }
     }
     ~ProfScope() {
         if (a && b) {
-            (void)hipEventRecord(b, c->compute);
+            (void)hipEventRecord(b, st);
             c->prof_spans.push_back({cls, a, b});
         }
     }
@@ -245,6 +248,9 @@ void free_ctx(legend_ctx* c) {
                      c->ws.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.loss_sum, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
+    if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
+    if (c->ev_keys) (void)hipEventDestroy(c->ev_keys);
+    if (c->ev_sorted) (void)hipEventDestroy(c->ev_sorted);
     if (c->ev_fence) (void)hipEventDestroy(c->ev_fence);
     if (c->ev_t0) (void)hipEventDestroy(c->ev_t0);
     if (c->ev_t1) (void)hipEventDestroy(c->ev_t1);
@@ -351,16 +357,26 @@ uint64_t batch_hash_prefix(const legend_ctx* c, int epoch, int i, int j, int64_t
 }
 
 // index side of one batch: negatives, keys, sort, segment heads
-int enqueue_index_side(legend_ctx* c, const BatchGeom& g, const BucketParams& bp, int* sorted_buf) {
+// `side_stream`: sort on the auxiliary stream; the caller orders the update after ev_sorted.
+// The sort depends only on the keys, the chunk kernel only on the negative ids, so the two run
+// side by side (the chunk kernel is MFMA/LDS-bound, the sort a chain of small memory-bound kernels).
+int enqueue_index_side(legend_ctx* c, const BatchGeom& g, const BucketParams& bp, int* sorted_buf, bool side_stream) {
     {
         ProfScope ps(c, KC_PREPARE);
         HIP_TRY(c, launch_prepare(c->compute, g, bp, c->ws));
     }
-    {
-        ProfScope ps(c, KC_SORT);
-        HIP_TRY(c, launch_sort(c->compute, g.n_occ, c->key_bits, c->ws, sorted_buf));
-        HIP_TRY(c, launch_segments(c->compute, g.n_occ, c->ws.keys[*sorted_buf], c->ws));
+    hipStream_t st = c->compute;
+    if (side_stream) {
+        HIP_TRY(c, hipEventRecord(c->ev_keys, c->compute));
+        HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_keys, 0));
+        st = c->aux;
     }
+    {
+        ProfScope ps(c, KC_SORT, st);
+        HIP_TRY(c, launch_sort(st, g.n_occ, c->key_bits, c->ws, sorted_buf));
+        HIP_TRY(c, launch_segments(st, g.n_occ, c->ws.keys[*sorted_buf], c->ws));
+    }
+    if (side_stream) HIP_TRY(c, hipEventRecord(c->ev_sorted, c->aux));
     return LEGEND_OK;
 }
 
@@ -447,6 +463,9 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     if (cfg->copy_stream) c->copy = (hipStream_t)cfg->copy_stream;
     else { INIT_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)); c->own_copy = true; }
     INIT_TRY(hipEventCreateWithFlags(&c->ev_fence, hipEventDisableTiming));
+    INIT_TRY(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
+    INIT_TRY(hipEventCreateWithFlags(&c->ev_keys, hipEventDisableTiming));
+    INIT_TRY(hipEventCreateWithFlags(&c->ev_sorted, hipEventDisableTiming));
     INIT_TRY(hipEventCreate(&c->ev_t0));
     INIT_TRY(hipEventCreate(&c->ev_t1));
     INIT_TRY(hipEventRecord(c->ev_fence, c->compute));
@@ -610,7 +629,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         bp.batch_lo = b * B;
         bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, b);
         int sorted = 0;
-        rc = enqueue_index_side(c, g, bp, &sorted);
+        rc = enqueue_index_side(c, g, bp, &sorted, true);
         if (rc) return rc;
         {
             ProfScope ps(c, KC_CHUNK);
@@ -620,6 +639,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             ProfScope ps(c, KC_MISC);
             HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, c->ws));
         }
+        HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_sorted, 0));
         {
             ProfScope ps(c, KC_UPDATE);
             if (bp.atomic_mode) HIP_TRY(c, launch_update_atomic(c->compute, g, bp, c->ws));
@@ -753,7 +773,7 @@ int legend_debug_batch_indices(legend_ctx* c, int32_t i, int32_t j, const int32_
     unsigned long long saved = 0;
     HIP_TRY(c, hipMemcpyAsync(&saved, c->ws.uniq_total, sizeof saved, hipMemcpyDeviceToHost, c->compute));
     HIP_TRY(c, hipStreamSynchronize(c->compute));
-    rc = enqueue_index_side(c, g, bp, &sorted);
+    rc = enqueue_index_side(c, g, bp, &sorted, false);
     if (rc) return rc;
     uint32_t nu = 0;
     HIP_TRY(c, hipMemcpyAsync(&nu, c->ws.counters, sizeof nu, hipMemcpyDeviceToHost, c->compute));
