@@ -249,14 +249,22 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                     for (int v = 0; v < 16; ++v) { m_l[v] = acc[v]; s_l[v] = 1.f; }
                     seeded = true;
                 } else {
+                    float tmax = acc[0] - m_l[0];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float tdiff = acc[v] - m_l[v];
-                        if (tdiff > 16.f) {
-                            s_l[v] = fmaf(s_l[v], fast_exp(-tdiff), 1.f);
-                            m_l[v] = acc[v];
-                        } else {
-                            s_l[v] += fast_exp(tdiff);
+                    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v] - m_l[v]);
+                    if (tmax <= 16.f) {       // common case, no branch per score
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) s_l[v] += fast_exp(acc[v] - m_l[v]);
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const float tdiff = acc[v] - m_l[v];
+                            if (tdiff > 16.f) {
+                                s_l[v] = fmaf(s_l[v], fast_exp(-tdiff), 1.f);
+                                m_l[v] = acc[v];
+                            } else {
+                                s_l[v] += fast_exp(tdiff);
+                            }
                         }
                     }
                 }

@@ -7,6 +7,7 @@
 #include <chrono>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -77,6 +78,7 @@ struct legend_ctx {
     double prof_ms[KC_COUNT] = {0};
     int64_t prof_launches[KC_COUNT] = {0};
     int64_t batches_done = 0;
+    bool serial_sort = false;               // LEGEND_SERIAL_SORT=1: keep the sort on the compute stream (for per-kernel timing)
     bool keep_loss = false;                 // epoch driver: do not reset the device loss sum per bucket
     bool part_tables_dirty = false;         // d_part_emb / d_part_state lag behind part_slot
     bool fatal = false;
@@ -429,6 +431,10 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     c->Rp = Rp;
     c->part_floats = (size_t)2 * Rp * c->d;
     c->uses_rel = cfg->score != LEGEND_SCORE_DOT;
+    {
+        const char* e = std::getenv("LEGEND_SERIAL_SORT");
+        c->serial_sort = e && e[0] == '1';
+    }
     c->nrel_rows = std::max(cfg->num_relations, 1);
     c->host_part.assign(c->n, nullptr);
     c->slot_mem.assign(c->cap, nullptr);
@@ -629,7 +635,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         bp.batch_lo = b * B;
         bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, b);
         int sorted = 0;
-        rc = enqueue_index_side(c, g, bp, &sorted, true);
+        rc = enqueue_index_side(c, g, bp, &sorted, !c->serial_sort);
         if (rc) return rc;
         {
             ProfScope ps(c, KC_CHUNK);
@@ -639,7 +645,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             ProfScope ps(c, KC_MISC);
             HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, c->ws));
         }
-        HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_sorted, 0));
+        if (!c->serial_sort) HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_sorted, 0));
         {
             ProfScope ps(c, KC_UPDATE);
             if (bp.atomic_mode) HIP_TRY(c, launch_update_atomic(c->compute, g, bp, c->ws));
