@@ -243,4 +243,152 @@ hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_key
     return scan_launch(st, 1, sorted_keys, n, ws.scan_tmp, ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total);
 }
 
+// ------------------------------------------------------------------------------------------
+// Small batches (n <= kSmallSortMax): one workgroup sorts the pairs in LDS and emits the segment
+// heads, so a latency-bound tiny batch pays one launch instead of some twenty.
+// Same stable ranking as the multi-block scatter: wave w owns a contiguous quarter of the keys.
+// ------------------------------------------------------------------------------------------
+constexpr int kSmallSortMax = 4096;
+
+__global__ void __launch_bounds__(kSortThreads)
+k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, uint32_t* __restrict__ vals_out,
+                      uint32_t* __restrict__ uniq_keys, uint32_t* __restrict__ seg_start,
+                      uint32_t* __restrict__ counters, unsigned long long* __restrict__ uniq_total) {
+    constexpr int kWaves = kSortThreads / kWave;
+    extern __shared__ uint32_t sm[];
+    auto kb = [&](int b) { return sm + b * kSmallSortMax; };                     // key buffers 0 / 1
+    auto vb = [&](int b) { return sm + (2 + b) * kSmallSortMax; };               // value buffers 0 / 1
+    uint32_t* cnt = sm + 4 * kSmallSortMax;            // [kWaves][256]
+    uint32_t* pos0 = cnt + kWaves * kRadix;            // [kWaves][256]
+    uint32_t* wsum = pos0 + kWaves * kRadix;           // [kWaves] + carry
+    const int tid = threadIdx.x, w = tid / kWave, lane = lane_id();
+    for (int i = tid; i < n; i += kSortThreads) { kb(0)[i] = keys_in[i]; vb(0)[i] = (uint32_t)i; }
+    __syncthreads();
+    const int per_wave = (n + kWaves - 1) / kWaves;
+    const int lo = min(n, w * per_wave), hi = min(n, lo + per_wave);
+    int cur = 0;
+    for (int p = 0; p < passes; ++p) {
+        const int shift = 8 * p;
+        for (int i = tid; i < kWaves * kRadix; i += kSortThreads) cnt[i] = 0;
+        __syncthreads();
+        volatile uint32_t* mycnt = cnt + w * kRadix;
+        // pass 1 over the wave's keys: rank among equal digits inside the wave (kept in pos0's place later)
+        for (int base = lo; base < hi; base += kWave) {
+            const int i = base + lane;
+            const bool valid = i < hi;
+            const uint32_t key = valid ? kb(cur)[i] : 0u;
+            const uint32_t digit = (key >> shift) & (kRadix - 1);
+            unsigned long long mask = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bool bit = (digit >> b) & 1u;
+                const unsigned long long m = __ballot(bit);
+                mask &= bit ? m : ~m;
+            }
+            const unsigned long long lower = mask & ((1ull << lane) - 1ull);
+            uint32_t prefix = 0;
+            if (valid) prefix = mycnt[digit];
+            if (valid && lower == 0ull) mycnt[digit] = prefix + (uint32_t)__popcll(mask);
+            if (valid) vb(cur ^ 1)[i] = prefix + (uint32_t)__popcll(lower);   // rank, parked in the spare buffer
+        }
+        __syncthreads();
+        // exclusive scan over digits of the per-digit totals, then per-wave starting positions
+        {
+            const int d = tid;
+            uint32_t tot = 0;
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) tot += cnt[ww * kRadix + d];
+            uint32_t incl = tot;
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t t = __shfl_up(incl, off, kWave);
+                if (lane >= off) incl += t;
+            }
+            if (lane == kWave - 1) wsum[w] = incl;
+            __syncthreads();
+            uint32_t run = incl - tot;
+            for (int ww = 0; ww < w; ++ww) run += wsum[ww];
+#pragma unroll
+            for (int ww = 0; ww < kWaves; ++ww) {
+                pos0[ww * kRadix + d] = run;
+                run += cnt[ww * kRadix + d];
+            }
+        }
+        __syncthreads();
+        // scatter: ranks were parked in vbuf[cur^1]; move pairs through registers to avoid overwriting them
+        uint32_t mk[kSmallSortMax / kSortThreads], mv[kSmallSortMax / kSortThreads], mp[kSmallSortMax / kSortThreads];
+#pragma unroll
+        for (int r = 0; r < kSmallSortMax / kSortThreads; ++r) {
+            const int i = tid + r * kSortThreads;
+            if (i < n) {
+                const int ww = min(kWaves - 1, i / per_wave);
+                mk[r] = kb(cur)[i];
+                mv[r] = vb(cur)[i];
+                mp[r] = pos0[ww * kRadix + ((mk[r] >> shift) & (kRadix - 1))] + vb(cur ^ 1)[i];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kSmallSortMax / kSortThreads; ++r) {
+            const int i = tid + r * kSortThreads;
+            if (i < n) { kb(cur ^ 1)[mp[r]] = mk[r]; vb(cur ^ 1)[mp[r]] = mv[r]; }
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    // sorted values out; segment heads by a block scan of the head flags
+    for (int i = tid; i < n; i += kSortThreads) vals_out[i] = vb(cur)[i];
+    if (tid == 0) wsum[kWaves] = 0;
+    __syncthreads();
+    for (int base = 0; base < n; base += kSortThreads) {
+        const int i = base + tid;
+        const uint32_t key = i < n ? kb(cur)[i] : 0u;
+        const uint32_t flag = (i < n && (i == 0 || key != kb(cur)[i - 1])) ? 1u : 0u;
+        uint32_t incl = flag;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint32_t t = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += t;
+        }
+        if (lane == kWave - 1) wsum[w] = incl;
+        __syncthreads();
+        uint32_t run = wsum[kWaves] + incl - flag;
+        for (int ww = 0; ww < w; ++ww) run += wsum[ww];
+        if (flag) { uniq_keys[run] = key; seg_start[run] = (uint32_t)i; }
+        __syncthreads();
+        if (tid == kSortThreads - 1) wsum[kWaves] = run + flag;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const uint32_t total = wsum[kWaves];
+        seg_start[total] = (uint32_t)n;
+        counters[0] = total;
+        counters[2] = 0;
+        counters[3] = 0;
+        *uniq_total += total;
+    }
+}
+
+hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf) {
+    *out_buf = 0;
+    if (n <= 0) return hipSuccess;
+    if (n <= kSmallSortMax) {
+        int passes = (key_bits + 7) / 8;
+        if (passes < 1) passes = 1;
+        const size_t lds = (4 * (size_t)kSmallSortMax + 2 * 4 * kRadix + 8) * sizeof(uint32_t);
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_small_sort_segments),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(k_small_sort_segments, dim3(1), dim3(kSortThreads), lds, st, ws.keys[0], (int)n, passes,
+                           ws.vals[1], ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total);
+        *out_buf = 1;
+        return hipGetLastError();
+    }
+    hipError_t e = launch_sort(st, n, key_bits, ws, out_buf);
+    if (e != hipSuccess) return e;
+    return launch_segments(st, n, ws.keys[*out_buf], ws);
+}
+
 }  // namespace legend

@@ -90,6 +90,8 @@ hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams
 // sorts ws.keys[0]/vals[0] (n_occ entries); result buffer index returned in *out_buf
 hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
 hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws);
+// sort + segment heads; small inputs take a single-workgroup kernel
+hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, int32_t rows_per_partition);

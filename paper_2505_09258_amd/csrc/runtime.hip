@@ -375,8 +375,7 @@ int enqueue_index_side(legend_ctx* c, const BatchGeom& g, const BucketParams& bp
     }
     {
         ProfScope ps(c, KC_SORT, st);
-        HIP_TRY(c, launch_sort(st, g.n_occ, c->key_bits, c->ws, sorted_buf));
-        HIP_TRY(c, launch_segments(st, g.n_occ, c->ws.keys[*sorted_buf], c->ws));
+        HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, c->ws, sorted_buf));
     }
     if (side_stream) HIP_TRY(c, hipEventRecord(c->ev_sorted, c->aux));
     return LEGEND_OK;
