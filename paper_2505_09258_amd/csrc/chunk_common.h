@@ -52,6 +52,8 @@ __device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const f
 // use the same mapping, so the sum over k is complete and every lane can fetch its four
 // values of a row-major operand with one 128-bit LDS read.
 
+bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp);
+hipError_t launch_chunks_fast(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_chunks_wide(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 
 }  // namespace legend

@@ -39,7 +39,9 @@ bool dim_supported(int dim) { return dim >= 1 && (dim <= kNarrowMaxDim || (dim <
 template <int NB, int SCORE, int LOSS, int DFIX>
 __global__ void __launch_bounds__(kChunkThreads, 2)     // two waves per SIMD: two workgroups share a compute unit
 k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float* __restrict__ grad,
-        double* __restrict__ loss_partial) {
+        double* __restrict__ loss_partial, const uint32_t* __restrict__ only_if) {
+    // redo mode: only the workgroups the single-sweep kernel flagged have anything to do
+    if (only_if && only_if[blockIdx.x] == 0u) return;
     constexpr int LPR = NB * 8;             // lanes that cooperate on one gathered row (float4 each)
     constexpr int RPS = kWave / LPR;        // rows a wave gathers per step
     constexpr int STEPS = 16 / RPS;         // each wave gathers 16 of the 64 tile rows
@@ -548,7 +550,8 @@ static size_t chunk_lds_bytes(int d, int nb) {
 }
 
 template <int NB, int DFIX>
-static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                                   const uint32_t* only_if) {
     dim3 grid((unsigned)(g.sides * g.nchunks * g.T)), block(kChunkThreads);
     size_t lds = chunk_lds_bytes(bp.dim, NB);
 #define LEGEND_CHUNK_CASE(SC, LO)                                                                              \
@@ -561,7 +564,7 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
             lds_allowed = lds;                                                                                 \
         }                                                                                                      \
         hipLaunchKernelGGL((k_chunk<NB, SC, LO, DFIX>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,      \
-                           ws.loss_partial);                                                                   \
+                           ws.loss_partial, only_if);                                                          \
         return hipGetLastError();                                                                              \
     }
     LEGEND_CHUNK_CASE(LEGEND_SCORE_DOT, LEGEND_LOSS_SOFTMAX)
@@ -576,12 +579,19 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
 
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     if (g.P <= 0) return hipSuccess;
+    const uint32_t* only_if = nullptr;
+    if (chunk_fast_applies(g, bp) && !ws.no_fast_path) {
+        // single sweep first; whatever it flags as out of range is redone by the two-sweep kernel
+        hipError_t e = launch_chunks_fast(st, g, bp, ws);
+        if (e != hipSuccess) return e;
+        only_if = ws.redo;
+    }
     // the dimensions of the paper's workloads get kernels with the dimension folded in
-    if (bp.dim == 100) return launch_chunks_nb<4, 100>(st, g, bp, ws);
-    if (bp.dim == 32) return launch_chunks_nb<1, 32>(st, g, bp, ws);
-    if (bp.dim <= 32) return launch_chunks_nb<1, 0>(st, g, bp, ws);
-    if (bp.dim <= 64) return launch_chunks_nb<2, 0>(st, g, bp, ws);
-    if (bp.dim <= 128) return launch_chunks_nb<4, 0>(st, g, bp, ws);
+    if (bp.dim == 100) return launch_chunks_nb<4, 100>(st, g, bp, ws, only_if);
+    if (bp.dim == 32) return launch_chunks_nb<1, 32>(st, g, bp, ws, only_if);
+    if (bp.dim <= 32) return launch_chunks_nb<1, 0>(st, g, bp, ws, only_if);
+    if (bp.dim <= 64) return launch_chunks_nb<2, 0>(st, g, bp, ws, only_if);
+    if (bp.dim <= 128) return launch_chunks_nb<4, 0>(st, g, bp, ws, only_if);
     return launch_chunks_wide(st, g, bp, ws);
 }
 

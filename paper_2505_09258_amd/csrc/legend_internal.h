@@ -78,6 +78,8 @@ struct Workspace {
     unsigned long long* uniq_total;  // running sum of unique rows
     float*    grad;           // [n_occ][dim] staged gradient rows
     double*   loss_partial;   // one per chunk workgroup
+    uint32_t* redo;           // per chunk workgroup: 1 = the single-sweep kernel left it to the general kernel
+    int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel
     double*   loss_sum;       // running bucket loss
     int64_t   cap_occ;
     int64_t   cap_wg;

@@ -247,7 +247,7 @@ void free_ctx(legend_ctx* c) {
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
-                     c->ws.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.loss_sum, c->edges_dev,
+                     c->ws.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.loss_sum, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
     if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
@@ -541,6 +541,11 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     INIT_RC(dev_alloc(c, &w.uniq_total, 1));
     INIT_RC(dev_alloc(c, &w.grad, (size_t)occ * c->d));
     INIT_RC(dev_alloc(c, &w.loss_partial, (size_t)nwg));
+    INIT_RC(dev_alloc(c, &w.redo, (size_t)nwg));
+    {
+        const char* e = std::getenv("LEGEND_NO_FAST_CHUNK");
+        w.no_fast_path = (e && e[0] == '1') ? 1 : 0;
+    }
     INIT_RC(dev_alloc(c, &w.loss_sum, 1));
     INIT_TRY(hipMemset(w.counters, 0, 4 * sizeof(uint32_t)));
     INIT_TRY(hipMemset(w.uniq_total, 0, sizeof(unsigned long long)));
