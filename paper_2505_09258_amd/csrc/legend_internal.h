@@ -80,6 +80,7 @@ struct Workspace {
     double*   loss_partial;   // one per chunk workgroup
     uint32_t* redo;           // per chunk workgroup: 1 = the single-sweep kernel left it to the general kernel
     int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel
+    float     fast_limit;     // largest S - f the single-sweep kernel accepts (LEGEND_FAST_CHUNK_LIMIT, default 60)
     double*   loss_sum;       // running bucket loss
     int64_t   cap_occ;
     int64_t   cap_wg;

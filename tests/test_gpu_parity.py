@@ -35,7 +35,14 @@ CASES = [
     _case("distmult_d400_both", DISTMULT, SOFTMAX, BOTH, 3_000, 45, 400, 1, 0, 0, 400, 100, 130, 0, 900, 0.15),
     _case("complex_d132_offdiag", COMPLEX, SOFTMAX, BOTH, 2_000, 7, 132, 2, 1, 0, 150, 40, 33, 8, 320, 0.3),
     _case("dot_d512_logistic", DOT, LOGISTIC, SRC, 800, 0, 512, 1, 0, 0, 96, 32, 64, 0, 200, 0.1),
+    # d = 100 with the largest negative count and full 64-row chunks (single-sweep kernel, all eight steps)
+    _case("distmult_d100_n1024", DISTMULT, SOFTMAX, SRC, 8_000, 11, 100, 2, 1, 0, 640, 64, 1_024, 100, 1_500, 0.3),
 ]
+
+# One node row in 64 is four times larger than the rest, so that some chunks hold a score far
+# above the positive's and others do not.
+_HOT_CASE = dict(_case("dot_d100_hot_rows", DOT, SOFTMAX, DST, 12_000, 0, 100, 2, 0, 1, 1_000, 50, 300, 0, 2_500, 0.1),
+                 hot_every=64, hot_scale=4.0)
 
 
 def _inputs(c):
@@ -43,6 +50,8 @@ def _inputs(c):
     rp = -(-c["V"] // c["n"])
     node = (c["std"] * rng.standard_normal((c["V"], c["d"]))).astype(np.float32)
     rel = (c["std"] * rng.standard_normal((max(c["nrel"], 1), c["d"]))).astype(np.float32) + np.float32(0.5 if c["score"] else 0)
+    if c.get("hot_every"):
+        node[17::c["hot_every"]] *= np.float32(c["hot_scale"])
 
     def rows(part, count):
         valid = min(rp, c["V"] - part * rp)
@@ -111,6 +120,34 @@ def test_every_batch_matches_oracle(c):
     """Batch by batch: the oracle restarts from the GPU's tables before each batch, so each
     comparison is one batch step from identical inputs (errors of earlier batches, which the
     1/sqrt(S) normalisation of Adagrad can amplify without bound, do not enter)."""
+    _check_every_batch(c)
+
+
+def test_single_sweep_kernel_hands_out_of_range_chunks_to_the_general_kernel(monkeypatch):
+    """The single-sweep kernel gives up on a chunk in which some negative scores more than a
+    limit above its positive; the two-sweep kernel then computes that chunk.  With the limit
+    lowered to 2 the hot rows put some chunks of every batch on either path."""
+    c, limit = _HOT_CASE, 2.0
+    node, rel, edges = _inputs(c)
+    rp = -(-c["V"] // c["n"])
+    e = edges[: c["B"]]
+    neg = negatives.batch_negatives(_ocfg(c), 1, c["i"], c["j"], 0, e, edges)[0]
+    ts = node[c["i"] * rp + e[:, 0]].astype(np.float64)
+    td = node[c["j"] * rp + e[:, 2]].astype(np.float64)
+    flagged = []
+    for ch in range(neg.shape[0]):
+        rows = slice(ch * c["C"], (ch + 1) * c["C"])
+        S = ts[rows] @ node[c["j"] * rp + neg[ch]].astype(np.float64).T
+        f = np.sum(ts[rows] * td[rows], axis=1)
+        margin = (S - f[:, None]).max()
+        assert abs(margin - limit) > 1e-3          # no chunk sits on the limit itself
+        flagged.append(margin > limit)
+    assert 0 < sum(flagged) < len(flagged), flagged
+    monkeypatch.setenv("LEGEND_FAST_CHUNK_LIMIT", str(limit))
+    _check_every_batch(c)
+
+
+def _check_every_batch(c):
     node, rel, edges = _inputs(c)
     L, ctx = _gpu_ctx(c, node, rel)
     try:
