@@ -68,11 +68,80 @@ struct FastShape {
     static constexpr size_t lds_bytes = sizeof(float) * (q_floats + n_floats + w_floats + 4 * kFRow + 16 + kIdsLds);
 };
 
+// Four elements of an embedding row that are handled together: elements 4c..4c+3, or for
+// ComplEx the real and imaginary parts of the complex components 2c and 2c+1 (elements 2c,
+// 2c+1, D/2+2c, D/2+2c+1; paper Sec. 2.1, score functions of Table 1).
+template <int SCORE, int D>
+struct RowItem {
+    static constexpr int H = D / 2;
+    static_assert(SCORE != LEGEND_SCORE_COMPLEX || H % 2 == 0, "ComplEx items need an even number of components");
+    __device__ static void load(const float* row, int c, float (&v)[4]) {
+        if (SCORE == LEGEND_SCORE_COMPLEX) {
+            const float2 a = *reinterpret_cast<const float2*>(row + 2 * c);
+            const float2 b = *reinterpret_cast<const float2*>(row + H + 2 * c);
+            v[0] = a.x; v[1] = a.y; v[2] = b.x; v[3] = b.y;
+        } else {
+            const float4 a = *reinterpret_cast<const float4*>(row + 4 * c);
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        }
+    }
+    __device__ static void store(float* row, int c, const float (&v)[4]) {
+        if (SCORE == LEGEND_SCORE_COMPLEX) {
+            *reinterpret_cast<float2*>(row + 2 * c) = make_float2(v[0], v[1]);
+            *reinterpret_cast<float2*>(row + H + 2 * c) = make_float2(v[2], v[3]);
+        } else {
+            *reinterpret_cast<float4*>(row + 4 * c) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    }
+    // q = x (.) r for the destination side, conj(r) (.) x for the source side
+    __device__ static void compose(int side, const float (&x)[4], const float (&r)[4], float (&q)[4]) {
+        if (SCORE == LEGEND_SCORE_DOT) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) q[t] = x[t];
+        } else if (SCORE == LEGEND_SCORE_DISTMULT) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) q[t] = x[t] * r[t];
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const float xr = x[p], xi = x[p + 2], rr = r[p], ri = r[p + 2];
+                if (side == 0) { q[p] = xr * rr - xi * ri; q[p + 2] = xr * ri + xi * rr; }
+                else           { q[p] = rr * xr + ri * xi; q[p + 2] = rr * xi - ri * xr; }
+            }
+        }
+    }
+    // gradients of x and r from the gradient of q
+    __device__ static void chain(int side, const float (&x)[4], const float (&r)[4], const float (&gq)[4],
+                                 float (&gx)[4], float (&gr)[4]) {
+        if (SCORE == LEGEND_SCORE_DOT) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { gx[t] = gq[t]; gr[t] = 0.f; }
+        } else if (SCORE == LEGEND_SCORE_DISTMULT) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { gx[t] = r[t] * gq[t]; gr[t] = x[t] * gq[t]; }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const float xr = x[p], xi = x[p + 2], rr = r[p], ri = r[p + 2];
+                const float gre = gq[p], gim = gq[p + 2];
+                if (side == 0) {
+                    gx[p] = rr * gre + ri * gim;      gx[p + 2] = rr * gim - ri * gre;
+                    gr[p] = xr * gre + xi * gim;      gr[p + 2] = xr * gim - xi * gre;
+                } else {
+                    gx[p] = rr * gre - ri * gim;      gx[p + 2] = rr * gim + ri * gre;
+                    gr[p] = gre * xr + gim * xi;      gr[p + 2] = gre * xi - gim * xr;
+                }
+            }
+        }
+    }
+};
+
 template <int SCORE, int D>
 __global__ void __launch_bounds__(kFThreads, 1)
 k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float* __restrict__ grad,
              double* __restrict__ loss_partial, uint32_t* __restrict__ redo, float limit) {
     using Sh = FastShape<D>;
+    using Item = RowItem<SCORE, D>;
     constexpr int QS = Sh::QS, KG = Sh::KG, KT = Sh::KT, NJ = Sh::NJ, STEPS = Sh::STEPS;
     constexpr int d = D;
 
@@ -116,40 +185,55 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     for (int k = tid; k < N; k += kFThreads) ids_s[k] = my_negs[k];         // N <= 1024 here
     if (tid < 16) flag_s[tid] = 0;
 
-    // ---- prologue: Q rows and positive scores; 8 threads per row -------------------------------
-    const int prow = tid >> 3;
-    const int ppart = tid & 7;
+    // ---- prologue: Q rows and positive scores ---------------------------------------------------
+    // A row is cut into D/4 items of four elements; a thread takes up to ITEMS (row, item) pairs
+    // and issues all its loads before it uses any of them.
+    constexpr int IPR = D / 4;
+    constexpr int ITEMS = (kFRow * IPR + kFThreads - 1) / kFThreads;
+    int it_row[ITEMS], it_c[ITEMS];
+#pragma unroll
+    for (int s = 0; s < ITEMS; ++s) {
+        const int idx = tid + kFThreads * s;
+        it_row[s] = idx / IPR;
+        it_c[s] = idx - it_row[s] * IPR;
+    }
     {
-        float partial = 0.f;
-        if (prow < nrows) {
-            const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;
-            const float* y = Ey + (int64_t)eb[prow * 3 + ycol] * d;
-            const float* r = SCORE == LEGEND_SCORE_DOT ? x : bp.E_rel + (int64_t)eb[prow * 3 + 1] * d;
-            if (SCORE == LEGEND_SCORE_COMPLEX) {
-                constexpr int h = d >> 1;
-                for (int k = ppart; k < h; k += 8) {
-                    float xr = x[k], xi = x[k + h], rr = r[k], ri = r[k + h];
-                    float qr, qi;
-                    if (side == 0) { qr = xr * rr - xi * ri; qi = xr * ri + xi * rr; }
-                    else           { qr = rr * xr + ri * xi; qi = rr * xi - ri * xr; }
-                    Qs[prow * QS + k] = qr;
-                    Qs[prow * QS + k + h] = qi;
-                    partial += qr * y[k] + qi * y[k + h];
-                }
-            } else {
-                for (int k = ppart; k < d; k += 8) {
-                    float q = SCORE == LEGEND_SCORE_DOT ? x[k] : x[k] * r[k];
-                    Qs[prow * QS + k] = q;
-                    partial += q * y[k];
-                }
-            }
-        } else {
-            for (int k = ppart; k < d; k += 8) Qs[prow * QS + k] = 0.f;
+        float* part_s = Ws;                   // [64][IPR] partial positive scores
+        int32_t ex[ITEMS], ey[ITEMS], er[ITEMS];
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+            const bool live = it_row[s] < nrows;
+            ex[s] = live ? eb[it_row[s] * 3 + xcol] : 0;
+            ey[s] = live ? eb[it_row[s] * 3 + ycol] : 0;
+            er[s] = live && SCORE != LEGEND_SCORE_DOT ? eb[it_row[s] * 3 + 1] : 0;
         }
-        partial += wave_shfl_xor(partial, 1);
-        partial += wave_shfl_xor(partial, 2);
-        partial += wave_shfl_xor(partial, 4);
-        if (ppart == 0) ref_s[prow] = partial;
+        float x[ITEMS][4], y[ITEMS][4], r[ITEMS][4];
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+            Item::load(Ex + (int64_t)ex[s] * d, it_c[s], x[s]);
+            Item::load(Ey + (int64_t)ey[s] * d, it_c[s], y[s]);
+            if (SCORE != LEGEND_SCORE_DOT) Item::load(bp.E_rel + (int64_t)er[s] * d, it_c[s], r[s]);
+        }
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+            if (it_row[s] < kFRow) {
+                float q[4] = {0.f, 0.f, 0.f, 0.f};
+                float partial = 0.f;
+                if (it_row[s] < nrows) {
+                    Item::compose(side, x[s], r[s], q);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) partial += q[t] * y[s][t];
+                }
+                Item::store(Qs + it_row[s] * QS, it_c[s], q);
+                part_s[it_row[s] * IPR + it_c[s]] = partial;
+            }
+        }
+        __syncthreads();
+        if (tid < kFRow) {
+            float f = 0.f;
+            for (int cc = 0; cc < IPR; ++cc) f += part_s[tid * IPR + cc];
+            ref_s[tid] = f;
+        }
     }
 
     // ---- gather machinery: wave w fetches rows 16w..16w+15 of a 128-negative tile ---------------
@@ -382,54 +466,44 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     }
     __syncthreads();
     {
-        float row_loss = 0.f;
-        if (prow < nrows) {
-            const float sc = scale_s[prow];
-            row_loss = logl_s[prow];          // lse - f with the positive score as reference
-            const float a = -1.f;
-            const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;
-            const float* y = Ey + (int64_t)eb[prow * 3 + ycol] * d;
-            const float* r = SCORE == LEGEND_SCORE_DOT ? x : bp.E_rel + (int64_t)eb[prow * 3 + 1] * d;
-            const int64_t e = e0 + prow;
-            float* gx = grad + (side_base + (side == 0 ? 0 : g.P) + e) * d;
-            float* gy = grad + (side_base + (side == 0 ? g.P : 0) + e) * d;
-            float* gr = grad + (side_base + 2 * (int64_t)g.P + e) * d;
-            const float* g0 = Ns + prow * QS;
-            const float* g1 = g0 + kFRow * QS;
-            if (SCORE == LEGEND_SCORE_COMPLEX) {
-                constexpr int h = d >> 1;
-                for (int k = ppart; k < h; k += 8) {
-                    float xr = x[k], xi = x[k + h], rr = r[k], ri = r[k + h];
-                    float qr, qi;
-                    if (side == 0) { qr = xr * rr - xi * ri; qi = xr * ri + xi * rr; }
-                    else           { qr = rr * xr + ri * xi; qi = rr * xi - ri * xr; }
-                    float gre = (g0[k] + g1[k]) * sc + a * y[k];
-                    float gim = (g0[k + h] + g1[k + h]) * sc + a * y[k + h];
-                    gy[k] = a * qr;
-                    gy[k + h] = a * qi;
-                    if (side == 0) {
-                        gx[k] = rr * gre + ri * gim;      gx[k + h] = rr * gim - ri * gre;
-                        gr[k] = xr * gre + xi * gim;      gr[k + h] = xr * gim - xi * gre;
-                    } else {
-                        gx[k] = rr * gre - ri * gim;      gx[k + h] = rr * gim + ri * gre;
-                        gr[k] = gre * xr + gim * xi;      gr[k + h] = gre * xi - gim * xr;
-                    }
+        int32_t ex[ITEMS], ey[ITEMS], er[ITEMS];
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+            const bool live = it_row[s] < nrows;
+            ex[s] = live ? eb[it_row[s] * 3 + xcol] : 0;
+            ey[s] = live ? eb[it_row[s] * 3 + ycol] : 0;
+            er[s] = live && SCORE != LEGEND_SCORE_DOT ? eb[it_row[s] * 3 + 1] : 0;
+        }
+        float x[ITEMS][4], y[ITEMS][4], r[ITEMS][4];
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+            Item::load(Ex + (int64_t)ex[s] * d, it_c[s], x[s]);
+            Item::load(Ey + (int64_t)ey[s] * d, it_c[s], y[s]);
+            if (SCORE != LEGEND_SCORE_DOT) Item::load(bp.E_rel + (int64_t)er[s] * d, it_c[s], r[s]);
+        }
+#pragma unroll
+        for (int s = 0; s < ITEMS; ++s) {
+            if (it_row[s] < nrows) {
+                const int row = it_row[s];
+                const float sc = scale_s[row];
+                const float a = -1.f;                     // dL/df of Eq. 1
+                float q[4], g0[4], g1[4], gv[4], gy4[4], gx4[4], gr4[4];
+                Item::compose(side, x[s], r[s], q);
+                Item::load(Ns + row * QS, it_c[s], g0);
+                Item::load(Ns + (kFRow + row) * QS, it_c[s], g1);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    gv[t] = (g0[t] + g1[t]) * sc + a * y[s][t];
+                    gy4[t] = a * q[t];
                 }
-            } else {
-                for (int k = ppart; k < d; k += 8) {
-                    const float q = SCORE == LEGEND_SCORE_DOT ? x[k] : x[k] * r[k];
-                    const float gv = (g0[k] + g1[k]) * sc + a * y[k];
-                    gy[k] = a * q;
-                    if (SCORE == LEGEND_SCORE_DOT) {
-                        gx[k] = gv;
-                    } else {
-                        gx[k] = r[k] * gv;
-                        gr[k] = x[k] * gv;
-                    }
-                }
+                Item::chain(side, x[s], r[s], gv, gx4, gr4);
+                const int64_t e = e0 + row;
+                Item::store(grad + (side_base + (side == 0 ? 0 : g.P) + e) * d, it_c[s], gx4);
+                Item::store(grad + (side_base + (side == 0 ? g.P : 0) + e) * d, it_c[s], gy4);
+                if (SCORE != LEGEND_SCORE_DOT) Item::store(grad + (side_base + 2 * (int64_t)g.P + e) * d, it_c[s], gr4);
             }
         }
-        if (ppart == 0) rowloss_s[prow] = row_loss;
+        if (tid < kFRow) rowloss_s[tid] = tid < nrows ? logl_s[tid] : 0.f;   // lse - f, the positive score being the reference
     }
     __syncthreads();
     if (tid == 0) {
