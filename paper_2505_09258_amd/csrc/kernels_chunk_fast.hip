@@ -11,18 +11,22 @@
 // from overflow) or a row sum under- or overflows, the workgroup writes nothing and flags
 // itself; the general two-sweep kernel then redoes it.
 //
-// Work split (16x16x4 fp32 MFMA; g = lane / 16, l15 = lane % 16):
-//   sweep, per 128 negatives:
-//     scores    wave w owns the 16 negatives 16w..16w+15 it has gathered itself and all 64 rows:
-//               four 16x16 blocks S[16r + 4g + v][16w + l15], r = 0..3, v = 0..3;
+// Work split (16x16x4 fp32 MFMA; g = lane / 16, l15 = lane % 16).  The eight waves form two
+// groups of four; the negatives are cut into tiles of 64, even tiles for group 0, odd ones for
+// group 1; wave wl of a group:
+//   sweep, per tile of its group:
+//     scores    owns the 16 negatives 16wl..16wl+15 of the tile, which it has gathered itself,
+//               and all 64 rows: four 16x16 blocks S[16r + 4g + v][16wl + l15], r, v = 0..3;
 //     P         the same 16 values per lane, kept for the whole kernel, and written to LDS as
 //               W[row][negative] for the next step;
-//     G_Q       wave (rq = w % 4, kh = w / 4) adds W[16rq.., 64kh..64kh+63] x Neg[64kh.., :] to its
-//               16 x 112 slice; the two halves kh are added once at the end;
-//   afterwards, per 128 negatives and with no workgroup barrier:
-//     G_neg     wave w contracts its stored P (as the A operand of P^T: lane = negative,
-//               k = row) with (Q / l)^T read from LDS over all 64 rows, stages its 16 gradient
-//               rows in its own LDS area and writes them out as one contiguous 6400-byte run.
+//     G_Q       adds W[16wl..16wl+15, tile] x Neg[tile, :] to its 16 x 112 slice; the partial
+//               sums of the two groups are added once at the end;
+//   the two groups run half a step apart, so that one is in the vector-ALU part of its step
+//   while the other keeps the matrix pipe busy;
+//   afterwards, per tile and with no workgroup barrier:
+//     G_neg     contracts its stored P (as the A operand of P^T: lane = negative, k = row)
+//               with (Q / l)^T read from LDS over all 64 rows, stages its 16 gradient rows in
+//               its own LDS area and writes them out as one contiguous 6400-byte run.
 #include <type_traits>
 
 #include "chunk_common.h"
@@ -48,10 +52,10 @@ __device__ __forceinline__ void static_for(F&& f) {
 constexpr int kFThreads = 512;
 constexpr int kFWaves = kFThreads / kWave;
 constexpr int kFRow = 64;                // rows of Q per workgroup
-constexpr int kFSuper = 128;             // negatives per sweep step: 16 per wave
-constexpr int kFWS = kFSuper + 4;        // row stride of the W tile
+constexpr int kFTile = 64;               // negatives per tile of a wave group: 16 per wave
+constexpr int kFWS = kFTile + 4;         // row stride of a W tile
 constexpr int kFQT = kFRow + 4;          // row stride of the transposed, scaled Q
-constexpr int kFMaxSteps = 8;            // 1024 negatives
+constexpr int kFMaxSteps = 8;            // tiles per wave group: 1024 negatives in all
 
 template <int D>
 struct FastShape {
@@ -63,8 +67,8 @@ struct FastShape {
     static constexpr int LPR = 32;                          // lanes per gathered row (float4 each)
     static constexpr int STEPS = 16 / (kWave / LPR);        // a wave gathers 16 rows, two at a time
     static constexpr int q_floats = kFRow * QS;
-    static constexpr int n_floats = kFSuper * QS + 16;      // + slack: column blocks run past the last row
-    static constexpr int w_floats = kFRow * kFWS > 16 * NJ * kFQT ? kFRow * kFWS : 16 * NJ * kFQT;
+    static constexpr int n_floats = 2 * kFTile * QS + 16;   // one tile per wave group; + slack: column blocks run past the last row
+    static constexpr int w_floats = 2 * kFRow * kFWS > 16 * NJ * kFQT ? 2 * kFRow * kFWS : 16 * NJ * kFQT;
     static constexpr size_t lds_bytes = sizeof(float) * (q_floats + n_floats + w_floats + 4 * kFRow + 16 + kIdsLds);
 };
 
@@ -148,7 +152,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     extern __shared__ __align__(16) float smem[];
     float* Qs = smem;
     float* Ns = Qs + Sh::q_floats;
-    float* Ws = Ns + Sh::n_floats;              // sweep: W[64][132]; afterwards: row sums, then (Q/l)^T [112][68]
+    float* Ws = Ns + Sh::n_floats;              // sweep: W[2][64][68]; before: partial f; afterwards: row sums, then (Q/l)^T [112][68]
     float* ref_s = Ws + Sh::w_floats;           // [64] positive scores = softmax reference
     float* scale_s = ref_s + kFRow;             // [64] 1 / l_e
     float* logl_s = scale_s + kFRow;            // [64] log l_e
@@ -232,125 +236,159 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         if (tid < kFRow) {
             float f = 0.f;
             for (int cc = 0; cc < IPR; ++cc) f += part_s[tid * IPR + cc];
-            ref_s[tid] = f;
+            ref_s[tid] = tid < nrows ? f : 1e30f;     // rows past the chunk: every numerator becomes 0
         }
     }
 
-    // ---- gather machinery: wave w fetches rows 16w..16w+15 of a 128-negative tile ---------------
+    // ---- gather machinery: a wave fetches rows 16wl..16wl+15 of its group's 64-negative tile -----
+    const int grp = w >> 2, wl = w & 3;       // wave group and wave within it
+    float* Ng = Ns + grp * (kFTile * QS);
+    float* Wg = Ws + grp * (kFRow * kFWS);
     float4 pf[STEPS];
     const int grow_lane = lane >> 5;
     const int gc0 = (lane & 31) * 4;
     const int gcol_ld = gc0 < d ? gc0 : 0;
     typedef __attribute__((address_space(3))) const int32_t* lds_ids_t;
-    auto gather_issue = [&](int n0) {
+    auto gather_issue = [&](int n0) __attribute__((always_inline)) {
         int32_t idv[STEPS];
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) idv[s] = ((lds_ids_t)ids_s)[min(n0 + w * 16 + s * 2 + grow_lane, N - 1)];
+        for (int s = 0; s < STEPS; ++s) idv[s] = ((lds_ids_t)ids_s)[min(n0 + wl * 16 + s * 2 + grow_lane, N - 1)];
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) pf[s] = *reinterpret_cast<const float4*>(En + (int64_t)idv[s] * d + gcol_ld);
     };
-    auto gather_commit = [&](int n0) {
+    auto gather_commit = [&](int n0) __attribute__((always_inline)) {
+        if (n0 + kFTile > N) {                // last tile: rows past the last negative are zero
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            const int rt = w * 16 + s * 2 + grow_lane;
-            float4 v = pf[s];
-            if (n0 + rt >= N) v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gc0 < d) *reinterpret_cast<float4*>(Ns + rt * QS + gc0) = v;
+            for (int s = 0; s < STEPS; ++s)
+                if (n0 + wl * 16 + s * 2 + grow_lane >= N) pf[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        if (gc0 < d) {
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s)
+                *reinterpret_cast<float4*>(Ng + (wl * 16 + s * 2 + grow_lane) * QS + gc0) = pf[s];
         }
     };
 
-    const int ntiles = (N + kFSuper - 1) / kFSuper;
-    const int rq = w & 3, kh = w >> 2;
+    // Tiles 2i belong to wave group 0 and tiles 2i + 1 to group 1.  The groups run half a step
+    // apart: while one scores a tile and takes the exponentials (matrix pipe, then vector ALU
+    // and LDS writes), the other multiplies its previous W tile into G_Q (matrix pipe with LDS
+    // reads), so that the two waves of a SIMD want different units most of the time.
+    const int ntiles = (N + kFTile - 1) / kFTile;
+    auto tile_of = [&](int i) { return 2 * i + grp; };
 
     f32x4 P[kFMaxSteps][4];                   // the chunk's softmax numerators owned by this wave
     f32x4 accB[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) accB[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    bool out_of_range = false;
+    float top = -1e30f;                       // largest S - f seen
 
     __syncthreads();                          // ids, Q and the references are in LDS
-    gather_issue(0);
+    if (tile_of(0) < ntiles) gather_issue(tile_of(0) * kFTile);
 
-    // ---- the sweep: scores, numerators, unnormalised G_Q ---------------------------------------
-    static_for<0, kFMaxSteps>([&](auto U) {
-        constexpr int u = decltype(U)::value;
-        if (u < ntiles) {
-            const int n0 = u * kFSuper;
-            gather_commit(n0);                // own rows only; the previous step ended with a barrier
-            if (u + 1 < ntiles) gather_issue(n0 + kFSuper);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // scores and numerators of tile i of this group; P[i] is written
+    auto score_tile = [&](auto I) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
+        const int n0 = tile_of(i) * kFTile;
+        gather_commit(n0);                    // own rows only; their last readers are a barrier behind
+        if (tile_of(i + 1) < ntiles) gather_issue(n0 + 2 * kFTile);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-            // scores of all 64 rows against the wave's own 16 negatives
-            f32x4 acc[4];
+        f32x4 acc[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const float* qa = Qs + l15 * QS + 4 * gq;
-            const float* nb = Ns + (16 * w + l15) * QS + 4 * gq;
+        for (int r = 0; r < 4; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const float* qa = Qs + l15 * QS + 4 * gq;
+        const float* nb = Ng + (16 * wl + l15) * QS + 4 * gq;
 #pragma unroll
-            for (int G = 0; G < KG; ++G) {
-                const float4 b = lds4(nb + 16 * G);
-                float4 a[4];
+        for (int G = 0; G < KG; ++G) {
+            const float4 b = lds4(nb + 16 * G);
+            float4 a[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) a[r] = lds4(qa + 16 * r * QS + 16 * G);
+            for (int r = 0; r < 4; ++r) a[r] = lds4(qa + 16 * r * QS + 16 * G);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].x, b.x, acc[r]);
+            for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].x, b.x, acc[r]);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].y, b.y, acc[r]);
+            for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].y, b.y, acc[r]);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].z, b.z, acc[r]);
+            for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].z, b.z, acc[r]);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].w, b.w, acc[r]);
+            for (int r = 0; r < 4; ++r) acc[r] = mfma16(a[r].w, b.w, acc[r]);
+        }
+#pragma unroll
+        for (int ts = 0; ts < KT; ++ts) {
+            const int k = 16 * KG + 4 * ts + gq;
+            const float b = Ng[(16 * wl + l15) * QS + k];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = mfma16(Qs[(16 * r + l15) * QS + k], b, acc[r]);
+        }
+        if (n0 + kFTile > N && n0 + 16 * wl + l15 >= N) {      // columns past the last negative
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = f32x4{-1e30f, -1e30f, -1e30f, -1e30f};
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float4 rf = lds4(ref_s + 16 * r + 4 * gq);
+            const float refv[4] = {rf.x, rf.y, rf.z, rf.w};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float diff = acc[r][v] - refv[v];
+                top = fmaxf(top, diff);
+                const float p = fast_exp(diff);
+                acc[r][v] = p;
+                Wg[(16 * r + 4 * gq + v) * kFWS + 16 * wl + l15] = p;
             }
+            P[i][r] = acc[r];
+        }
+    };
+    // G_Q += W tile x negatives tile of this group: wave wl has rows 16wl..16wl+15, all columns
+    auto accumulate_tile = [&](int i) __attribute__((always_inline)) {
+        const int n0 = tile_of(i) * kFTile;
+        const float* wa = Wg + (16 * wl + l15) * kFWS + 4 * gq;
+        const float* nbB = Ng + (4 * gq) * QS + l15;
 #pragma unroll
-            for (int ts = 0; ts < KT; ++ts) {
-                const int k = 16 * KG + 4 * ts + gq;
-                const float b = Ns[(16 * w + l15) * QS + k];
+        for (int G = 0; G < 4; ++G) {
+            if (n0 + 16 * G < N) {            // uniform
+                const float4 a4 = lds4(wa + 16 * G);
+                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[r] = mfma16(Qs[(16 * r + l15) * QS + k], b, acc[r]);
-            }
-
-            const bool col_ok = n0 + 16 * w + l15 < N;
+                for (int s = 0; s < 4; ++s) {
+                    const float* nrow = nbB + (16 * G + s) * QS;
+                    float b[NJ];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float4 rf = lds4(ref_s + 16 * r + 4 * gq);
-                const float refv[4] = {rf.x, rf.y, rf.z, rf.w};
+                    for (int j = 0; j < NJ; ++j) b[j] = nrow[16 * j];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int row = 16 * r + 4 * gq + v;
-                    const bool ok = col_ok && row < nrows;
-                    const float diff = acc[r][v] - refv[v];
-                    out_of_range |= ok && (diff > limit);
-                    const float p = ok ? fast_exp(diff) : 0.f;
-                    acc[r][v] = p;
-                    Ws[row * kFWS + 16 * w + l15] = p;
+                    for (int j = 0; j < NJ; ++j) accB[j] = mfma16(av[s], b[j], accB[j]);
                 }
-                P[u][r] = acc[r];
             }
-            __syncthreads();                  // W and the whole negatives tile are visible
+        }
+    };
 
-            {
-                const float* wa = Ws + (16 * rq + l15) * kFWS + 64 * kh + 4 * gq;
-                const float* nbB = Ns + (64 * kh + 4 * gq) * QS + l15;
-#pragma unroll
-                for (int G = 0; G < 4; ++G) {
-                    if (n0 + 64 * kh + 16 * G < N) {          // uniform per wave
-                        const float4 a4 = lds4(wa + 16 * G);
-                        const float av[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-                        for (int s = 0; s < 4; ++s) {
-                            const float* nrow = nbB + (16 * G + s) * QS;
-                            float b[NJ];
-#pragma unroll
-                            for (int j = 0; j < NJ; ++j) b[j] = nrow[16 * j];
-#pragma unroll
-                            for (int j = 0; j < NJ; ++j) accB[j] = mfma16(av[s], b[j], accB[j]);
-                        }
+    // ---- the sweep ---------------------------------------------------------------------------------
+    // half-step h: group 0 scores tile h/2 (h even) or accumulates it (h odd); group 1 does the
+    // same one half-step later.  Every branch below is uniform per wave, and the barrier count
+    // depends on the tile count only.
+    static_for<0, 2 * kFMaxSteps + 1>([&](auto Hh) {
+        constexpr int h = decltype(Hh)::value;
+        if (h <= ntiles) {
+            if constexpr (h % 2 == 0) {
+                if (grp == 0) {
+                    if constexpr (h / 2 < kFMaxSteps) {
+                        if (tile_of(h / 2) < ntiles) score_tile(std::integral_constant<int, h / 2>{});
+                    }
+                } else {
+                    if constexpr (h >= 2) {
+                        if (tile_of(h / 2 - 1) < ntiles) accumulate_tile(h / 2 - 1);
                     }
                 }
+            } else {
+                if (grp == 0) {
+                    if (tile_of(h / 2) < ntiles) accumulate_tile(h / 2);
+                } else {
+                    if (tile_of(h / 2) < ntiles) score_tile(std::integral_constant<int, h / 2>{});
+                }
             }
-            __syncthreads();                  // the tile and W may be overwritten
+            __syncthreads();
         }
     });
 
@@ -362,7 +400,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             f32x4 l = f32x4{0.f, 0.f, 0.f, 0.f};
             static_for<0, kFMaxSteps>([&](auto U) {
                 constexpr int u = decltype(U)::value;
-                if (u < ntiles) l += P[u][r];
+                if (tile_of(u) < ntiles) l += P[u][r];
             });
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -374,7 +412,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 if (l15 == 0) Lw[w * kFRow + 16 * r + 4 * gq + v] = s;
             }
         }
-        if (__ballot(out_of_range) != 0ull && lane == 0) flag_s[w] = 1u;
+        if (__ballot(top > limit) != 0ull && lane == 0) flag_s[w] = 1u;
     }
     __syncthreads();
     if (tid < kFRow) {
@@ -403,13 +441,13 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     }
     __syncthreads();
 
-    // ---- G_neg, 128 negatives at a time; every wave works on its own 16 rows --------------------
+    // ---- G_neg, tile by tile; every wave works on its own 16 negatives, no workgroup barrier ------
     float* St = Ns + w * (16 * QS);           // private staging area, used as [16][d] without padding
     const float* qt = QT + l15 * kFQT + 4 * gq;
     static_for<0, kFMaxSteps>([&](auto U) {
         constexpr int u = decltype(U)::value;
-        if (u < ntiles) {
-            const int n0 = u * kFSuper + 16 * w;
+        if (tile_of(u) < ntiles) {
+            const int n0 = tile_of(u) * kFTile + 16 * wl;
             f32x4 accC[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; ++j) accC[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -455,13 +493,13 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     __syncthreads();
 
     // ---- epilogue: the two halves of G_Q to LDS, chain rule, gradient rows of the positives -----
-    float* Gs = Ns + kh * (kFRow * QS);       // [2][64][QS]
+    float* Gs = Ns + grp * (kFRow * QS);      // [2][64][QS]: one partial sum per wave group
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int col = 16 * j + l15;
         if (col < d) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Gs[(16 * rq + 4 * gq + v) * QS + col] = accB[j][v];
+            for (int v = 0; v < 4; ++v) Gs[(16 * wl + 4 * gq + v) * QS + col] = accB[j][v];
         }
     }
     __syncthreads();
@@ -517,7 +555,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 // expensive to compile); every other shape takes the general kernel.
 bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp) {
     if (bp.loss != LEGEND_LOSS_SOFTMAX || bp.atomic_mode != 0) return false;
-    if (g.N > kFMaxSteps * kFSuper || g.N > kIdsLds || g.rows_tile > kFRow) return false;
+    if (g.N > 2 * kFMaxSteps * kFTile || g.N > kIdsLds || g.rows_tile > kFRow) return false;
     return bp.dim == 100;
 }
 
