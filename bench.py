@@ -227,7 +227,10 @@ def main() -> int:
     Q = sides * (-(-P // w.chunk_size)) * N
     u_b = uniq / max(nbatches, 1)
     alg_bytes = 12 * P + 4 * Q + 4 * d * (2 * P + Q) + 16 * d * u_b
-    roofline = {"kernel": ("k_chunk_wide" if w.dim > 128 else "k_chunk") + " (gather + scores + loss + backward, fp32 MFMA)", "bound": "mfma",
+    single_sweep = (w.dim == 100 and w.loss == graphs.LOSS_SOFTMAX and w.num_negs <= 1024 and args.update_mode != "atomic"
+                    and os.environ.get("LEGEND_NO_FAST_CHUNK") != "1")
+    kname = "k_chunk_wide" if w.dim > 128 else ("k_chunk_fast" if single_sweep else "k_chunk")
+    roofline = {"kernel": kname + " (gather + scores + loss + backward, fp32 MFMA)", "bound": "mfma",
                 "achieved": round(achieved_tflops, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4),
                 "traffic": CHUNK_TRAFFIC_BYTES.get(w.name),

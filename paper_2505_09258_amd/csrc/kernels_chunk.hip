@@ -577,15 +577,18 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    return g.P > 0 && chunk_fast_applies(g, bp) && !ws.no_fast_path;
+}
+
+// redo = false: the batch computation proper.  redo = true (only after a single-sweep launch):
+// the two-sweep kernel over the workgroups the single-sweep kernel flagged as out of range.
+hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws, bool redo) {
     if (g.P <= 0) return hipSuccess;
-    const uint32_t* only_if = nullptr;
-    if (chunk_fast_applies(g, bp) && !ws.no_fast_path) {
-        // single sweep first; whatever it flags as out of range is redone by the two-sweep kernel
-        hipError_t e = launch_chunks_fast(st, g, bp, ws);
-        if (e != hipSuccess) return e;
-        only_if = ws.redo;
-    }
+    const bool single = chunks_use_single_sweep(g, bp, ws);
+    if (redo && !single) return hipSuccess;
+    if (!redo && single) return launch_chunks_fast(st, g, bp, ws);
+    const uint32_t* only_if = redo ? ws.redo : nullptr;
     // the dimensions of the paper's workloads get kernels with the dimension folded in
     if (bp.dim == 100) return launch_chunks_nb<4, 100>(st, g, bp, ws, only_if);
     if (bp.dim == 32) return launch_chunks_nb<1, 32>(st, g, bp, ws, only_if);

@@ -14,6 +14,7 @@ enum KernelClass : int {
     KC_SORT,          // radix sort passes (histogram, scan, scatter) + segment heads
     KC_CHUNK,         // fused gather + scores + loss + backward per chunk (MFMA)
     KC_UPDATE,        // segmented gradient reduce + Adagrad
+    KC_CHUNK_REDO,    // two-sweep kernel over the chunks the single-sweep kernel handed back
     KC_MISC,          // loss reduction, validation, scoring
     KC_COUNT
 };
@@ -95,7 +96,9 @@ hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace&
 hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws);
 // sort + segment heads; small inputs take a single-workgroup kernel
 hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
-hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+// redo = false: the batch computation; redo = true: second launch over the workgroups the single-sweep kernel flagged
+bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws, bool redo);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, int32_t rows_per_partition);
 hipError_t launch_update_atomic(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);

@@ -32,7 +32,7 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
-const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "misc"};
+const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "chunk_redo", "misc"};
 
 struct ProfSpan {
     int cls;
@@ -63,9 +63,12 @@ struct legend_ctx {
     hipStream_t compute = nullptr, copy = nullptr;
     bool own_compute = false, own_copy = false;
     hipEvent_t ev_fence = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
-    hipStream_t aux = nullptr;              // sorts the batch's keys while the chunk kernel runs
-    hipEvent_t ev_keys = nullptr, ev_sorted = nullptr;
-    Workspace ws{};
+    hipStream_t aux = nullptr;              // index side (negatives, keys, sort) of the next batch, one batch ahead
+    hipEvent_t ev_start = nullptr;          // compute stream has reached the start of a bucket call
+    hipEvent_t ev_index[2] = {nullptr, nullptr};    // index side of a batch complete (per workspace)
+    hipEvent_t ev_updated[2] = {nullptr, nullptr};  // update of a batch complete: its index buffers are free
+    Workspace ws{};                         // even batches of a call; also every serial path
+    Workspace ws_odd{};                     // odd batches: own index-side buffers, the rest shared with ws
     BatchGeom gmax{};
     int key_bits = 0;
     int32_t* edges_dev = nullptr;
@@ -78,7 +81,7 @@ struct legend_ctx {
     double prof_ms[KC_COUNT] = {0};
     int64_t prof_launches[KC_COUNT] = {0};
     int64_t batches_done = 0;
-    bool serial_sort = false;               // LEGEND_SERIAL_SORT=1: keep the sort on the compute stream (for per-kernel timing)
+    bool serial_sort = false;               // LEGEND_SERIAL_SORT=1: everything on the compute stream, batch after batch (for per-kernel timing)
     bool keep_loss = false;                 // epoch driver: do not reset the device loss sum per bucket
     bool part_tables_dirty = false;         // d_part_emb / d_part_state lag behind part_slot
     bool fatal = false;
@@ -247,12 +250,16 @@ void free_ctx(legend_ctx* c) {
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
-                     c->ws.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.loss_sum, c->edges_dev,
+                     c->ws.counters, c->ws_odd.neg_ids, c->ws_odd.keys[0], c->ws_odd.keys[1], c->ws_odd.vals[0], c->ws_odd.vals[1],
+                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.loss_sum, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
     if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
-    if (c->ev_keys) (void)hipEventDestroy(c->ev_keys);
-    if (c->ev_sorted) (void)hipEventDestroy(c->ev_sorted);
+    if (c->ev_start) (void)hipEventDestroy(c->ev_start);
+    for (int k = 0; k < 2; ++k) {
+        if (c->ev_index[k]) (void)hipEventDestroy(c->ev_index[k]);
+        if (c->ev_updated[k]) (void)hipEventDestroy(c->ev_updated[k]);
+    }
     if (c->ev_fence) (void)hipEventDestroy(c->ev_fence);
     if (c->ev_t0) (void)hipEventDestroy(c->ev_t0);
     if (c->ev_t1) (void)hipEventDestroy(c->ev_t1);
@@ -358,26 +365,17 @@ uint64_t batch_hash_prefix(const legend_ctx* c, int epoch, int i, int j, int64_t
     return h;
 }
 
-// index side of one batch: negatives, keys, sort, segment heads
-// `side_stream`: sort on the auxiliary stream; the caller orders the update after ev_sorted.
-// The sort depends only on the keys, the chunk kernel only on the negative ids, so the two run
-// side by side (the chunk kernel is MFMA/LDS-bound, the sort a chain of small memory-bound kernels).
-int enqueue_index_side(legend_ctx* c, const BatchGeom& g, const BucketParams& bp, int* sorted_buf, bool side_stream) {
+// index side of one batch: negatives, keys, sort, segment heads, all on stream `st` into `ws`
+int enqueue_index_side(legend_ctx* c, hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                       int* sorted_buf) {
     {
-        ProfScope ps(c, KC_PREPARE);
-        HIP_TRY(c, launch_prepare(c->compute, g, bp, c->ws));
-    }
-    hipStream_t st = c->compute;
-    if (side_stream) {
-        HIP_TRY(c, hipEventRecord(c->ev_keys, c->compute));
-        HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_keys, 0));
-        st = c->aux;
+        ProfScope ps(c, KC_PREPARE, st);
+        HIP_TRY(c, launch_prepare(st, g, bp, ws));
     }
     {
         ProfScope ps(c, KC_SORT, st);
-        HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, c->ws, sorted_buf));
+        HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, ws, sorted_buf));
     }
-    if (side_stream) HIP_TRY(c, hipEventRecord(c->ev_sorted, c->aux));
     return LEGEND_OK;
 }
 
@@ -469,8 +467,11 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     else { INIT_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)); c->own_copy = true; }
     INIT_TRY(hipEventCreateWithFlags(&c->ev_fence, hipEventDisableTiming));
     INIT_TRY(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
-    INIT_TRY(hipEventCreateWithFlags(&c->ev_keys, hipEventDisableTiming));
-    INIT_TRY(hipEventCreateWithFlags(&c->ev_sorted, hipEventDisableTiming));
+    INIT_TRY(hipEventCreateWithFlags(&c->ev_start, hipEventDisableTiming));
+    for (int k = 0; k < 2; ++k) {
+        INIT_TRY(hipEventCreateWithFlags(&c->ev_index[k], hipEventDisableTiming));
+        INIT_TRY(hipEventCreateWithFlags(&c->ev_updated[k], hipEventDisableTiming));
+    }
     INIT_TRY(hipEventCreate(&c->ev_t0));
     INIT_TRY(hipEventCreate(&c->ev_t1));
     INIT_TRY(hipEventRecord(c->ev_fence, c->compute));
@@ -550,6 +551,25 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         if (!(w.fast_limit <= 60.f)) w.fast_limit = 60.f;     // a test knob: it can only tighten the limit
     }
     INIT_RC(dev_alloc(c, &w.loss_sum, 1));
+    {
+        // second set of index-side buffers, so that the index side of batch b+1 can be built while
+        // batch b is still being computed and applied
+        Workspace& o = c->ws_odd;
+        o = w;
+        o.neg_ids = nullptr; o.keys[0] = o.keys[1] = nullptr; o.vals[0] = o.vals[1] = nullptr;
+        o.ghist = nullptr; o.scan_tmp = nullptr; o.uniq_keys = nullptr; o.seg_start = nullptr; o.counters = nullptr;
+        INIT_RC(dev_alloc(c, &o.neg_ids, (size_t)c->gmax.sides * c->gmax.nchunks * c->gmax.N));
+        for (int k = 0; k < 2; ++k) {
+            INIT_RC(dev_alloc(c, &o.keys[k], (size_t)occ));
+            INIT_RC(dev_alloc(c, &o.vals[k], (size_t)occ));
+        }
+        INIT_RC(dev_alloc(c, &o.ghist, (size_t)nblk * 256));
+        INIT_RC(dev_alloc(c, &o.scan_tmp, (size_t)std::max<int64_t>(nblk, (nblk * 256 + 2047) / 2048) + 2));
+        INIT_RC(dev_alloc(c, &o.uniq_keys, (size_t)occ));
+        INIT_RC(dev_alloc(c, &o.seg_start, (size_t)occ + 1));
+        INIT_RC(dev_alloc(c, &o.counters, 4));
+        INIT_TRY(hipMemset(o.counters, 0, 4 * sizeof(uint32_t)));
+    }
     INIT_TRY(hipMemset(w.counters, 0, 4 * sizeof(uint32_t)));
     INIT_TRY(hipMemset(w.uniq_total, 0, sizeof(unsigned long long)));
     INIT_TRY(hipMemset(w.loss_sum, 0, sizeof(double)));
@@ -635,29 +655,69 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
     const int B = c->cfg.batch_size;
     const int64_t nb = batch_end - batch_begin;
     int64_t edges_done = 0;
-    for (int64_t b = batch_begin; b < batch_end; ++b) {
+    // The index side of a batch (negative ids, sort keys, sort, segment heads) depends on the edge
+    // list and the counter hash only.  It is built one batch ahead on the auxiliary stream, into
+    // the workspace the batch before last has released, while the compute stream runs the chunk
+    // and update kernels of the current batch.
+    auto batch_params = [&](int64_t b, BatchGeom* g) {
         const int P = (int)std::min<int64_t>(B, m - b * B);
-        edges_done += P;
-        BatchGeom g = make_geom(c, P);
+        *g = make_geom(c, P);
         bp.batch_lo = b * B;
         bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, b);
-        int sorted = 0;
-        rc = enqueue_index_side(c, g, bp, &sorted, !c->serial_sort);
+    };
+    int sorted_of[2] = {0, 0};
+    const bool ahead = !c->serial_sort;
+    if (ahead && batch_begin < batch_end) {
+        BatchGeom g0;
+        batch_params(batch_begin, &g0);
+        HIP_TRY(c, hipEventRecord(c->ev_start, c->compute));        // edges staged, earlier calls done with the workspaces
+        HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_start, 0));
+        rc = enqueue_index_side(c, c->aux, g0, bp, c->ws, &sorted_of[0]);
         if (rc) return rc;
+        HIP_TRY(c, hipEventRecord(c->ev_index[0], c->aux));
+    }
+    for (int64_t b = batch_begin; b < batch_end; ++b) {
+        const int cur = ahead ? (int)((b - batch_begin) & 1) : 0;
+        const Workspace& ws = cur ? c->ws_odd : c->ws;
+        BatchGeom g;
+        batch_params(b, &g);
+        edges_done += g.P;
+        if (ahead) {
+            HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_index[cur], 0));
+        } else {
+            rc = enqueue_index_side(c, c->compute, g, bp, ws, &sorted_of[0]);
+            if (rc) return rc;
+        }
         {
             ProfScope ps(c, KC_CHUNK);
-            HIP_TRY(c, launch_chunks(c->compute, g, bp, c->ws));
+            HIP_TRY(c, launch_chunks(c->compute, g, bp, ws, false));
+        }
+        if (chunks_use_single_sweep(g, bp, ws)) {
+            ProfScope ps(c, KC_CHUNK_REDO);
+            HIP_TRY(c, launch_chunks(c->compute, g, bp, ws, true));
         }
         {
             ProfScope ps(c, KC_MISC);
-            HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, c->ws));
+            HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, ws));
         }
-        if (!c->serial_sort) HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_sorted, 0));
+        if (ahead && b + 1 < batch_end) {
+            // next batch's index side: its workspace is free once the update of batch b-1 is done
+            const int nxt = cur ^ 1;
+            BatchGeom gn;
+            BucketParams keep = bp;
+            batch_params(b + 1, &gn);
+            if (b > batch_begin) HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_updated[nxt], 0));
+            rc = enqueue_index_side(c, c->aux, gn, bp, nxt ? c->ws_odd : c->ws, &sorted_of[nxt]);
+            if (rc) return rc;
+            HIP_TRY(c, hipEventRecord(c->ev_index[nxt], c->aux));
+            bp = keep;
+        }
         {
             ProfScope ps(c, KC_UPDATE);
-            if (bp.atomic_mode) HIP_TRY(c, launch_update_atomic(c->compute, g, bp, c->ws));
-            else HIP_TRY(c, launch_update(c->compute, g, bp, c->ws, c->ws.vals[sorted], (int32_t)c->Rp));
+            if (bp.atomic_mode) HIP_TRY(c, launch_update_atomic(c->compute, g, bp, ws));
+            else HIP_TRY(c, launch_update(c->compute, g, bp, ws, ws.vals[sorted_of[cur]], (int32_t)c->Rp));
         }
+        if (ahead) HIP_TRY(c, hipEventRecord(c->ev_updated[cur], c->compute));
         c->batches_done += 1;
     }
     if (stats) HIP_TRY(c, hipEventRecord(c->ev_t1, c->compute));
@@ -786,7 +846,7 @@ int legend_debug_batch_indices(legend_ctx* c, int32_t i, int32_t j, const int32_
     unsigned long long saved = 0;
     HIP_TRY(c, hipMemcpyAsync(&saved, c->ws.uniq_total, sizeof saved, hipMemcpyDeviceToHost, c->compute));
     HIP_TRY(c, hipStreamSynchronize(c->compute));
-    rc = enqueue_index_side(c, g, bp, &sorted, false);
+    rc = enqueue_index_side(c, c->compute, g, bp, c->ws, &sorted);
     if (rc) return rc;
     uint32_t nu = 0;
     HIP_TRY(c, hipMemcpyAsync(&nu, c->ws.counters, sizeof nu, hipMemcpyDeviceToHost, c->compute));
