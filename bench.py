@@ -22,9 +22,9 @@ if ROOT not in sys.path:
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
-# HBM bytes per k_chunk launch from the rocprofv3 counter runs summarised in
+# HBM bytes per k_chunk_fast launch from the rocprofv3 counter runs summarised in
 # profiles/c2_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB, calibrated on a copy)
-CHUNK_TRAFFIC_BYTES = {"c2": int((485520.2 * 2.0 + 439878.7) * 1024)}
+CHUNK_TRAFFIC_BYTES = {"c2": int((275977.3 * 2.0 + 442509.5) * 1024)}
 
 
 def log(*a):
@@ -233,7 +233,7 @@ def main() -> int:
     roofline = {"kernel": kname + " (gather + scores + loss + backward, fp32 MFMA)", "bound": "mfma",
                 "achieved": round(achieved_tflops, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4),
-                "traffic": CHUNK_TRAFFIC_BYTES.get(w.name),
+                "traffic": CHUNK_TRAFFIC_BYTES.get(w.name) if single_sweep else None,
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": round(chunk_ms, 4)}
 
     # ---- second pass with every kernel class event-timed (separate from the timed region) ----
