@@ -54,6 +54,20 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
         edges += stats["edges"]
     L.legend_sync(ctx)
     wall = time.perf_counter() - t0
+    log(f"[bench] {K} epoch(s), prefetch {'off' if args.no_overlap else 'on'}: {wall:.2f} s, {edges / wall:.3e} edges/s")
+    ablation = None
+    if args.ablation and not args.no_overlap:
+        # the same epochs again with every swap serialised (the paper's "without prefetching")
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        edges2 = 0
+        for ep in range(W + K, W + 2 * K):
+            edges2 += L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=False)["edges"]
+        L.legend_sync(ctx)
+        wall2 = time.perf_counter() - t1
+        log(f"[bench] {K} epoch(s), prefetch off: {wall2:.2f} s, {edges2 / wall2:.3e} edges/s")
+        ablation = {"prefetch_off_value": round(edges2 / wall2, 1), "prefetch_off_s_per_epoch": round(wall2 / K, 3),
+                    "prefetch_on_s_per_epoch": round(wall / K, 3)}
     out = {
         "metric": "edges/sec trained (1 GPU)", "value": round(edges / wall, 1), "unit": "edges/s", "n_gpus": 1,
         "steps": K, "warmup": W, "ms_per_step": round(wall * 1e3 / K, 3), "higher_is_better": True, "scaling": "weak",
@@ -66,6 +80,8 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
         "epoch": {"batches": stats["batches"], "swaps": stats["swaps"], "buffer_states": stats["buffer_states"],
                   "bytes_per_swap": stats["bytes_per_swap"], "loss_sum": stats["loss_sum"]},
     }
+    if ablation:
+        out["prefetch_ablation"] = ablation
     L.legend_destroy(ctx)
     print(json.dumps(out), flush=True)
     return 0
@@ -88,6 +104,7 @@ def main() -> int:
                          "instead of K resident batches; --steps then counts epochs")
     ap.add_argument("--capacity", type=int, default=0, help="buffer slots for --epoch (0: all partitions resident)")
     ap.add_argument("--no-overlap", action="store_true", help="--epoch: serialize swaps (the paper's 'without prefetching')")
+    ap.add_argument("--ablation", action="store_true", help="--epoch: afterwards run the same number of epochs with swaps serialised")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -107,9 +124,19 @@ def main() -> int:
         w = graphs.scaled(w, args.scale)
 
     t0 = time.time()
-    src, rel_ids, dst = graphs.generate_edges(w, args.seed)
-    buckets = graphs.bucket_edges(w, src, rel_ids, dst)
+    last = [time.time()]
+
+    def progress(what):
+        def cb(done, total):
+            if time.time() - last[0] > 30:          # a long generation keeps reporting
+                last[0] = time.time()
+                log(f"[bench] {what}: {done}/{total} after {time.time() - t0:.0f}s")
+        return cb
+
+    src, rel_ids, dst = graphs.generate_edges(w, args.seed, progress=progress("edges"))
+    buckets = graphs.bucket_edges(w, src, rel_ids, dst, progress=progress("buckets"))
     del src, rel_ids, dst
+    log(f"[bench] edges bucketed after {time.time() - t0:.1f}s")
     node, rel = graphs.init_tables(w, args.seed)
     log(f"[bench] generated {w.name}: {w.num_nodes} nodes, {w.num_edges} edges, {len(buckets)} buckets in {time.time() - t0:.1f}s")
 

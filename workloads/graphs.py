@@ -120,8 +120,9 @@ def _sample_ranks(rng: np.random.Generator, count: int, size: int, skew: Tuple[f
     return k
 
 
-def generate_edges(w: Workload, seed: int, block: int = 1 << 24):
-    """Global edge list as three int64/int32 arrays (src, rel, dst), seeded."""
+def generate_edges(w: Workload, seed: int, block: int = 1 << 24, progress=None):
+    """Global edge list as three int64/int32 arrays (src, rel, dst), seeded.
+    `progress(done, total)` is called after every block (long generations report through it)."""
     rng = np.random.default_rng([seed, 0xE])
     perm = np.random.default_rng([seed, 0xF]).permutation(w.num_nodes)
     src = np.empty(w.num_edges, np.int64)
@@ -133,10 +134,12 @@ def generate_edges(w: Workload, seed: int, block: int = 1 << 24):
         dst[lo:hi] = perm[_sample_ranks(rng, hi - lo, w.num_nodes, w.dst_skew)]
         if w.num_relations > 1:
             rel[lo:hi] = _sample_ranks(rng, hi - lo, w.num_relations, w.rel_skew)
+        if progress is not None:
+            progress(hi, w.num_edges)
     return src, rel, dst
 
 
-def bucket_edges(w: Workload, src: np.ndarray, rel: np.ndarray, dst: np.ndarray):
+def bucket_edges(w: Workload, src: np.ndarray, rel: np.ndarray, dst: np.ndarray, progress=None):
     """Stable partition of the edges into n*n buckets.
 
     Returns {(i, j): int32 [m_ij, 3]} with columns (src_local, rel, dst_local);
@@ -146,6 +149,9 @@ def bucket_edges(w: Workload, src: np.ndarray, rel: np.ndarray, dst: np.ndarray)
     pi = src // rp
     pj = dst // rp
     bid = (pi * n + pj).astype(np.int16 if n * n < 32768 else np.int32)
+    del pi, pj
+    if progress is not None:
+        progress(0, n * n)
     order = np.argsort(bid, kind="stable")
     counts = np.bincount(bid, minlength=n * n)
     out = {}
@@ -159,6 +165,8 @@ def bucket_edges(w: Workload, src: np.ndarray, rel: np.ndarray, dst: np.ndarray)
         e[:, 1] = rel[idx]
         e[:, 2] = dst[idx] - j * rp
         out[(i, j)] = e
+        if progress is not None:
+            progress(b + 1, n * n)
     return out
 
 
