@@ -1,19 +1,21 @@
 // Single-sweep batch computation for the paper's large workloads: Eq. 1 loss, dim = 100, at most
 // 1024 negatives per chunk (paper Sec. 2.1 stage 5, Sec. 6).  The general kernel reads the
 // chunk's negatives twice because the row log-sum-exp must be known before any gradient.  Here
-// the softmax numerators are taken against a reference known up front, the positive score f_e:
-//     P_en = exp(S_en - f_e),   l_e = sum_n P_en,   W_en = P_en / l_e,   loss_e = log l_e,
+// the softmax numerators are taken against a reference m_e fixed after the first tile of
+// negatives, the row maximum over that tile (the tiles interleave the chunk's negatives, so the
+// first one is an even sample of them):
+//     P_en = exp(S_en - m_e),   l_e = sum_n P_en,   W_en = P_en / l_e,   loss_e = m_e + log l_e - f_e,
 // so one sweep over the negatives yields the unnormalised G_Q = sum_n P_en theta_n, and the P
 // blocks (64 x N values, the paper's "Intermediate Result 3") stay in the register file of the
 // workgroup: eight waves, 128 registers per lane each, one workgroup per compute unit.  After
 // the sweep the rows of Q are scaled by 1 / l_e and G_neg = P^T (Q / l) is formed straight from
-// the stored blocks.  If some S_en - f_e exceeds a limit (60 unless overridden; exp stays far
-// from overflow) or a row sum under- or overflows, the workgroup writes nothing and flags
-// itself; the general two-sweep kernel then redoes it.
+// the stored blocks.  If some S_en - m_e exceeds a limit (60 unless overridden; exp stays far
+// from overflow) or a row sum is not finite, the workgroup writes nothing and flags itself; the
+// general two-sweep kernel then redoes it.
 //
 // Work split (16x16x4 fp32 MFMA; g = lane / 16, l15 = lane % 16).  The eight waves form two
-// groups of four; the negatives are cut into tiles of 64, even tiles for group 0, odd ones for
-// group 1; wave wl of a group:
+// groups of four; the negatives are dealt into tiles of 64 (negative n sits in tile n mod T),
+// even tiles for group 0, odd ones for group 1; wave wl of a group:
 //   sweep, per tile of its group:
 //     scores    owns the 16 negatives 16wl..16wl+15 of the tile, which it has gathered itself,
 //               and all 64 rows: four 16x16 blocks S[16r + 4g + v][16wl + l15], r, v = 0..3;
@@ -26,7 +28,7 @@
 //   afterwards, per tile and with no workgroup barrier:
 //     G_neg     contracts its stored P (as the A operand of P^T: lane = negative, k = row)
 //               with (Q / l)^T read from LDS over all 64 rows, stages its 16 gradient rows in
-//               its own LDS area and writes them out as one contiguous 6400-byte run.
+//               its own LDS area and writes them out as whole rows of 16-byte pieces.
 #include <type_traits>
 
 #include "chunk_common.h"
@@ -69,7 +71,7 @@ struct FastShape {
     static constexpr int q_floats = kFRow * QS;
     static constexpr int n_floats = 2 * kFTile * QS + 16;   // one tile per wave group; + slack: column blocks run past the last row
     static constexpr int w_floats = 2 * kFRow * kFWS > 16 * NJ * kFQT ? 2 * kFRow * kFWS : 16 * NJ * kFQT;
-    static constexpr size_t lds_bytes = sizeof(float) * (q_floats + n_floats + w_floats + 4 * kFRow + 16 + kIdsLds);
+    static constexpr size_t lds_bytes = sizeof(float) * (q_floats + n_floats + w_floats + 9 * kFRow + 16 + kIdsLds);
 };
 
 // Four elements of an embedding row that are handled together: elements 4c..4c+3, or for
@@ -153,11 +155,13 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     float* Qs = smem;
     float* Ns = Qs + Sh::q_floats;
     float* Ws = Ns + Sh::n_floats;              // sweep: W[2][64][68]; before: partial f; afterwards: row sums, then (Q/l)^T [112][68]
-    float* ref_s = Ws + Sh::w_floats;           // [64] positive scores = softmax reference
+    float* ref_s = Ws + Sh::w_floats;           // [64] softmax reference: row maximum over the first tile
     float* scale_s = ref_s + kFRow;             // [64] 1 / l_e
     float* logl_s = scale_s + kFRow;            // [64] log l_e
     float* rowloss_s = logl_s + kFRow;          // [64]
-    uint32_t* flag_s = reinterpret_cast<uint32_t*>(rowloss_s + kFRow);   // [16]
+    float* f_s = rowloss_s + kFRow;             // [64] positive scores
+    float* mx_s = f_s + kFRow;                  // [4][64] per-wave row maxima of the first tile
+    uint32_t* flag_s = reinterpret_cast<uint32_t*>(mx_s + 4 * kFRow);    // [16]
     int32_t* ids_s = reinterpret_cast<int32_t*>(flag_s + 16);            // [kIdsLds]
 
     const int tid = threadIdx.x;
@@ -236,7 +240,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         if (tid < kFRow) {
             float f = 0.f;
             for (int cc = 0; cc < IPR; ++cc) f += part_s[tid * IPR + cc];
-            ref_s[tid] = tid < nrows ? f : 1e30f;     // rows past the chunk: every numerator becomes 0
+            f_s[tid] = f;
         }
     }
 
@@ -249,18 +253,23 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     const int gc0 = (lane & 31) * 4;
     const int gcol_ld = gc0 < d ? gc0 : 0;
     typedef __attribute__((address_space(3))) const int32_t* lds_ids_t;
-    auto gather_issue = [&](int n0) __attribute__((always_inline)) {
+    // Column k of tile t is negative k * ntiles + t: every tile is an even sample of the chunk's
+    // negatives (uniform and degree-weighted ones alike), so the row maxima of the first tile
+    // are a good reference for all of them.
+    const int ntiles = (N + kFTile - 1) / kFTile;
+    auto neg_of = [&](int t, int k) { return k * ntiles + t; };
+    auto gather_issue = [&](int t) __attribute__((always_inline)) {
         int32_t idv[STEPS];
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) idv[s] = ((lds_ids_t)ids_s)[min(n0 + wl * 16 + s * 2 + grow_lane, N - 1)];
+        for (int s = 0; s < STEPS; ++s) idv[s] = ((lds_ids_t)ids_s)[min(neg_of(t, wl * 16 + s * 2 + grow_lane), N - 1)];
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) pf[s] = *reinterpret_cast<const float4*>(En + (int64_t)idv[s] * d + gcol_ld);
     };
-    auto gather_commit = [&](int n0) __attribute__((always_inline)) {
-        if (n0 + kFTile > N) {                // last tile: rows past the last negative are zero
+    auto gather_commit = [&](int t) __attribute__((always_inline)) {
+        if (neg_of(t, kFTile - 1) >= N) {     // columns past the last negative are zero rows
 #pragma unroll
             for (int s = 0; s < STEPS; ++s)
-                if (n0 + wl * 16 + s * 2 + grow_lane >= N) pf[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (neg_of(t, wl * 16 + s * 2 + grow_lane) >= N) pf[s] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
         if (gc0 < d) {
 #pragma unroll
@@ -273,24 +282,26 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     // apart: while one scores a tile and takes the exponentials (matrix pipe, then vector ALU
     // and LDS writes), the other multiplies its previous W tile into G_Q (matrix pipe with LDS
     // reads), so that the two waves of a SIMD want different units most of the time.
-    const int ntiles = (N + kFTile - 1) / kFTile;
     auto tile_of = [&](int i) { return 2 * i + grp; };
 
     f32x4 P[kFMaxSteps][4];                   // the chunk's softmax numerators owned by this wave
     f32x4 accB[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) accB[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float top = -1e30f;                       // largest S - f seen
+    float top = -1e30f;                       // largest S - reference seen
 
     __syncthreads();                          // ids, Q and the references are in LDS
-    if (tile_of(0) < ntiles) gather_issue(tile_of(0) * kFTile);
+    if (tile_of(0) < ntiles) gather_issue(tile_of(0));
 
     // scores and numerators of tile i of this group; P[i] is written
-    auto score_tile = [&](auto I) __attribute__((always_inline)) {
+    // With FIRST (tile 0, wave group 0) the reference is made on the way: the row maxima of this
+    // tile, exchanged between the four waves across one extra workgroup barrier.
+    auto score_tile = [&](auto I, auto FIRST) __attribute__((always_inline)) {
         constexpr int i = decltype(I)::value;
-        const int n0 = tile_of(i) * kFTile;
-        gather_commit(n0);                    // own rows only; their last readers are a barrier behind
-        if (tile_of(i + 1) < ntiles) gather_issue(n0 + 2 * kFTile);
+        constexpr bool first = decltype(FIRST)::value;
+        const int t = tile_of(i);
+        gather_commit(t);                     // own rows only; their last readers are a barrier behind
+        if (tile_of(i + 1) < ntiles) gather_issue(t + 2);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -322,13 +333,49 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[r] = mfma16(Qs[(16 * r + l15) * QS + k], b, acc[r]);
         }
-        if (n0 + kFTile > N && n0 + 16 * wl + l15 >= N) {      // columns past the last negative
+        if (neg_of(t, 16 * wl + l15) >= N) {                  // columns past the last negative
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[r] = f32x4{-1e30f, -1e30f, -1e30f, -1e30f};
         }
+        float4 reff[4];
+        if constexpr (first) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float m = acc[r][v];
+                    m = fmaxf(m, wave_shfl_xor(m, 1));
+                    m = fmaxf(m, wave_shfl_xor(m, 2));
+                    m = fmaxf(m, wave_shfl_xor(m, 4));
+                    m = fmaxf(m, wave_shfl_xor(m, 8));
+                    if (l15 == 0) mx_s[wl * kFRow + 16 * r + 4 * gq + v] = m;
+                }
+            }
+            __syncthreads();                  // the other wave group passes the same barrier idle
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float4 m = lds4(mx_s + 16 * r + 4 * gq);
+#pragma unroll
+                for (int ww = 1; ww < 4; ++ww) {
+                    const float4 o = lds4(mx_s + ww * kFRow + 16 * r + 4 * gq);
+                    m.x = fmaxf(m.x, o.x); m.y = fmaxf(m.y, o.y); m.z = fmaxf(m.z, o.z); m.w = fmaxf(m.w, o.w);
+                }
+                // rows past the chunk: a huge reference turns every numerator into 0
+                const int row = 16 * r + 4 * gq;
+                m.x = row + 0 < nrows ? m.x : 1e30f;
+                m.y = row + 1 < nrows ? m.y : 1e30f;
+                m.z = row + 2 < nrows ? m.z : 1e30f;
+                m.w = row + 3 < nrows ? m.w : 1e30f;
+                reff[r] = m;
+                if (wl == 0 && l15 == 0) *reinterpret_cast<float4*>(ref_s + row) = m;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) reff[r] = lds4(ref_s + 16 * r + 4 * gq);
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float4 rf = lds4(ref_s + 16 * r + 4 * gq);
+            const float4 rf = reff[r];
             const float refv[4] = {rf.x, rf.y, rf.z, rf.w};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -343,12 +390,12 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     };
     // G_Q += W tile x negatives tile of this group: wave wl has rows 16wl..16wl+15, all columns
     auto accumulate_tile = [&](int i) __attribute__((always_inline)) {
-        const int n0 = tile_of(i) * kFTile;
+        const int t = tile_of(i);
         const float* wa = Wg + (16 * wl + l15) * kFWS + 4 * gq;
         const float* nbB = Ng + (4 * gq) * QS + l15;
 #pragma unroll
         for (int G = 0; G < 4; ++G) {
-            if (n0 + 16 * G < N) {            // uniform
+            if (neg_of(t, 16 * G) < N) {      // uniform: the group has a live column
                 const float4 a4 = lds4(wa + 16 * G);
                 const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
@@ -374,9 +421,11 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             if constexpr (h % 2 == 0) {
                 if (grp == 0) {
                     if constexpr (h / 2 < kFMaxSteps) {
-                        if (tile_of(h / 2) < ntiles) score_tile(std::integral_constant<int, h / 2>{});
+                        if (tile_of(h / 2) < ntiles)
+                            score_tile(std::integral_constant<int, h / 2>{}, std::integral_constant<bool, h == 0>{});
                     }
                 } else {
+                    if constexpr (h == 0) __syncthreads();        // the barrier inside group 0's first tile
                     if constexpr (h >= 2) {
                         if (tile_of(h / 2 - 1) < ntiles) accumulate_tile(h / 2 - 1);
                     }
@@ -385,7 +434,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 if (grp == 0) {
                     if (tile_of(h / 2) < ntiles) accumulate_tile(h / 2);
                 } else {
-                    if (tile_of(h / 2) < ntiles) score_tile(std::integral_constant<int, h / 2>{});
+                    if (tile_of(h / 2) < ntiles) score_tile(std::integral_constant<int, h / 2>{}, std::false_type{});
                 }
             }
             __syncthreads();
@@ -447,7 +496,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     static_for<0, kFMaxSteps>([&](auto U) {
         constexpr int u = decltype(U)::value;
         if (tile_of(u) < ntiles) {
-            const int n0 = tile_of(u) * kFTile + 16 * wl;
+            const int t = tile_of(u);
             f32x4 accC[NJ];
 #pragma unroll
             for (int j = 0; j < NJ; ++j) accC[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -457,14 +506,21 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                     float4 b[NJ];
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) b[j] = lds4(qt + 16 * j * kFQT + 16 * r);
+                    // step v contracts over rows 16r + 4g + v: nothing to add once 16r + v is past the chunk
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][0], b[j].x, accC[j]);
+                    if (16 * r + 1 < nrows) {
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][1], b[j].y, accC[j]);
+                        for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][1], b[j].y, accC[j]);
+                    }
+                    if (16 * r + 2 < nrows) {
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][2], b[j].z, accC[j]);
+                        for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][2], b[j].z, accC[j]);
+                    }
+                    if (16 * r + 3 < nrows) {
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][3], b[j].w, accC[j]);
+                        for (int j = 0; j < NJ; ++j) accC[j] = mfma16(P[u][r][3], b[j].w, accC[j]);
+                    }
                 }
             }
 #pragma unroll
@@ -478,12 +534,15 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const int valid4 = (d / 4) * max(0, min(16, N - n0));
-            float* dst = grad + (neg_base + n0) * d;
+            // whole gradient rows leave as 16-byte pieces; row k of the staging area is negative
+            // (16wl + k) * ntiles + t
 #pragma unroll
             for (int s = 0; s < (16 * d / 4 + kWave - 1) / kWave; ++s) {
                 const int idx = lane + kWave * s;
-                if (idx < valid4) *reinterpret_cast<float4*>(dst + 4 * idx) = lds4(St + 4 * idx);
+                const int k = idx / (d / 4);
+                const int n = neg_of(t, 16 * wl + k);
+                if (k < 16 && n < N)
+                    *reinterpret_cast<float4*>(grad + (neg_base + n) * d + 4 * (idx - k * (d / 4))) = lds4(St + 4 * idx);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -541,7 +600,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 if (SCORE != LEGEND_SCORE_DOT) Item::store(grad + (side_base + 2 * (int64_t)g.P + e) * d, it_c[s], gr4);
             }
         }
-        if (tid < kFRow) rowloss_s[tid] = tid < nrows ? logl_s[tid] : 0.f;   // lse - f, the positive score being the reference
+        if (tid < kFRow) rowloss_s[tid] = tid < nrows ? (ref_s[tid] - f_s[tid]) + logl_s[tid] : 0.f;   // lse - f
     }
     __syncthreads();
     if (tid == 0) {

@@ -124,22 +124,23 @@ def test_every_batch_matches_oracle(c):
 
 
 def test_single_sweep_kernel_hands_out_of_range_chunks_to_the_general_kernel(monkeypatch):
-    """The single-sweep kernel gives up on a chunk in which some negative scores more than a
-    limit above its positive; the two-sweep kernel then computes that chunk.  With the limit
-    lowered to 2 the hot rows put some chunks of every batch on either path."""
-    c, limit = _HOT_CASE, 2.0
+    """The single-sweep kernel takes the row maxima over its first tile of negatives (every T-th
+    negative of the chunk, T = number of 64-negative tiles) as the softmax reference and gives up
+    on a chunk in which some score lies more than a limit above its row's reference; the two-sweep
+    kernel then computes that chunk.  With the limit lowered to 1.25 the hot rows put some chunks
+    of every batch on either path."""
+    c, limit = _HOT_CASE, 1.25
     node, rel, edges = _inputs(c)
     rp = -(-c["V"] // c["n"])
+    tiles = -(-c["N"] // 64)
     e = edges[: c["B"]]
     neg = negatives.batch_negatives(_ocfg(c), 1, c["i"], c["j"], 0, e, edges)[0]
     ts = node[c["i"] * rp + e[:, 0]].astype(np.float64)
-    td = node[c["j"] * rp + e[:, 2]].astype(np.float64)
     flagged = []
     for ch in range(neg.shape[0]):
         rows = slice(ch * c["C"], (ch + 1) * c["C"])
         S = ts[rows] @ node[c["j"] * rp + neg[ch]].astype(np.float64).T
-        f = np.sum(ts[rows] * td[rows], axis=1)
-        margin = (S - f[:, None]).max()
+        margin = (S.max(axis=1) - S[:, ::tiles].max(axis=1)).max()
         assert abs(margin - limit) > 1e-3          # no chunk sits on the limit itself
         flagged.append(margin > limit)
     assert 0 < sum(flagged) < len(flagged), flagged
