@@ -9,7 +9,9 @@ f = <u, theta_d> = <theta_s, v>.  Embeddings of dimension d hold ComplEx numbers
 as [real half | imaginary half] (Sec. 6, "first half / last half").
 
 Loss: Eq. 1 as printed (the log-sum-exp runs over the sampled negatives only),
-or a logistic loss.  Both are sums, not means.
+the variant of Eq. 1 whose log-sum-exp also contains the positive score (the
+usual sampled softmax / cross-entropy; not the paper's default), or a logistic
+loss.  All are sums, not means.
 """
 
 from __future__ import annotations
@@ -17,7 +19,7 @@ from __future__ import annotations
 import numpy as np
 
 DOT, DISTMULT, COMPLEX = 0, 1, 2
-SOFTMAX, LOGISTIC = 0, 1
+SOFTMAX, LOGISTIC, SOFTMAX_POS = 0, 1, 2
 
 
 def _halves(x):
@@ -72,6 +74,14 @@ def side_loss(loss, f, S, neg_weight):
         z = ex.sum(axis=1, keepdims=True)
         lse = (m + np.log(z))[:, 0]
         return -f + lse, -np.ones_like(f), ex / z
+    if loss == SOFTMAX_POS:
+        # -f + log(exp f + sum_k exp S_k): the positive competes with its negatives
+        m = np.maximum(S.max(axis=1), f)[:, None]
+        ex = np.exp(S - m)
+        ef = np.exp(f[:, None] - m)
+        z = ex.sum(axis=1, keepdims=True) + ef
+        lse = (m + np.log(z))[:, 0]
+        return -f + lse, -1.0 + (ef / z)[:, 0], ex / z
     # logistic: softplus(-f) + w * sum_k softplus(S_k)
     sp = lambda x: np.logaddexp(0.0, x)
     sig = lambda x: 0.5 * (1.0 + np.tanh(0.5 * x))

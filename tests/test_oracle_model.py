@@ -101,6 +101,30 @@ def test_logistic_closed_forms():
     assert abs(l[0] - (np.log(2) + np.log(2))) < 1e-14
 
 
+def test_softmax_with_positive_closed_forms_and_library_cross_entropy():
+    # one negative scoring exactly like the positive: two equal logits
+    l, a, W = model.side_loss(model.SOFTMAX_POS, np.array([0.3]), np.array([[0.3]]), 1.0)
+    assert abs(l[0] - np.log(2.0)) < 1e-15 and abs(a[0] + 0.5) < 1e-15 and abs(W[0, 0] - 0.5) < 1e-15
+    # a hopeless negative: loss -> 0, nothing to learn
+    l, a, W = model.side_loss(model.SOFTMAX_POS, np.array([50.0]), np.array([[-50.0]]), 1.0)
+    assert l[0] < 1e-40 + np.exp(-100.0) * 1.01 and abs(a[0]) < 1e-40 and W[0, 0] < 1e-40
+    # torch's cross entropy over the logits [f, S_1..S_N] with class 0 as the target
+    rng = np.random.default_rng(3)
+    f, S = rng.standard_normal(5) * 3, rng.standard_normal((5, 9)) * 3
+    l, a, W = model.side_loss(model.SOFTMAX_POS, f, S, 1.0)
+    logits = torch.tensor(np.concatenate([f[:, None], S], 1), requires_grad=True)
+    ce = torch.nn.functional.cross_entropy(logits, torch.zeros(5, dtype=torch.long), reduction="none")
+    np.testing.assert_allclose(l, ce.detach().numpy(), rtol=1e-13)
+    ce.sum().backward()
+    np.testing.assert_allclose(a, logits.grad[:, 0].numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(W, logits.grad[:, 1:].numpy(), rtol=1e-12, atol=1e-15)
+    # overflow-free for large scores of either sign
+    l, a, W = model.side_loss(model.SOFTMAX_POS, f + 900.0, S + 900.0, 1.0)
+    np.testing.assert_allclose(l, ce.detach().numpy(), rtol=1e-10)
+    # the coefficients of a row sum to zero: a + sum_k W_k = 0
+    np.testing.assert_allclose(a + W.sum(1), 0.0, atol=1e-15)
+
+
 # ---------------------------------------------------------------- gradients
 
 def _tiny(score, loss, corrupt, i, j, seed=0, degree_negs=0):
@@ -123,7 +147,7 @@ def _loss_only(cfg, node, rel, edges, i, j):
 
 
 @pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
-@pytest.mark.parametrize("loss", [model.SOFTMAX, model.LOGISTIC])
+@pytest.mark.parametrize("loss", [model.SOFTMAX, model.LOGISTIC, model.SOFTMAX_POS])
 @pytest.mark.parametrize("corrupt", [0, 1, 2])
 @pytest.mark.parametrize("bucket", [(0, 0), (0, 1), (1, 0)])
 def test_gradients_match_central_finite_differences(score, loss, corrupt, bucket):
