@@ -77,6 +77,7 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
                                f"score={['dot', 'distmult', 'complex'][w.score]}; one step = one epoch, edges in host memory",
                    "update_mode": args.update_mode, "resident_partitions": capacity,
                    "prefetch": not args.no_overlap},
+        "fallback_chunks": L.legend_fallback_chunks_read(ctx),
         "epoch": {"batches": stats["batches"], "swaps": stats["swaps"], "buffer_states": stats["buffer_states"],
                   "bytes_per_swap": stats["bytes_per_swap"], "loss_sum": stats["loss_sum"]},
     }
@@ -310,7 +311,7 @@ def main() -> int:
         "device_ms_per_step": round(dev_ms / K, 4),
         "algorithmic_bytes_per_step": int(alg_bytes), "unique_rows_per_step": round(u_b),
         "hbm_GBs_whole_step": round(alg_bytes / (wall / K) / 1e9, 1), "copy_GBs_measured": round(copy_gbs, 1),
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "kernels": kernels, "fallback_chunks": L.legend_fallback_chunks_read(ctx),
     }
 
     # ---- the oracle, as it stands, on this machine's host cores (a baseline, not the target) ------

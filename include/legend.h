@@ -46,8 +46,10 @@ typedef enum legend_status {
 /* Score functions f(theta_s, theta_r, theta_d) = <theta_s (x) theta_r, theta_d>
  * (Sec. 2.1, Sec. 6).  ComplEx rows hold [real half | imaginary half]. */
 enum { LEGEND_SCORE_DOT = 0, LEGEND_SCORE_DISTMULT = 1, LEGEND_SCORE_COMPLEX = 2 };
-/* Eq. 1 as printed (log-sum-exp over the sampled negatives only) or logistic. */
-enum { LEGEND_LOSS_SOFTMAX = 0, LEGEND_LOSS_LOGISTIC = 1 };
+/* Eq. 1 as printed (log-sum-exp over the sampled negatives only), logistic, or
+ * the variant of Eq. 1 whose log-sum-exp also holds the positive score (sampled
+ * cross-entropy: -f + log(exp f + sum_k exp S_k)). */
+enum { LEGEND_LOSS_SOFTMAX = 0, LEGEND_LOSS_LOGISTIC = 1, LEGEND_LOSS_SOFTMAX_POS = 2 };
 /* Which endpoint of a positive edge is replaced by sampled nodes. */
 enum { LEGEND_CORRUPT_DST = 0, LEGEND_CORRUPT_SRC = 1, LEGEND_CORRUPT_BOTH = 2 };
 /* Embedding update (Sec. 2.1 stage 6): gradient rows of one table row are summed
@@ -278,6 +280,11 @@ typedef struct legend_batch_shape {
 int legend_batch_shape_of(legend_ctx* ctx, legend_batch_shape* out);
 /* Unique rows updated by the batches since the last call (sum), then cleared. */
 int legend_unique_rows_read(legend_ctx* ctx, int64_t* unique_rows, int64_t* batches);
+
+/* Chunk workgroups that the single-sweep batch kernel handed over to the two-sweep
+ * kernel (scores too far above the softmax reference) since the last call, then
+ * cleared.  A tuning aid: 0 in ordinary training. */
+int legend_fallback_chunks_read(legend_ctx* ctx, int64_t* chunks);
 
 /* Message of the last error on this thread ("" if none). */
 const char* legend_last_error(void);

@@ -20,7 +20,7 @@ LEGEND_OK = 0
 LEGEND_E_INVAL, LEGEND_E_NOMEM, LEGEND_E_NOT_RESIDENT = -1, -2, -3
 LEGEND_E_RANGE, LEGEND_E_HIP, LEGEND_E_STATE = -4, -5, -6
 SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX = 0, 1, 2
-LOSS_SOFTMAX, LOSS_LOGISTIC = 0, 1
+LOSS_SOFTMAX, LOSS_LOGISTIC, LOSS_SOFTMAX_POS = 0, 1, 2
 CORRUPT_DST, CORRUPT_SRC, CORRUPT_BOTH = 0, 1, 2
 UPDATE_DETERMINISTIC, UPDATE_ATOMIC = 0, 1
 MEM_HOST, MEM_DEVICE = 0, 1
@@ -30,7 +30,8 @@ EXPORTS = [
     "legend_init_partitions", "legend_destroy", "legend_swap_partition", "legend_partition_slot",
     "legend_train_bucket", "legend_train_bucket_range", "legend_train_epoch", "legend_score_edges", "legend_read_embeddings", "legend_debug_batch_indices",
     "legend_plan_order", "legend_sync", "legend_profile_enable", "legend_profile_read",
-    "legend_profile_name", "legend_batch_shape_of", "legend_unique_rows_read", "legend_last_error",
+    "legend_profile_name", "legend_batch_shape_of", "legend_unique_rows_read", "legend_fallback_chunks_read",
+    "legend_last_error",
 ]
 
 
@@ -96,6 +97,7 @@ def _load() -> C.CDLL:
     lib.legend_profile_name.restype = C.c_char_p
     lib.legend_batch_shape_of.argtypes = [vp, C.POINTER(legend_batch_shape)]
     lib.legend_unique_rows_read.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
+    lib.legend_fallback_chunks_read.argtypes = [vp, C.POINTER(i64)]
     lib.legend_last_error.restype = C.c_char_p
     for name in EXPORTS:
         if name not in ("legend_profile_name", "legend_last_error"):
@@ -301,6 +303,12 @@ def legend_batch_shape_of(ctx):
     _check(_lib.legend_batch_shape_of(ctx, C.byref(s)))
     return dict(occurrences=s.occurrences, neg_rows=s.neg_rows, workspace_bytes=s.workspace_bytes,
                 key_bits=s.key_bits, row_tiles=s.row_tiles)
+
+
+def legend_fallback_chunks_read(ctx) -> int:
+    n = C.c_int64(0)
+    _check(_lib.legend_fallback_chunks_read(ctx, C.byref(n)))
+    return int(n.value)
 
 
 def legend_unique_rows_read(ctx):

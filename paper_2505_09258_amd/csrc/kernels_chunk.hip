@@ -310,7 +310,15 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             sum += wave_shfl_xor(sum, 2);
             const float mx = lse_s[srow];
             __syncthreads();                  // every thread has read the row maxima
-            if (sq == 0) lse_s[srow] = mx + logf(sum);
+            if (sq == 0) {
+                float lse = mx + logf(sum);
+                if (bp.softmax_with_pos) {    // the positive score joins the log-sum-exp
+                    const float f = pos_s[srow];
+                    const float hi = fmaxf(lse, f), lo = fminf(lse, f);
+                    lse = hi + log1pf(expf(lo - hi));
+                }
+                lse_s[srow] = lse;
+            }
         }
         __syncthreads();
     }
@@ -487,7 +495,10 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
         if (prow < nrows) {
             const float f = pos_s[prow];
             float a;
-            if (LOSS == LEGEND_LOSS_SOFTMAX) { a = -1.f; row_loss = lse_s[prow] - f; }
+            if (LOSS == LEGEND_LOSS_SOFTMAX) {
+                row_loss = lse_s[prow] - f;
+                a = bp.softmax_with_pos ? expf(-row_loss) - 1.f : -1.f;
+            }
             else { a = -sigmoidf(-f); row_loss = softplusf(-f); }
             const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;
             const float* y = Ey + (int64_t)eb[prow * 3 + ycol] * d;

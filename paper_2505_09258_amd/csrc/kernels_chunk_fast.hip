@@ -145,7 +145,8 @@ struct RowItem {
 template <int SCORE, int D>
 __global__ void __launch_bounds__(kFThreads, 1)
 k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float* __restrict__ grad,
-             double* __restrict__ loss_partial, uint32_t* __restrict__ redo, float limit) {
+             double* __restrict__ loss_partial, uint32_t* __restrict__ redo, unsigned long long* __restrict__ redo_total,
+             float limit) {
     using Sh = FastShape<D>;
     using Item = RowItem<SCORE, D>;
     constexpr int QS = Sh::QS, KG = Sh::KG, KT = Sh::KT, NJ = Sh::NJ, STEPS = Sh::STEPS;
@@ -470,16 +471,27 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 #pragma unroll
         for (int ww = 0; ww < kFWaves; ++ww) sum += Lw[ww * kFRow + tid];
         const bool live = tid < nrows;
-        // a row sum that is tiny or not finite means the reference was a poor one for this row
+        float pos_term = 0.f;
+        if (bp.softmax_with_pos && live) {    // Eq. 1 variant: the positive score is one more term of the sum
+            const float dpos = f_s[tid] - ref_s[tid];
+            if (dpos > limit) flag_s[8] = 1u;
+            pos_term = expf(fminf(dpos, 80.f));
+            sum += pos_term;
+        }
+        // the reference is one of the row's scores, so the sum is at least 1 unless a score is not finite
         if (live && !(sum > 1e-30f && sum < 1e30f)) flag_s[8] = 1u;
         scale_s[tid] = live ? 1.f / sum : 0.f;
         logl_s[tid] = live ? logf(sum) : 0.f;
+        mx_s[tid] = live ? pos_term / sum - 1.f : 0.f;      // dL/df (the maxima kept here are no longer needed)
     }
     __syncthreads();
     bool bad = flag_s[8] != 0u;
 #pragma unroll
     for (int ww = 0; ww < kFWaves; ++ww) bad |= flag_s[ww] != 0u;
-    if (tid == 0) redo[blockIdx.x] = bad ? 1u : 0u;
+    if (tid == 0) {
+        redo[blockIdx.x] = bad ? 1u : 0u;
+        if (bad) atomicAdd(redo_total, 1ull);
+    }
     if (bad) return;                          // uniform: nothing has been written yet
 
     // ---- (Q / l)^T into LDS: QT[k][e] -----------------------------------------------------------
@@ -583,7 +595,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             if (it_row[s] < nrows) {
                 const int row = it_row[s];
                 const float sc = scale_s[row];
-                const float a = -1.f;                     // dL/df of Eq. 1
+                const float a = mx_s[row];                // dL/df: -1 for Eq. 1 as printed
                 float q[4], g0[4], g1[4], gv[4], gy4[4], gx4[4], gr4[4];
                 Item::compose(side, x[s], r[s], q);
                 Item::load(Ns + row * QS, it_c[s], g0);
@@ -630,7 +642,7 @@ static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const Buck
         configured = true;
     }
     hipLaunchKernelGGL((k_chunk_fast<SC, D>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,
-                       ws.loss_partial, ws.redo, ws.fast_limit);
+                       ws.loss_partial, ws.redo, ws.redo_total, ws.fast_limit);
     return hipGetLastError();
 }
 

@@ -203,6 +203,11 @@ k_chunk_wide(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             // the partial tiles are rewritten only after the next commit's barrier
         }
         lse = m_run + logf(l_run);
+        if (bp.softmax_with_pos) {            // the positive score joins the log-sum-exp
+            const float f = pos_s[prow];
+            const float hi = fmaxf(lse, f), lo = fminf(lse, f);
+            lse = hi + log1pf(expf(lo - hi));
+        }
         if (ppart == 0) lse_s[prow] = lse;
     }
 
@@ -368,7 +373,10 @@ k_chunk_wide(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         if (prow < nrows) {
             const float f = pos_s[prow];
             float a;
-            if (LOSS == LEGEND_LOSS_SOFTMAX) { a = -1.f; row_loss = lse - f; }
+            if (LOSS == LEGEND_LOSS_SOFTMAX) {
+                row_loss = lse - f;
+                a = bp.softmax_with_pos ? expf(-row_loss) - 1.f : -1.f;
+            }
             else { a = -sigmoidf(-f); row_loss = softplusf(-f); }
             const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;
             const float* y = Ey + (int64_t)eb[prow * 3 + ycol] * d;

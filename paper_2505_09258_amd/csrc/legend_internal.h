@@ -54,7 +54,8 @@ struct BucketParams {
     int32_t rows_valid_dst;
     int32_t num_relations;
     int32_t dim;
-    int32_t score, loss;
+    int32_t score, loss;       // loss: LEGEND_LOSS_SOFTMAX or LEGEND_LOSS_LOGISTIC (kernel template parameter)
+    int32_t softmax_with_pos;  // Eq. 1 variant: the positive score is a term of the log-sum-exp
     int32_t same_part;         // i == j
     uint32_t key_base_dst;     // key offset of table slot 1 (0 when same_part)
     uint32_t key_base_rel;     // key offset of the relation table
@@ -80,6 +81,7 @@ struct Workspace {
     float*    grad;           // [n_occ][dim] staged gradient rows
     double*   loss_partial;   // one per chunk workgroup
     uint32_t* redo;           // per chunk workgroup: 1 = the single-sweep kernel left it to the general kernel
+    unsigned long long* redo_total;  // running count of such workgroups
     int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel
     float     fast_limit;     // largest S - f the single-sweep kernel accepts (LEGEND_FAST_CHUNK_LIMIT, default 60)
     double*   loss_sum;       // running bucket loss

@@ -251,7 +251,7 @@ void free_ctx(legend_ctx* c) {
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
                      c->ws.counters, c->ws_odd.neg_ids, c->ws_odd.keys[0], c->ws_odd.keys[1], c->ws_odd.vals[0], c->ws_odd.vals[1],
-                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.loss_sum, c->edges_dev,
+                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
     if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
@@ -344,7 +344,8 @@ int bucket_params(legend_ctx* c, int i, int j, const int32_t* dev_edges, int64_t
     p.num_relations = c->cfg.num_relations;
     p.dim = c->d;
     p.score = c->cfg.score;
-    p.loss = c->cfg.loss;
+    p.loss = c->cfg.loss == LEGEND_LOSS_LOGISTIC ? LEGEND_LOSS_LOGISTIC : LEGEND_LOSS_SOFTMAX;
+    p.softmax_with_pos = c->cfg.loss == LEGEND_LOSS_SOFTMAX_POS ? 1 : 0;
     p.same_part = i == j;
     p.key_base_dst = i == j ? 0u : (uint32_t)c->Rp;
     p.key_base_rel = i == j ? (uint32_t)c->Rp : (uint32_t)(2 * c->Rp);
@@ -397,7 +398,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "num_nodes, dim, num_partitions must be positive and num_partitions <= num_nodes");
     if (!dim_supported(cfg->dim))
         return fail(LEGEND_E_INVAL, "dim %d is not supported (1..128, or a multiple of 4 up to %d)", cfg->dim, max_dim_supported());
-    if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 1 || cfg->corrupt < 0 || cfg->corrupt > 2)
+    if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 2 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
     if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)
         return fail(LEGEND_E_INVAL, "unknown update_mode %d", cfg->update_mode);
@@ -543,6 +544,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     INIT_RC(dev_alloc(c, &w.grad, (size_t)occ * c->d));
     INIT_RC(dev_alloc(c, &w.loss_partial, (size_t)nwg));
     INIT_RC(dev_alloc(c, &w.redo, (size_t)nwg));
+    INIT_RC(dev_alloc(c, &w.redo_total, 1));
+    INIT_TRY(hipMemset(w.redo_total, 0, sizeof(unsigned long long)));
     {
         const char* e = std::getenv("LEGEND_NO_FAST_CHUNK");
         w.no_fast_path = (e && e[0] == '1') ? 1 : 0;
@@ -1021,6 +1024,18 @@ int legend_unique_rows_read(legend_ctx* c, int64_t* unique_rows, int64_t* batche
     *unique_rows = (int64_t)u;
     *batches = c->batches_done;
     c->batches_done = 0;
+    return LEGEND_OK;
+}
+
+int legend_fallback_chunks_read(legend_ctx* c, int64_t* chunks) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (!chunks) return fail(LEGEND_E_INVAL, "NULL output");
+    unsigned long long u = 0;
+    HIP_TRY(c, hipMemcpyAsync(&u, c->ws.redo_total, sizeof u, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemsetAsync(c->ws.redo_total, 0, sizeof u, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    *chunks = (int64_t)u;
     return LEGEND_OK;
 }
 

@@ -10,7 +10,7 @@ from tests.parity_util import EMB_RTOL, STATE_RTOL, OracleRun, check_scores, com
 pytestmark = pytest.mark.gpu
 
 DOT, DISTMULT, COMPLEX = 0, 1, 2
-SOFTMAX, LOGISTIC = 0, 1
+SOFTMAX, LOGISTIC, SOFTMAX_POS = 0, 1, 2
 DST, SRC, BOTH = 0, 1, 2
 
 
@@ -37,6 +37,10 @@ CASES = [
     _case("dot_d512_logistic", DOT, LOGISTIC, SRC, 800, 0, 512, 1, 0, 0, 96, 32, 64, 0, 200, 0.1),
     # d = 100 with the largest negative count and full 64-row chunks (single-sweep kernel, all eight steps)
     _case("distmult_d100_n1024", DISTMULT, SOFTMAX, SRC, 8_000, 11, 100, 2, 1, 0, 640, 64, 1_024, 100, 1_500, 0.3),
+    # Eq. 1 with the positive score inside the log-sum-exp, through each of the three chunk kernels
+    _case("complex_d100_softmax_pos", COMPLEX, SOFTMAX_POS, BOTH, 5_000, 9, 100, 2, 0, 1, 600, 50, 200, 40, 1_300, 0.3),
+    _case("dot_d48_softmax_pos", DOT, SOFTMAX_POS, DST, 3_000, 0, 48, 1, 0, 0, 500, 64, 100, 0, 1_100, 0.3),
+    _case("distmult_d256_softmax_pos", DISTMULT, SOFTMAX_POS, SRC, 2_000, 5, 256, 1, 0, 0, 200, 40, 70, 0, 450, 0.2),
 ]
 
 # One node row in 64 is four times larger than the rest, so that some chunks hold a score far
@@ -145,6 +149,17 @@ def test_single_sweep_kernel_hands_out_of_range_chunks_to_the_general_kernel(mon
         flagged.append(margin > limit)
     assert 0 < sum(flagged) < len(flagged), flagged
     monkeypatch.setenv("LEGEND_FAST_CHUNK_LIMIT", str(limit))
+    # the library's own count of handed-over chunks equals the prediction for the first batch
+    L, ctx = _gpu_ctx(c, node, rel)
+    try:
+        for p in sorted({c["i"], c["j"]}):
+            L.legend_swap_partition(ctx, -1, p)
+        assert L.legend_fallback_chunks_read(ctx) == 0
+        L.legend_train_bucket_range(ctx, c["i"], c["j"], edges, epoch=1, batch_begin=0, batch_end=1)
+        assert L.legend_fallback_chunks_read(ctx) == sum(flagged)
+        assert L.legend_fallback_chunks_read(ctx) == 0
+    finally:
+        L.legend_destroy(ctx)
     _check_every_batch(c)
 
 

@@ -27,7 +27,7 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX = 0, 1, 2
-LOSS_SOFTMAX, LOSS_LOGISTIC = 0, 1
+LOSS_SOFTMAX, LOSS_LOGISTIC, LOSS_SOFTMAX_POS = 0, 1, 2
 CORRUPT_DST, CORRUPT_SRC, CORRUPT_BOTH = 0, 1, 2
 
 
