@@ -4,13 +4,14 @@
 // the softmax numerators are taken against a reference m_e fixed after the first tile of
 // negatives, the row maximum over that tile (the tiles interleave the chunk's negatives, so the
 // first one is an even sample of them):
-//     P_en = exp(S_en - m_e),   l_e = sum_n P_en,   W_en = P_en / l_e,   loss_e = m_e + log l_e - f_e,
+//     P_en = c exp(S_en - m_e),   l_e = sum_n P_en,   W_en = P_en / l_e,   loss_e = m_e + log(l_e / c) - f_e,
+// (c = 2^-58 makes room for scores above m_e),
 // so one sweep over the negatives yields the unnormalised G_Q = sum_n P_en theta_n, and the P
 // blocks (64 x N values, the paper's "Intermediate Result 3") stay in the register file of the
 // workgroup: eight waves, 128 registers per lane each, one workgroup per compute unit.  After
-// the sweep the rows of Q are scaled by 1 / l_e and G_neg = P^T (Q / l) is formed straight from
-// the stored blocks.  If some S_en - m_e exceeds a limit (60 unless overridden; exp stays far
-// from overflow) or a row sum is not finite, the workgroup writes nothing and flags itself; the
+// the sweep the stored numerators are scaled by 1 / l_e and G_neg = W^T Q is formed straight from
+// the stored blocks.  If some S_en exceeds the first tile's row maximum by more than a limit
+// (110 unless overridden; the numerators stay far from overflow) or a row sum is not finite, the workgroup writes nothing and flags itself; the
 // general two-sweep kernel then redoes it.
 //
 // Work split (16x16x4 fp32 MFMA; g = lane / 16, l15 = lane % 16).  The eight waves form two
@@ -27,7 +28,7 @@
 //   while the other keeps the matrix pipe busy;
 //   afterwards, per tile and with no workgroup barrier:
 //     G_neg     contracts its stored P (as the A operand of P^T: lane = negative, k = row)
-//               with (Q / l)^T read from LDS over all 64 rows, stages its 16 gradient rows in
+//               with Q^T read from LDS over all 64 rows, stages its 16 gradient rows in
 //               its own LDS area and writes them out as whole rows of 16-byte pieces.
 #include <type_traits>
 
@@ -58,6 +59,23 @@ constexpr int kFTile = 64;               // negatives per tile of a wave group: 
 constexpr int kFWS = kFTile + 4;         // row stride of a W tile
 constexpr int kFQT = kFRow + 4;          // row stride of the transposed, scaled Q
 constexpr int kFMaxSteps = 8;            // tiles per wave group: 1024 negatives in all
+// The numerators are kept as exp(S - m) * 2^-58, m the row maximum of the first tile: scores up
+// to `limit` (110) above m still give numerators far from overflow, and what lies more than
+// about 47 below m would have a weight under 1e-20 anyway.  The factor is applied inside the
+// exponential (below), not by moving m: S - m must keep its full precision.
+constexpr float kFLiftLn = 58.f * 0.693147180559945309f;
+
+// exp(x) * 2^-58 for x <= 110 without overflow: 2^(h/2) is scaled by 2^-29 and squared.
+__device__ inline float fast_exp_lifted(float x) {
+    const float L2E_HI = 1.44269502162933349609375f;
+    const float L2E_LO = 1.925963033500011e-8f;
+    const float hi = x * L2E_HI;
+    float lo = fmaf(x, L2E_HI, -hi);
+    lo = fmaf(x, L2E_LO, lo);
+    const float r = __builtin_amdgcn_exp2f(0.5f * hi) * 1.862645149230957e-9f;     // 2^-29
+    const float r2 = r * r;
+    return fmaf(r2, lo * 0.6931471805599453f, r2);
+}
 
 template <int D>
 struct FastShape {
@@ -155,7 +173,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     extern __shared__ __align__(16) float smem[];
     float* Qs = smem;
     float* Ns = Qs + Sh::q_floats;
-    float* Ws = Ns + Sh::n_floats;              // sweep: W[2][64][68]; before: partial f; afterwards: row sums, then (Q/l)^T [112][68]
+    float* Ws = Ns + Sh::n_floats;              // sweep: W[2][64][68]; before: partial f; afterwards: row sums, then Q^T [112][68]
     float* ref_s = Ws + Sh::w_floats;           // [64] softmax reference: row maximum over the first tile
     float* scale_s = ref_s + kFRow;             // [64] 1 / l_e
     float* logl_s = scale_s + kFRow;            // [64] log l_e
@@ -382,7 +400,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             for (int v = 0; v < 4; ++v) {
                 const float diff = acc[r][v] - refv[v];
                 top = fmaxf(top, diff);
-                const float p = fast_exp(diff);
+                const float p = fast_exp_lifted(diff);
                 acc[r][v] = p;
                 Wg[(16 * r + 4 * gq + v) * kFWS + 16 * wl + l15] = p;
             }
@@ -475,11 +493,12 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         if (bp.softmax_with_pos && live) {    // Eq. 1 variant: the positive score is one more term of the sum
             const float dpos = f_s[tid] - ref_s[tid];
             if (dpos > limit) flag_s[8] = 1u;
-            pos_term = expf(fminf(dpos, 80.f));
+            pos_term = fast_exp_lifted(fminf(dpos, 110.f));
             sum += pos_term;
         }
-        // the reference is one of the row's scores, so the sum is at least 1 unless a score is not finite
-        if (live && !(sum > 1e-30f && sum < 1e30f)) flag_s[8] = 1u;
+        // the row maximum of the first tile alone contributes 2^-58, so the sum can only leave
+        // this range if a score is not finite
+        if (live && !(sum > 1e-30f && sum < 1e36f)) flag_s[8] = 1u;
         scale_s[tid] = live ? 1.f / sum : 0.f;
         logl_s[tid] = live ? logf(sum) : 0.f;
         mx_s[tid] = live ? pos_term / sum - 1.f : 0.f;      // dL/df (the maxima kept here are no longer needed)
@@ -494,11 +513,20 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     }
     if (bad) return;                          // uniform: nothing has been written yet
 
-    // ---- (Q / l)^T into LDS: QT[k][e] -----------------------------------------------------------
+    // ---- Q^T into LDS: QT[k][e]; the stored numerators become the softmax weights W = P / l ------
     float* QT = Ws;
     for (int idx = tid; idx < 16 * NJ * kFRow; idx += kFThreads) {
         const int e = idx & (kFRow - 1), k = idx >> 6;
-        QT[k * kFQT + e] = k < d ? Qs[e * QS + k] * scale_s[e] : 0.f;
+        QT[k * kFQT + e] = k < d ? Qs[e * QS + k] : 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float4 sc4 = lds4(scale_s + 16 * r + 4 * gq);
+        const f32x4 sc = f32x4{sc4.x, sc4.y, sc4.z, sc4.w};
+        static_for<0, kFMaxSteps>([&](auto U) {
+            constexpr int u = decltype(U)::value;
+            if (tile_of(u) < ntiles) P[u][r] *= sc;
+        });
     }
     __syncthreads();
 
@@ -612,7 +640,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 if (SCORE != LEGEND_SCORE_DOT) Item::store(grad + (side_base + 2 * (int64_t)g.P + e) * d, it_c[s], gr4);
             }
         }
-        if (tid < kFRow) rowloss_s[tid] = tid < nrows ? (ref_s[tid] - f_s[tid]) + logl_s[tid] : 0.f;   // lse - f
+        if (tid < kFRow) rowloss_s[tid] = tid < nrows ? (ref_s[tid] - f_s[tid]) + (logl_s[tid] + kFLiftLn) : 0.f;   // lse - f
     }
     __syncthreads();
     if (tid == 0) {

@@ -83,7 +83,7 @@ struct Workspace {
     uint32_t* redo;           // per chunk workgroup: 1 = the single-sweep kernel left it to the general kernel
     unsigned long long* redo_total;  // running count of such workgroups
     int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel
-    float     fast_limit;     // largest S - f the single-sweep kernel accepts (LEGEND_FAST_CHUNK_LIMIT, default 60)
+    float     fast_limit;     // largest S - f the single-sweep kernel accepts (LEGEND_FAST_CHUNK_LIMIT, default 110): largest score above the reference row maximum
     double*   loss_sum;       // running bucket loss
     int64_t   cap_occ;
     int64_t   cap_wg;
