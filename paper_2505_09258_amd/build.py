@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblegend_hip.so")
 
-SOURCES = ["runtime.hip", "kernels_prepare.hip", "kernels_sort.hip", "kernels_chunk.hip", "kernels_chunk_wide.hip", "kernels_chunk_fast.hip",
+SOURCES = ["runtime.hip", "kernels_prepare.hip", "kernels_sort.hip", "kernels_chunk.hip", "kernels_chunk_gemm.hip", "kernels_chunk_fast.hip",
            "kernels_update.hip", "order_plan.cpp"]
 
 HIP_FLAGS = [

@@ -14,7 +14,7 @@ constexpr int kChunkThreads = 256;
 constexpr int kIdsLds = 1024;   // negative ids of a chunk kept in LDS (more than that: read from global)
 constexpr int kNarrowMaxDim = 128;
 constexpr int kWideMaxDim = 512;
-constexpr int kWideRowTile = 32;
+constexpr int kWideRowTile = 112;  // rows of positives per tile for dim > 128 (seven 16-row MFMA blocks)
 
 // LDS row stride of the Q and negative tiles: dim rounded up to 8, plus 4.  It is a multiple
 // of 4 (rows stay 16-byte aligned for 128-bit LDS accesses) and 4 mod 8 (32 rows read at the
@@ -54,6 +54,6 @@ __device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const f
 
 bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp);
 hipError_t launch_chunks_fast(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
-hipError_t launch_chunks_wide(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 
 }  // namespace legend

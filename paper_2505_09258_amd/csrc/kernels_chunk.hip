@@ -606,7 +606,7 @@ hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams&
     if (bp.dim <= 32) return launch_chunks_nb<1, 0>(st, g, bp, ws, only_if);
     if (bp.dim <= 64) return launch_chunks_nb<2, 0>(st, g, bp, ws, only_if);
     if (bp.dim <= 128) return launch_chunks_nb<4, 0>(st, g, bp, ws, only_if);
-    return launch_chunks_wide(st, g, bp, ws);
+    return launch_chunks_gemm(st, g, bp, ws);
 }
 
 // Sum of the per-workgroup losses in a fixed order, added to the running bucket loss.

@@ -1,0 +1,516 @@
+// Batch computation for wide embeddings (128 < dim <= 512, dim a multiple of 4; paper Sec. 2.1
+// stage 5, Sec. 6) as a short chain of tiled fp32-MFMA contractions.  A (row tile of <= 112
+// positives) x (all N negatives) score block does not fit on chip next to d-wide operand tiles,
+// so the scores go through a device buffer that stays in the L2 / Infinity cache (the paper keeps
+// its "Intermediate Result 3" in global memory for the same reason):
+//   k_gemm_compose   Q = theta_s (x) theta_r (or conj(theta_r) (x) theta_d), positive scores f
+//   k_gemm_scores    S = Q Neg^T, 112 x 64 tiles, the dimension streamed in slices of 80 columns
+//   k_gemm_rowstats  per row: log-sum-exp (maximum, then sum of exponentials), loss term, dL/df
+//   k_gemm_gq        G_Q = W Neg with W = dL/dS rebuilt from S on the way into LDS
+//   k_gemm_gneg      G_neg = W^T Q, written to the gradient rows of the negatives
+//   k_gemm_chain     chain rule: gradient rows of theta_s, theta_r, theta_d of the positives
+// All contractions use 16x16x4 MFMA with the contraction index in groups of 16 (lane group g
+// supplies k = 16G + 4g + s to four consecutive MFMAs), so a k-contiguous operand is one 128-bit
+// LDS read per four MFMAs; operands whose contraction index is the slow one are read 32 bits at
+// a time.
+#include "chunk_common.h"
+
+namespace legend {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline f32x4 mfma16g(float a, float b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+constexpr int kGRows = 112;              // rows of a tile of positives: seven 16-row blocks
+constexpr int kGRowBlocks = kGRows / 16;
+constexpr int kGNeg = 64;                // negatives per tile
+constexpr int kGSlice = 80;              // columns of the dimension per slice: five 16-column blocks
+constexpr int kGSS = kGSlice + 4;        // LDS row stride of a slice
+constexpr int kGWS = kGNeg + 4;          // LDS row stride of a W tile
+
+static_assert(kGRows == kWideRowTile, "tile geometry");
+
+struct TileCoord {
+    int si, side, c, t_row, nrows;
+    int64_t e0;          // first edge of the tile inside the batch
+    int64_t wgrow;       // (si * nchunks + c) * T + t_row
+};
+
+__device__ inline TileCoord tile_coord(const BatchGeom& g, int64_t wgrow) {
+    TileCoord tc;
+    tc.wgrow = wgrow;
+    int64_t q = wgrow;
+    tc.t_row = (int)(q % g.T);  q /= g.T;
+    tc.c = (int)(q % g.nchunks);
+    tc.si = (int)(q / g.nchunks);
+    tc.side = g.side_id[tc.si];
+    const int chunk_rows = min(g.C, g.P - tc.c * g.C);
+    const int row0 = tc.t_row * g.rows_tile;
+    tc.nrows = max(0, min(g.rows_tile, chunk_rows - row0));
+    tc.e0 = (int64_t)tc.c * g.C + row0;
+    return tc;
+}
+
+// ---- Q and positive scores --------------------------------------------------------------------
+// one workgroup of 128 threads per (side, edge)
+template <int SCORE>
+__global__ void __launch_bounds__(128)
+k_gemm_compose(BatchGeom g, BucketParams bp, float* __restrict__ Q, float* __restrict__ fpos) {
+    const int64_t idx = blockIdx.x;
+    const int si = (int)(idx / g.P);
+    const int64_t e = idx % g.P;
+    const int side = g.side_id[si];
+    const int d = bp.dim;
+    const int32_t* eb = bp.edges + (bp.batch_lo + e) * 3;
+    const float* x = (side == 0 ? bp.E_src : bp.E_dst) + (int64_t)eb[side == 0 ? 0 : 2] * d;
+    const float* y = (side == 0 ? bp.E_dst : bp.E_src) + (int64_t)eb[side == 0 ? 2 : 0] * d;
+    const float* r = SCORE == LEGEND_SCORE_DOT ? x : bp.E_rel + (int64_t)eb[1] * d;
+    float* q = Q + idx * d;
+    float partial = 0.f;
+    if (SCORE == LEGEND_SCORE_COMPLEX) {
+        const int h = d >> 1;
+        for (int k = threadIdx.x; k < h; k += 128) {
+            const float xr = x[k], xi = x[k + h], rr = r[k], ri = r[k + h];
+            float qr, qi;
+            if (side == 0) { qr = xr * rr - xi * ri; qi = xr * ri + xi * rr; }
+            else           { qr = rr * xr + ri * xi; qi = rr * xi - ri * xr; }
+            q[k] = qr;
+            q[k + h] = qi;
+            partial += qr * y[k] + qi * y[k + h];
+        }
+    } else {
+        for (int k = threadIdx.x; k < d; k += 128) {
+            const float v = SCORE == LEGEND_SCORE_DOT ? x[k] : x[k] * r[k];
+            q[k] = v;
+            partial += v * y[k];
+        }
+    }
+    __shared__ float red[128];
+    red[threadIdx.x] = partial;
+    __syncthreads();
+    for (int off = 64; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) fpos[idx] = red[0];
+}
+
+// ---- S = Q Neg^T ---------------------------------------------------------------------------------
+// grid: (negative tiles, row tiles).  Four waves; wave w owns negatives 16w..16w+15 of the tile
+// and all row blocks.  S is stored as [row tile][row][Npad].
+__global__ void __launch_bounds__(256, 2)
+k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ Q,
+              float* __restrict__ S, int Npad) {
+    __shared__ __align__(16) float Qs[kGRows * kGSS];
+    __shared__ __align__(16) float Ns[kGNeg * kGSS];
+    __shared__ int32_t ids_s[kGNeg];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
+    const TileCoord tc = tile_coord(g, blockIdx.y);
+    const int n0 = blockIdx.x * kGNeg;
+    const int N = g.N, d = bp.dim;
+    const float* En = tc.side == 0 ? bp.E_dst : bp.E_src;
+    const float* Qrows = Q + ((int64_t)tc.si * g.P + tc.e0) * d;
+    const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
+    if (tid < kGNeg) ids_s[tid] = my_negs[min(n0 + tid, N - 1)];
+    __syncthreads();
+
+    f32x4 acc[kGRowBlocks];
+#pragma unroll
+    for (int r = 0; r < kGRowBlocks; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int rblocks = (tc.nrows + 15) >> 4;
+    constexpr int V4 = kGSlice / 4;
+    for (int c0 = 0; c0 < d; c0 += kGSlice) {
+        // slice of Q and of the negatives into LDS, zero beyond the rows / negatives / columns that exist
+        for (int idx = tid; idx < kGRows * V4; idx += 256) {
+            const int row = idx / V4, c4 = idx - row * V4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < tc.nrows && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(Qrows + (int64_t)row * d + c0 + 4 * c4);
+            *reinterpret_cast<float4*>(Qs + row * kGSS + 4 * c4) = v;
+        }
+        for (int idx = tid; idx < kGNeg * V4; idx += 256) {
+            const int row = idx / V4, c4 = idx - row * V4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n0 + row < N && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(En + (int64_t)ids_s[row] * d + c0 + 4 * c4);
+            *reinterpret_cast<float4*>(Ns + row * kGSS + 4 * c4) = v;
+        }
+        __syncthreads();
+        const int groups = min(kGSlice, d - c0 + 15) >> 4;
+        const float* nb = Ns + (16 * w + l15) * kGSS + 4 * gq;
+        const float* qa = Qs + l15 * kGSS + 4 * gq;
+        for (int G = 0; G < groups; ++G) {
+            const float4 b = lds4(nb + 16 * G);
+#pragma unroll
+            for (int r = 0; r < kGRowBlocks; ++r) {
+                if (r < rblocks) {
+                    const float4 a = lds4(qa + 16 * r * kGSS + 16 * G);
+                    acc[r] = mfma16g(a.x, b.x, acc[r]);
+                    acc[r] = mfma16g(a.y, b.y, acc[r]);
+                    acc[r] = mfma16g(a.z, b.z, acc[r]);
+                    acc[r] = mfma16g(a.w, b.w, acc[r]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const int n = n0 + 16 * w + l15;
+    float* Srow = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
+    if (n < N) {
+#pragma unroll
+        for (int r = 0; r < kGRowBlocks; ++r) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * r + 4 * gq + v;
+                if (row < tc.nrows) Srow[(int64_t)row * Npad + n] = acc[r][v];
+            }
+        }
+    }
+}
+
+// ---- row statistics ---------------------------------------------------------------------------
+// One workgroup per row tile, one wave per row at a time; a row of scores is read twice (maximum,
+// then sum) from the cache-resident score buffer.  Softmax: rowm = the row's log-sum-exp, the
+// weights are W = exp(S - rowm); logistic: W = w sigmoid(S).  rowa = dL/df, loss_partial[tile] =
+// sum over the tile's rows.
+template <int LOSS>
+__global__ void __launch_bounds__(256)
+k_gemm_rowstats(BatchGeom g, BucketParams bp, const float* __restrict__ S, const float* __restrict__ fpos, int Npad,
+                float* __restrict__ rowm, float* __restrict__ rowa, double* __restrict__ loss_partial) {
+    __shared__ double wave_loss[4];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const TileCoord tc = tile_coord(g, blockIdx.x);
+    const int N = g.N;
+    const float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
+    double loss = 0.0;
+    for (int row = w; row < tc.nrows; row += 4) {
+        const float* s = Stile + (int64_t)row * Npad;
+        const int64_t ridx = (int64_t)tc.si * g.P + tc.e0 + row;
+        const float f = fpos[ridx];
+        if (LOSS == LEGEND_LOSS_SOFTMAX) {
+            float m = -INFINITY;
+            for (int n = lane; n < N; n += kWave) m = fmaxf(m, s[n]);
+            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+            if (bp.softmax_with_pos) m = fmaxf(m, f);
+            float l = 0.f;
+            for (int n = lane; n < N; n += kWave) l += expf(s[n] - m);
+            for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, kWave);
+            float a = -1.f;
+            if (bp.softmax_with_pos) {
+                const float pf = expf(f - m);
+                l += pf;
+                a = pf / l - 1.f;
+            }
+            const float lse = m + logf(l);
+            if (lane == 0) {
+                rowm[ridx] = lse;
+                rowa[ridx] = a;
+            }
+            loss += (double)(lse - f);
+        } else {
+            float t = 0.f;
+            for (int n = lane; n < N; n += kWave) t += softplusf(s[n]);
+            for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
+            if (lane == 0) {
+                rowm[ridx] = 0.f;
+                rowa[ridx] = -sigmoidf(-f);
+            }
+            loss += (double)(softplusf(-f) + bp.neg_weight * t);
+        }
+    }
+    if (lane == 0) wave_loss[w] = loss;
+    __syncthreads();
+    if (tid == 0) loss_partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
+}
+
+// W tile [rows][64 negatives] from the scores: softmax weights or logistic weights; zero outside
+template <int LOSS, int THREADS>
+__device__ inline void load_w_tile(float* Wt, const float* Stile, const float* rowm_tile, int nrows, int n0, int N, int Npad,
+                                   float wneg, int tid) {
+    for (int idx = tid; idx < kGRows * (kGNeg / 4); idx += THREADS) {
+        const int row = idx / (kGNeg / 4), c4 = idx - row * (kGNeg / 4);
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < nrows) {
+            const float4 s = *reinterpret_cast<const float4*>(Stile + (int64_t)row * Npad + n0 + 4 * c4);
+            const int n = n0 + 4 * c4;
+            if (LOSS == LEGEND_LOSS_SOFTMAX) {
+                const float m = rowm_tile[row];
+                if (n + 0 < N) o.x = expf(s.x - m);
+                if (n + 1 < N) o.y = expf(s.y - m);
+                if (n + 2 < N) o.z = expf(s.z - m);
+                if (n + 3 < N) o.w = expf(s.w - m);
+            } else {
+                if (n + 0 < N) o.x = wneg * sigmoidf(s.x);
+                if (n + 1 < N) o.y = wneg * sigmoidf(s.y);
+                if (n + 2 < N) o.z = wneg * sigmoidf(s.z);
+                if (n + 3 < N) o.w = wneg * sigmoidf(s.w);
+            }
+        }
+        *reinterpret_cast<float4*>(Wt + row * kGWS + 4 * c4) = o;
+    }
+}
+
+// ---- G_Q = W Neg ---------------------------------------------------------------------------------
+// grid: (column tiles of 80, row tiles).  Five waves; wave w owns columns 16w..16w+15 of the tile
+// and all row blocks; the negatives are streamed 64 at a time.
+template <int LOSS>
+__global__ void __launch_bounds__(320, 2)
+k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ S,
+          const float* __restrict__ rowm, int Npad, float* __restrict__ GQ) {
+    __shared__ __align__(16) float Wt[kGRows * kGWS];
+    __shared__ __align__(16) float Nt[kGNeg * kGSS];
+    __shared__ int32_t ids_s[kGNeg];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
+    const TileCoord tc = tile_coord(g, blockIdx.y);
+    const int c0 = blockIdx.x * kGSlice;
+    const int N = g.N, d = bp.dim;
+    const float* En = tc.side == 0 ? bp.E_dst : bp.E_src;
+    const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
+    const float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
+    const float* rowm_tile = rowm + (int64_t)tc.si * g.P + tc.e0;
+    const int rblocks = (tc.nrows + 15) >> 4;
+    constexpr int V4 = kGSlice / 4;
+
+    f32x4 acc[kGRowBlocks];
+#pragma unroll
+    for (int r = 0; r < kGRowBlocks; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int n0 = 0; n0 < N; n0 += kGNeg) {
+        if (tid < kGNeg) ids_s[tid] = my_negs[min(n0 + tid, N - 1)];
+        load_w_tile<LOSS, 320>(Wt, Stile, rowm_tile, tc.nrows, n0, N, Npad, bp.neg_weight, tid);
+        __syncthreads();
+        for (int idx = tid; idx < kGNeg * V4; idx += 320) {
+            const int row = idx / V4, c4 = idx - row * V4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n0 + row < N && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(En + (int64_t)ids_s[row] * d + c0 + 4 * c4);
+            *reinterpret_cast<float4*>(Nt + row * kGSS + 4 * c4) = v;
+        }
+        __syncthreads();
+        const int groups = (min(kGNeg, N - n0) + 15) >> 4;
+        const float* wa = Wt + l15 * kGWS + 4 * gq;
+        const float* nb = Nt + (4 * gq) * kGSS + 16 * w + l15;
+        for (int G = 0; G < groups; ++G) {
+            float b[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) b[s] = nb[(16 * G + s) * kGSS];
+#pragma unroll
+            for (int r = 0; r < kGRowBlocks; ++r) {
+                if (r < rblocks) {
+                    const float4 a = lds4(wa + 16 * r * kGWS + 16 * G);
+                    acc[r] = mfma16g(a.x, b[0], acc[r]);
+                    acc[r] = mfma16g(a.y, b[1], acc[r]);
+                    acc[r] = mfma16g(a.z, b[2], acc[r]);
+                    acc[r] = mfma16g(a.w, b[3], acc[r]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+    const int col = c0 + 16 * w + l15;
+    if (col < d) {
+        float* out = GQ + ((int64_t)tc.si * g.P + tc.e0) * d + col;
+#pragma unroll
+        for (int r = 0; r < kGRowBlocks; ++r) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = 16 * r + 4 * gq + v;
+                if (row < tc.nrows) out[(int64_t)row * d] = acc[r][v];
+            }
+        }
+    }
+}
+
+// ---- G_neg = W^T Q -------------------------------------------------------------------------------
+// grid: (column tiles of 80, row tiles).  The Q slice of the column tile stays in LDS; the
+// negatives are walked 64 at a time; wave w owns columns 16w..16w+15 and the four 16-negative
+// blocks of a tile.  Both operands have the contraction index (the row) as the slow one.
+template <int LOSS>
+__global__ void __launch_bounds__(320, 2)
+k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ S,
+            const float* __restrict__ rowm, int Npad, const float* __restrict__ Q, float* __restrict__ grad) {
+    extern __shared__ __align__(16) float gneg_smem[];
+    float* Wt = gneg_smem;                    // [112][68]
+    float* Qs = Wt + kGRows * kGWS;           // [112][84]
+    int32_t* ids_s = reinterpret_cast<int32_t*>(Qs + kGRows * kGSS);     // [64]
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
+    const TileCoord tc = tile_coord(g, blockIdx.y);
+    const int c0 = blockIdx.x * kGSlice;
+    const int N = g.N, d = bp.dim;
+    const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
+    const float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
+    const float* rowm_tile = rowm + (int64_t)tc.si * g.P + tc.e0;
+    const float* Qrows = Q + ((int64_t)tc.si * g.P + tc.e0) * d;
+    const int kgroups = (tc.nrows + 15) >> 4;
+    const bool atomic = bp.atomic_mode != 0;
+    float* Gn = tc.side == 0 ? bp.G_dst : bp.G_src;
+    const int64_t neg_base = (int64_t)tc.si * g.per_side + (int64_t)g.roles * g.P + ((int64_t)tc.c * g.T + tc.t_row) * N;
+    constexpr int V4 = kGSlice / 4;
+
+    for (int idx = tid; idx < kGRows * V4; idx += 320) {
+        const int row = idx / V4, c4 = idx - row * V4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < tc.nrows && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(Qrows + (int64_t)row * d + c0 + 4 * c4);
+        *reinterpret_cast<float4*>(Qs + row * kGSS + 4 * c4) = v;
+    }
+    const int col = c0 + 16 * w + l15;
+    for (int n0 = 0; n0 < N; n0 += kGNeg) {
+        __syncthreads();                      // the previous tile's W has been consumed (and Qs is complete)
+        if (atomic && tid < kGNeg) ids_s[tid] = my_negs[min(n0 + tid, N - 1)];
+        load_w_tile<LOSS, 320>(Wt, Stile, rowm_tile, tc.nrows, n0, N, Npad, bp.neg_weight, tid);
+        __syncthreads();
+        f32x4 acc[4];
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const float* wa = Wt + (4 * gq) * kGWS + l15;
+        const float* qb = Qs + (4 * gq) * kGSS + 16 * w + l15;
+        for (int G = 0; G < kgroups; ++G) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float b = qb[(16 * G + s) * kGSS];
+                const float* arow = wa + (16 * G + s) * kGWS;
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma16g(arow[16 * mb], b, acc[mb]);
+            }
+        }
+        if (col < d) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int k = 16 * mb + 4 * gq + v;
+                    const int n = n0 + k;
+                    if (n < N) {
+                        if (atomic) unsafeAtomicAdd(Gn + (int64_t)ids_s[k] * d + col, acc[mb][v]);
+                        else grad[(neg_base + n) * d + col] = acc[mb][v];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---- chain rule for the positives ---------------------------------------------------------------
+template <int SCORE>
+__global__ void __launch_bounds__(128)
+k_gemm_chain(BatchGeom g, BucketParams bp, const float* __restrict__ Q, const float* __restrict__ GQ,
+             const float* __restrict__ rowa, float* __restrict__ grad) {
+    const int64_t idx = blockIdx.x;
+    const int si = (int)(idx / g.P);
+    const int64_t e = idx % g.P;
+    const int side = g.side_id[si];
+    const int d = bp.dim;
+    const int32_t* eb = bp.edges + (bp.batch_lo + e) * 3;
+    const int xid = eb[side == 0 ? 0 : 2], yid = eb[side == 0 ? 2 : 0], rid = eb[1];
+    const float* x = (side == 0 ? bp.E_src : bp.E_dst) + (int64_t)xid * d;
+    const float* y = (side == 0 ? bp.E_dst : bp.E_src) + (int64_t)yid * d;
+    const float* r = SCORE == LEGEND_SCORE_DOT ? x : bp.E_rel + (int64_t)rid * d;
+    const float* q = Q + idx * d;
+    const float* gqr = GQ + idx * d;
+    const float a = rowa[idx];
+    const bool atomic = bp.atomic_mode != 0;
+    const int64_t side_base = (int64_t)si * g.per_side;
+    float* gx = grad + (side_base + (side == 0 ? 0 : g.P) + e) * d;
+    float* gy = grad + (side_base + (side == 0 ? g.P : 0) + e) * d;
+    float* gr = grad + (side_base + 2 * (int64_t)g.P + e) * d;
+    if (atomic) {
+        gx = (side == 0 ? bp.G_src : bp.G_dst) + (int64_t)xid * d;
+        gy = (side == 0 ? bp.G_dst : bp.G_src) + (int64_t)yid * d;
+        gr = bp.G_rel + (int64_t)rid * d;
+    }
+    auto emit = [&](float* p, float v) {
+        if (atomic) unsafeAtomicAdd(p, v);
+        else *p = v;
+    };
+    if (SCORE == LEGEND_SCORE_COMPLEX) {
+        const int h = d >> 1;
+        for (int k = threadIdx.x; k < h; k += 128) {
+            const float xr = x[k], xi = x[k + h], rr = r[k], ri = r[k + h];
+            const float gre = gqr[k] + a * y[k], gim = gqr[k + h] + a * y[k + h];
+            emit(gy + k, a * q[k]);
+            emit(gy + k + h, a * q[k + h]);
+            if (side == 0) {
+                emit(gx + k, rr * gre + ri * gim);      emit(gx + k + h, rr * gim - ri * gre);
+                emit(gr + k, xr * gre + xi * gim);      emit(gr + k + h, xr * gim - xi * gre);
+            } else {
+                emit(gx + k, rr * gre - ri * gim);      emit(gx + k + h, rr * gim + ri * gre);
+                emit(gr + k, gre * xr + gim * xi);      emit(gr + k + h, gre * xi - gim * xr);
+            }
+        }
+    } else {
+        for (int k = threadIdx.x; k < d; k += 128) {
+            const float gv = gqr[k] + a * y[k];
+            emit(gy + k, a * q[k]);
+            if (SCORE == LEGEND_SCORE_DOT) {
+                emit(gx + k, gv);
+            } else {
+                emit(gx + k, r[k] * gv);
+                emit(gr + k, x[k] * gv);
+            }
+        }
+    }
+}
+
+int64_t gemm_npad(int N) { return ((int64_t)N + kGNeg - 1) / kGNeg * kGNeg; }
+
+hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    if (bp.dim <= kNarrowMaxDim || bp.dim > kWideMaxDim || (bp.dim & 3) || g.rows_tile > kGRows || !ws.gemm_Q)
+        return hipErrorInvalidValue;
+    const int64_t tiles = (int64_t)g.sides * g.nchunks * g.T;
+    const int64_t rows = (int64_t)g.sides * g.P;
+    const int Npad = (int)gemm_npad(g.N);
+    const int ntiles = Npad / kGNeg;
+    const int coltiles = (bp.dim + kGSlice - 1) / kGSlice;
+    const bool softmax = bp.loss == LEGEND_LOSS_SOFTMAX;
+    const size_t gneg_lds = sizeof(float) * (kGRows * kGWS + kGRows * kGSS) + sizeof(int32_t) * kGNeg;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<LEGEND_LOSS_SOFTMAX>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<LEGEND_LOSS_LOGISTIC>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    switch (bp.score) {
+        case LEGEND_SCORE_DOT:
+            hipLaunchKernelGGL(k_gemm_compose<LEGEND_SCORE_DOT>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_f);
+            break;
+        case LEGEND_SCORE_DISTMULT:
+            hipLaunchKernelGGL(k_gemm_compose<LEGEND_SCORE_DISTMULT>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_f);
+            break;
+        default:
+            hipLaunchKernelGGL(k_gemm_compose<LEGEND_SCORE_COMPLEX>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_f);
+            break;
+    }
+    hipLaunchKernelGGL(k_gemm_scores, dim3((unsigned)ntiles, (unsigned)tiles), dim3(256), 0, st, g, bp, ws.neg_ids, ws.gemm_Q,
+                       ws.gemm_S, Npad);
+    if (softmax) {
+        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)tiles), dim3(256), 0, st, g, bp, ws.gemm_S,
+                           ws.gemm_f, Npad, ws.gemm_m, ws.gemm_a, ws.loss_partial);
+        hipLaunchKernelGGL(k_gemm_gq<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), 0, st, g, bp,
+                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_G);
+        hipLaunchKernelGGL(k_gemm_gneg<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), gneg_lds, st, g, bp,
+                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_Q, ws.grad);
+    } else {
+        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(256), 0, st, g, bp, ws.gemm_S,
+                           ws.gemm_f, Npad, ws.gemm_m, ws.gemm_a, ws.loss_partial);
+        hipLaunchKernelGGL(k_gemm_gq<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), 0, st, g, bp,
+                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_G);
+        hipLaunchKernelGGL(k_gemm_gneg<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), gneg_lds, st, g, bp,
+                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_Q, ws.grad);
+    }
+    switch (bp.score) {
+        case LEGEND_SCORE_DOT:
+            hipLaunchKernelGGL(k_gemm_chain<LEGEND_SCORE_DOT>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_G, ws.gemm_a, ws.grad);
+            break;
+        case LEGEND_SCORE_DISTMULT:
+            hipLaunchKernelGGL(k_gemm_chain<LEGEND_SCORE_DISTMULT>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_G, ws.gemm_a, ws.grad);
+            break;
+        default:
+            hipLaunchKernelGGL(k_gemm_chain<LEGEND_SCORE_COMPLEX>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_G, ws.gemm_a, ws.grad);
+            break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace legend

@@ -82,6 +82,13 @@ struct Workspace {
     double*   loss_partial;   // one per chunk workgroup
     uint32_t* redo;           // per chunk workgroup: 1 = the single-sweep kernel left it to the general kernel
     unsigned long long* redo_total;  // running count of such workgroups
+    // dim > 128 only: operands and intermediate results of the chain of contractions
+    float*    gemm_Q;         // [sides][P][dim] composed rows
+    float*    gemm_f;         // [sides][P] positive scores
+    float*    gemm_S;         // [row tiles][rows_tile][N rounded up to 64] negative scores
+    float*    gemm_m;         // [sides][P] row log-sum-exp
+    float*    gemm_a;         // [sides][P] dL/df
+    float*    gemm_G;         // [sides][P][dim] G_Q
     int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel
     float     fast_limit;     // largest S - f the single-sweep kernel accepts (LEGEND_FAST_CHUNK_LIMIT, default 110): largest score above the reference row maximum
     double*   loss_sum;       // running bucket loss
@@ -116,6 +123,7 @@ hipError_t launch_gather_rows(hipStream_t st, const int64_t* ids, int64_t m, flo
 int64_t update_long_rows_capacity(int64_t n_occ);
 int64_t update_long_units_capacity(int64_t n_occ);
 int row_tiles_for(int chunk_size, int dim);          // T
+int64_t gemm_npad(int N);                            // negatives per row of the score buffer (dim > 128)
 int rows_per_tile_for(int chunk_size, int dim);      // ceil(C / T)
 int max_dim_supported();
 bool dim_supported(int dim);
