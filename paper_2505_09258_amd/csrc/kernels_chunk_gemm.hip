@@ -5,8 +5,8 @@
 // its "Intermediate Result 3" in global memory for the same reason):
 //   k_gemm_compose   Q = theta_s (x) theta_r (or conj(theta_r) (x) theta_d), positive scores f
 //   k_gemm_scores    S = Q Neg^T, 112 x 64 tiles, the dimension streamed in slices of 80 columns
-//   k_gemm_rowstats  per row: log-sum-exp (maximum, then sum of exponentials), loss term, dL/df
-//   k_gemm_gq        G_Q = W Neg with W = dL/dS rebuilt from S on the way into LDS
+//   k_gemm_rowstats  per row: log-sum-exp, loss term, dL/df; S is replaced by the weights W = dL/dS
+//   k_gemm_gq        G_Q = W Neg
 //   k_gemm_gneg      G_neg = W^T Q, written to the gradient rows of the negatives
 //   k_gemm_chain     chain rule: gradient rows of theta_s, theta_r, theta_d of the positives
 // All contractions use 16x16x4 MFMA with the contraction index in groups of 16 (lane group g
@@ -97,6 +97,58 @@ k_gemm_compose(BatchGeom g, BucketParams bp, float* __restrict__ Q, float* __res
     if (threadIdx.x == 0) fpos[idx] = red[0];
 }
 
+// A thread's share of a [rows][64] tile of W (from the buffer the row statistics left) and of a
+// [64][80] tile of negatives, fetched into registers one tile ahead of their use.
+template <int THREADS>
+struct WTileRegs {
+    static constexpr int V4 = kGNeg / 4;
+    static constexpr int ITEMS = (kGRows * V4 + THREADS - 1) / THREADS;
+    float4 v[ITEMS];
+    __device__ void fetch(const float* Wtile, int Npad, int nrows, int n0, int tid) {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const int idx = tid + THREADS * k;
+            const int row = idx / V4, c4 = idx - row * V4;
+            v[k] = row < nrows ? *reinterpret_cast<const float4*>(Wtile + (int64_t)row * Npad + n0 + 4 * c4)
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    __device__ void store(float* Wt, int tid) const {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const int idx = tid + THREADS * k;
+            const int row = idx / V4, c4 = idx - row * V4;
+            if (row < kGRows) *reinterpret_cast<float4*>(Wt + row * kGWS + 4 * c4) = v[k];
+        }
+    }
+};
+
+template <int THREADS, int ROWS>
+struct SliceRegs {                            // [ROWS][80 columns] of row-major fp32 rows
+    static constexpr int V4 = kGSlice / 4;
+    static constexpr int ITEMS = (ROWS * V4 + THREADS - 1) / THREADS;
+    float4 v[ITEMS];
+    // row_ptr(row) gives the start of the row or nullptr for a row that does not exist
+    template <class F>
+    __device__ void fetch(F&& row_ptr, int c0, int d, int tid) {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const int idx = tid + THREADS * k;
+            const int row = idx / V4, c4 = idx - row * V4;
+            const float* p = row < ROWS ? row_ptr(row) : nullptr;
+            v[k] = (p && c0 + 4 * c4 < d) ? *reinterpret_cast<const float4*>(p + c0 + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    __device__ void store(float* T, int tid) const {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const int idx = tid + THREADS * k;
+            const int row = idx / V4, c4 = idx - row * V4;
+            if (row < ROWS) *reinterpret_cast<float4*>(T + row * kGSS + 4 * c4) = v[k];
+        }
+    }
+};
+
 // ---- S = Q Neg^T ---------------------------------------------------------------------------------
 // grid: (negative tiles, row tiles).  Four waves; wave w owns negatives 16w..16w+15 of the tile
 // and all row blocks.  S is stored as [row tile][row][Npad].
@@ -120,22 +172,24 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
 #pragma unroll
     for (int r = 0; r < kGRowBlocks; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int rblocks = (tc.nrows + 15) >> 4;
-    constexpr int V4 = kGSlice / 4;
+    const int nrows = tc.nrows;
+    auto q_row = [=](int row) -> const float* { return row < nrows ? Qrows + (int64_t)row * d : nullptr; };
+    const int32_t* ids = ids_s;
+    auto n_row = [=](int row) -> const float* { return n0 + row < N ? En + (int64_t)ids[row] * d : nullptr; };
+    SliceRegs<256, kGRows> qr;
+    SliceRegs<256, kGNeg> nr;
+    qr.fetch(q_row, 0, d, tid);
+    nr.fetch(n_row, 0, d, tid);
     for (int c0 = 0; c0 < d; c0 += kGSlice) {
-        // slice of Q and of the negatives into LDS, zero beyond the rows / negatives / columns that exist
-        for (int idx = tid; idx < kGRows * V4; idx += 256) {
-            const int row = idx / V4, c4 = idx - row * V4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < tc.nrows && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(Qrows + (int64_t)row * d + c0 + 4 * c4);
-            *reinterpret_cast<float4*>(Qs + row * kGSS + 4 * c4) = v;
-        }
-        for (int idx = tid; idx < kGNeg * V4; idx += 256) {
-            const int row = idx / V4, c4 = idx - row * V4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (n0 + row < N && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(En + (int64_t)ids_s[row] * d + c0 + 4 * c4);
-            *reinterpret_cast<float4*>(Ns + row * kGSS + 4 * c4) = v;
-        }
+        // slice of Q and of the negatives into LDS (zero beyond the rows / negatives / columns that
+        // exist), the next slice in flight
+        qr.store(Qs, tid);
+        nr.store(Ns, tid);
         __syncthreads();
+        if (c0 + kGSlice < d) {
+            qr.fetch(q_row, c0 + kGSlice, d, tid);
+            nr.fetch(n_row, c0 + kGSlice, d, tid);
+        }
         const int groups = min(kGSlice, d - c0 + 15) >> 4;
         const float* nb = Ns + (16 * w + l15) * kGSS + 4 * gq;
         const float* qa = Qs + l15 * kGSS + 4 * gq;
@@ -168,23 +222,25 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
     }
 }
 
-// ---- row statistics ---------------------------------------------------------------------------
-// One workgroup per row tile, one wave per row at a time; a row of scores is read twice (maximum,
-// then sum) from the cache-resident score buffer.  Softmax: rowm = the row's log-sum-exp, the
-// weights are W = exp(S - rowm); logistic: W = w sigmoid(S).  rowa = dL/df, loss_partial[tile] =
-// sum over the tile's rows.
+// ---- row statistics and weights ------------------------------------------------------------
+// One workgroup (16 waves) per row tile, one wave per row at a time; a row of scores is read
+// from the cache-resident buffer for the maximum, for the sum, and a third time to be replaced
+// by the weights W = dL/dS: exp(S - lse) for the softmax losses, w sigmoid(S) for the logistic
+// loss, 0 in the padding up to Npad.  rowa = dL/df, loss_partial[tile] = sum over the tile's rows.
+constexpr int kStatThreads = 1024;
 template <int LOSS>
-__global__ void __launch_bounds__(256)
-k_gemm_rowstats(BatchGeom g, BucketParams bp, const float* __restrict__ S, const float* __restrict__ fpos, int Npad,
-                float* __restrict__ rowm, float* __restrict__ rowa, double* __restrict__ loss_partial) {
-    __shared__ double wave_loss[4];
+__global__ void __launch_bounds__(kStatThreads)
+k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float* __restrict__ fpos, int Npad,
+                float* __restrict__ rowa, double* __restrict__ loss_partial) {
+    constexpr int WAVES = kStatThreads / kWave;
+    __shared__ double wave_loss[WAVES];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const TileCoord tc = tile_coord(g, blockIdx.x);
     const int N = g.N;
-    const float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
+    float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
     double loss = 0.0;
-    for (int row = w; row < tc.nrows; row += 4) {
-        const float* s = Stile + (int64_t)row * Npad;
+    for (int row = w; row < tc.nrows; row += WAVES) {
+        float* s = Stile + (int64_t)row * Npad;
         const int64_t ridx = (int64_t)tc.si * g.P + tc.e0 + row;
         const float f = fpos[ridx];
         if (LOSS == LEGEND_LOSS_SOFTMAX) {
@@ -193,7 +249,7 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, const float* __restrict__ S, const
             for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
             if (bp.softmax_with_pos) m = fmaxf(m, f);
             float l = 0.f;
-            for (int n = lane; n < N; n += kWave) l += expf(s[n] - m);
+            for (int n = lane; n < N; n += kWave) l += fast_exp(s[n] - m);
             for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, kWave);
             float a = -1.f;
             if (bp.softmax_with_pos) {
@@ -201,90 +257,64 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, const float* __restrict__ S, const
                 l += pf;
                 a = pf / l - 1.f;
             }
-            const float lse = m + logf(l);
-            if (lane == 0) {
-                rowm[ridx] = lse;
-                rowa[ridx] = a;
-            }
-            loss += (double)(lse - f);
+            const float il = 1.f / l;
+            for (int n = lane; n < Npad; n += kWave) s[n] = n < N ? fast_exp(s[n] - m) * il : 0.f;
+            if (lane == 0) rowa[ridx] = a;
+            loss += (double)(m + logf(l) - f);
         } else {
             float t = 0.f;
             for (int n = lane; n < N; n += kWave) t += softplusf(s[n]);
             for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
-            if (lane == 0) {
-                rowm[ridx] = 0.f;
-                rowa[ridx] = -sigmoidf(-f);
-            }
+            for (int n = lane; n < Npad; n += kWave) s[n] = n < N ? bp.neg_weight * sigmoidf(s[n]) : 0.f;
+            if (lane == 0) rowa[ridx] = -sigmoidf(-f);
             loss += (double)(softplusf(-f) + bp.neg_weight * t);
         }
     }
     if (lane == 0) wave_loss[w] = loss;
     __syncthreads();
-    if (tid == 0) loss_partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
-}
-
-// W tile [rows][64 negatives] from the scores: softmax weights or logistic weights; zero outside
-template <int LOSS, int THREADS>
-__device__ inline void load_w_tile(float* Wt, const float* Stile, const float* rowm_tile, int nrows, int n0, int N, int Npad,
-                                   float wneg, int tid) {
-    for (int idx = tid; idx < kGRows * (kGNeg / 4); idx += THREADS) {
-        const int row = idx / (kGNeg / 4), c4 = idx - row * (kGNeg / 4);
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row < nrows) {
-            const float4 s = *reinterpret_cast<const float4*>(Stile + (int64_t)row * Npad + n0 + 4 * c4);
-            const int n = n0 + 4 * c4;
-            if (LOSS == LEGEND_LOSS_SOFTMAX) {
-                const float m = rowm_tile[row];
-                if (n + 0 < N) o.x = expf(s.x - m);
-                if (n + 1 < N) o.y = expf(s.y - m);
-                if (n + 2 < N) o.z = expf(s.z - m);
-                if (n + 3 < N) o.w = expf(s.w - m);
-            } else {
-                if (n + 0 < N) o.x = wneg * sigmoidf(s.x);
-                if (n + 1 < N) o.y = wneg * sigmoidf(s.y);
-                if (n + 2 < N) o.z = wneg * sigmoidf(s.z);
-                if (n + 3 < N) o.w = wneg * sigmoidf(s.w);
-            }
-        }
-        *reinterpret_cast<float4*>(Wt + row * kGWS + 4 * c4) = o;
+    if (tid == 0) {
+        double t = 0.0;
+        for (int k = 0; k < WAVES; ++k) t += wave_loss[k];
+        loss_partial[blockIdx.x] = t;
     }
 }
 
 // ---- G_Q = W Neg ---------------------------------------------------------------------------------
 // grid: (column tiles of 80, row tiles).  Five waves; wave w owns columns 16w..16w+15 of the tile
-// and all row blocks; the negatives are streamed 64 at a time.
-template <int LOSS>
+// and all row blocks; the negatives are streamed 64 at a time, the next tile in flight.
 __global__ void __launch_bounds__(320, 2)
-k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ S,
-          const float* __restrict__ rowm, int Npad, float* __restrict__ GQ) {
+k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ W, int Npad,
+          float* __restrict__ GQ) {
     __shared__ __align__(16) float Wt[kGRows * kGWS];
     __shared__ __align__(16) float Nt[kGNeg * kGSS];
-    __shared__ int32_t ids_s[kGNeg];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
     const TileCoord tc = tile_coord(g, blockIdx.y);
     const int c0 = blockIdx.x * kGSlice;
     const int N = g.N, d = bp.dim;
     const float* En = tc.side == 0 ? bp.E_dst : bp.E_src;
     const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
-    const float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
-    const float* rowm_tile = rowm + (int64_t)tc.si * g.P + tc.e0;
+    const float* Wtile = W + (int64_t)tc.wgrow * g.rows_tile * Npad;
     const int rblocks = (tc.nrows + 15) >> 4;
-    constexpr int V4 = kGSlice / 4;
+
+    WTileRegs<320> wr;
+    SliceRegs<320, kGNeg> nr;
+    auto neg_row = [&](int n0) {
+        return [=](int row) -> const float* { return n0 + row < N ? En + (int64_t)my_negs[n0 + row] * d : nullptr; };
+    };
+    wr.fetch(Wtile, Npad, tc.nrows, 0, tid);
+    nr.fetch(neg_row(0), c0, d, tid);
 
     f32x4 acc[kGRowBlocks];
 #pragma unroll
     for (int r = 0; r < kGRowBlocks; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int n0 = 0; n0 < N; n0 += kGNeg) {
-        if (tid < kGNeg) ids_s[tid] = my_negs[min(n0 + tid, N - 1)];
-        load_w_tile<LOSS, 320>(Wt, Stile, rowm_tile, tc.nrows, n0, N, Npad, bp.neg_weight, tid);
+        wr.store(Wt, tid);
+        nr.store(Nt, tid);
         __syncthreads();
-        for (int idx = tid; idx < kGNeg * V4; idx += 320) {
-            const int row = idx / V4, c4 = idx - row * V4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (n0 + row < N && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(En + (int64_t)ids_s[row] * d + c0 + 4 * c4);
-            *reinterpret_cast<float4*>(Nt + row * kGSS + 4 * c4) = v;
+        if (n0 + kGNeg < N) {
+            wr.fetch(Wtile, Npad, tc.nrows, n0 + kGNeg, tid);
+            nr.fetch(neg_row(n0 + kGNeg), c0, d, tid);
         }
-        __syncthreads();
         const int groups = (min(kGNeg, N - n0) + 15) >> 4;
         const float* wa = Wt + l15 * kGWS + 4 * gq;
         const float* nb = Nt + (4 * gq) * kGSS + 16 * w + l15;
@@ -323,40 +353,38 @@ k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, con
 // grid: (column tiles of 80, row tiles).  The Q slice of the column tile stays in LDS; the
 // negatives are walked 64 at a time; wave w owns columns 16w..16w+15 and the four 16-negative
 // blocks of a tile.  Both operands have the contraction index (the row) as the slow one.
-template <int LOSS>
 __global__ void __launch_bounds__(320, 2)
-k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ S,
-            const float* __restrict__ rowm, int Npad, const float* __restrict__ Q, float* __restrict__ grad) {
+k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ W, int Npad,
+            const float* __restrict__ Q, float* __restrict__ grad) {
     extern __shared__ __align__(16) float gneg_smem[];
     float* Wt = gneg_smem;                    // [112][68]
     float* Qs = Wt + kGRows * kGWS;           // [112][84]
-    int32_t* ids_s = reinterpret_cast<int32_t*>(Qs + kGRows * kGSS);     // [64]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
     const TileCoord tc = tile_coord(g, blockIdx.y);
     const int c0 = blockIdx.x * kGSlice;
     const int N = g.N, d = bp.dim;
     const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
-    const float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
-    const float* rowm_tile = rowm + (int64_t)tc.si * g.P + tc.e0;
+    const float* Wtile = W + (int64_t)tc.wgrow * g.rows_tile * Npad;
     const float* Qrows = Q + ((int64_t)tc.si * g.P + tc.e0) * d;
     const int kgroups = (tc.nrows + 15) >> 4;
     const bool atomic = bp.atomic_mode != 0;
     float* Gn = tc.side == 0 ? bp.G_dst : bp.G_src;
     const int64_t neg_base = (int64_t)tc.si * g.per_side + (int64_t)g.roles * g.P + ((int64_t)tc.c * g.T + tc.t_row) * N;
-    constexpr int V4 = kGSlice / 4;
 
-    for (int idx = tid; idx < kGRows * V4; idx += 320) {
-        const int row = idx / V4, c4 = idx - row * V4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row < tc.nrows && c0 + 4 * c4 < d) v = *reinterpret_cast<const float4*>(Qrows + (int64_t)row * d + c0 + 4 * c4);
-        *reinterpret_cast<float4*>(Qs + row * kGSS + 4 * c4) = v;
+    WTileRegs<320> wr;
+    wr.fetch(Wtile, Npad, tc.nrows, 0, tid);
+    {
+        SliceRegs<320, kGRows> qr;
+        const int nrows = tc.nrows;
+        qr.fetch([=](int row) -> const float* { return row < nrows ? Qrows + (int64_t)row * d : nullptr; }, c0, d, tid);
+        qr.store(Qs, tid);
     }
     const int col = c0 + 16 * w + l15;
     for (int n0 = 0; n0 < N; n0 += kGNeg) {
-        __syncthreads();                      // the previous tile's W has been consumed (and Qs is complete)
-        if (atomic && tid < kGNeg) ids_s[tid] = my_negs[min(n0 + tid, N - 1)];
-        load_w_tile<LOSS, 320>(Wt, Stile, rowm_tile, tc.nrows, n0, N, Npad, bp.neg_weight, tid);
+        __syncthreads();                      // the previous tile's W has been consumed
+        wr.store(Wt, tid);
         __syncthreads();
+        if (n0 + kGNeg < N) wr.fetch(Wtile, Npad, tc.nrows, n0 + kGNeg, tid);
         f32x4 acc[4];
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -376,10 +404,9 @@ k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, c
             for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const int k = 16 * mb + 4 * gq + v;
-                    const int n = n0 + k;
+                    const int n = n0 + 16 * mb + 4 * gq + v;
                     if (n < N) {
-                        if (atomic) unsafeAtomicAdd(Gn + (int64_t)ids_s[k] * d + col, acc[mb][v]);
+                        if (atomic) unsafeAtomicAdd(Gn + (int64_t)my_negs[n] * d + col, acc[mb][v]);
                         else grad[(neg_base + n) * d + col] = acc[mb][v];
                     }
                 }
@@ -460,14 +487,11 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
     const int ntiles = Npad / kGNeg;
     const int coltiles = (bp.dim + kGSlice - 1) / kGSlice;
     const bool softmax = bp.loss == LEGEND_LOSS_SOFTMAX;
-    const size_t gneg_lds = sizeof(float) * (kGRows * kGWS + kGRows * kGSS) + sizeof(int32_t) * kGNeg;
+    const size_t gneg_lds = sizeof(float) * (kGRows * kGWS + kGRows * kGSS);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<LEGEND_LOSS_SOFTMAX>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<LEGEND_LOSS_LOGISTIC>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -484,21 +508,16 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
     }
     hipLaunchKernelGGL(k_gemm_scores, dim3((unsigned)ntiles, (unsigned)tiles), dim3(256), 0, st, g, bp, ws.neg_ids, ws.gemm_Q,
                        ws.gemm_S, Npad);
-    if (softmax) {
-        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)tiles), dim3(256), 0, st, g, bp, ws.gemm_S,
-                           ws.gemm_f, Npad, ws.gemm_m, ws.gemm_a, ws.loss_partial);
-        hipLaunchKernelGGL(k_gemm_gq<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), 0, st, g, bp,
-                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_G);
-        hipLaunchKernelGGL(k_gemm_gneg<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), gneg_lds, st, g, bp,
-                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_Q, ws.grad);
-    } else {
-        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(256), 0, st, g, bp, ws.gemm_S,
-                           ws.gemm_f, Npad, ws.gemm_m, ws.gemm_a, ws.loss_partial);
-        hipLaunchKernelGGL(k_gemm_gq<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), 0, st, g, bp,
-                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_G);
-        hipLaunchKernelGGL(k_gemm_gneg<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), gneg_lds, st, g, bp,
-                           ws.neg_ids, ws.gemm_S, ws.gemm_m, Npad, ws.gemm_Q, ws.grad);
-    }
+    if (softmax)
+        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
+                           ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
+    else
+        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
+                           ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
+    hipLaunchKernelGGL(k_gemm_gq, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), 0, st, g, bp, ws.neg_ids, ws.gemm_S, Npad,
+                       ws.gemm_G);
+    hipLaunchKernelGGL(k_gemm_gneg, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), gneg_lds, st, g, bp, ws.neg_ids,
+                       ws.gemm_S, Npad, ws.gemm_Q, ws.grad);
     switch (bp.score) {
         case LEGEND_SCORE_DOT:
             hipLaunchKernelGGL(k_gemm_chain<LEGEND_SCORE_DOT>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_G, ws.gemm_a, ws.grad);

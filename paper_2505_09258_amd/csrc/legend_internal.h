@@ -85,8 +85,7 @@ struct Workspace {
     // dim > 128 only: operands and intermediate results of the chain of contractions
     float*    gemm_Q;         // [sides][P][dim] composed rows
     float*    gemm_f;         // [sides][P] positive scores
-    float*    gemm_S;         // [row tiles][rows_tile][N rounded up to 64] negative scores
-    float*    gemm_m;         // [sides][P] row log-sum-exp
+    float*    gemm_S;         // [row tiles][rows_tile][N rounded up to 64] negative scores, then the weights dL/dS
     float*    gemm_a;         // [sides][P] dL/df
     float*    gemm_G;         // [sides][P][dim] G_Q
     int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel

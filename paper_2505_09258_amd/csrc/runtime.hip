@@ -251,7 +251,7 @@ void free_ctx(legend_ctx* c) {
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
                      c->ws.counters, c->ws_odd.neg_ids, c->ws_odd.keys[0], c->ws_odd.keys[1], c->ws_odd.vals[0], c->ws_odd.vals[1],
-                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->ws.gemm_Q, c->ws.gemm_G, c->ws.gemm_f, c->ws.gemm_m,
+                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->ws.gemm_Q, c->ws.gemm_G, c->ws.gemm_f,
                      c->ws.gemm_a, c->ws.gemm_S, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
@@ -560,7 +560,6 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         INIT_RC(dev_alloc(c, &w.gemm_Q, rows * c->d));
         INIT_RC(dev_alloc(c, &w.gemm_G, rows * c->d));
         INIT_RC(dev_alloc(c, &w.gemm_f, rows));
-        INIT_RC(dev_alloc(c, &w.gemm_m, rows));
         INIT_RC(dev_alloc(c, &w.gemm_a, rows));
         INIT_RC(dev_alloc(c, &w.gemm_S, (size_t)nwg * c->gmax.rows_tile * (size_t)gemm_npad(c->gmax.N)));
     }
