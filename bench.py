@@ -257,7 +257,8 @@ def main() -> int:
     alg_bytes = 12 * P + 4 * Q + 4 * d * (2 * P + Q) + 16 * d * u_b
     single_sweep = (w.dim == 100 and w.loss == graphs.LOSS_SOFTMAX and w.num_negs <= 1024 and args.update_mode != "atomic"
                     and os.environ.get("LEGEND_NO_FAST_CHUNK") != "1")
-    kname = "k_chunk_wide" if w.dim > 128 else ("k_chunk_fast" if single_sweep else "k_chunk")
+    kname = ("k_gemm_compose/scores/rowstats/gq/gneg/chain (one launch each)" if w.dim > 128
+             else ("k_chunk_fast" if single_sweep else "k_chunk"))
     roofline = {"kernel": kname + " (gather + scores + loss + backward, fp32 MFMA)", "bound": "mfma",
                 "achieved": round(achieved_tflops, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4),
