@@ -106,6 +106,9 @@ def main() -> int:
     ap.add_argument("--capacity", type=int, default=0, help="buffer slots for --epoch (0: all partitions resident)")
     ap.add_argument("--no-overlap", action="store_true", help="--epoch: serialize swaps (the paper's 'without prefetching')")
     ap.add_argument("--ablation", action="store_true", help="--epoch: afterwards run the same number of epochs with swaps serialised")
+    ap.add_argument("--dim", type=int, default=0, help="override the embedding dimension of the workload (dimension sweep)")
+    ap.add_argument("--score", choices=["dot", "distmult", "complex"], default=None, help="override the score function")
+    ap.add_argument("--batch-size", type=int, default=0, help="override the batch size")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -123,6 +126,18 @@ def main() -> int:
     w = graphs.WORKLOADS[args.workload]
     if args.scale > 1:
         w = graphs.scaled(w, args.scale)
+    over = {}
+    if args.dim:
+        over["dim"] = args.dim
+    if args.score:
+        over["score"] = {"dot": graphs.SCORE_DOT, "distmult": graphs.SCORE_DISTMULT, "complex": graphs.SCORE_COMPLEX}[args.score]
+        if over["score"] != graphs.SCORE_DOT and w.num_relations == 0:
+            over["num_relations"] = 1
+    if args.batch_size:
+        over["batch_size"] = args.batch_size
+    if over:
+        import dataclasses
+        w = dataclasses.replace(w, name=w.name + "+" + ",".join(f"{k}={v}" for k, v in over.items()), **over)
 
     t0 = time.time()
     last = [time.time()]

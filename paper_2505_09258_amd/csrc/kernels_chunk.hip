@@ -31,7 +31,7 @@ int rows_per_tile_for(int chunk_size, int dim) {
     return (chunk_size + t - 1) / t;
 }
 int max_dim_supported() { return kWideMaxDim; }
-bool dim_supported(int dim) { return dim >= 1 && (dim <= kNarrowMaxDim || (dim <= kWideMaxDim && dim % 4 == 0)); }
+bool dim_supported(int dim) { return dim >= 1 && dim <= kWideMaxDim; }
 
 // NB: number of 32-wide column blocks covering the embedding dimension (dim <= 32 * NB).
 // DFIX: the embedding dimension when it is known at compile time (strides, trip counts and

@@ -1,4 +1,4 @@
-// Batch computation for wide embeddings (128 < dim <= 512, dim a multiple of 4; paper Sec. 2.1
+// Batch computation for wide embeddings (128 < dim <= 512; paper Sec. 2.1
 // stage 5, Sec. 6) as a short chain of tiled fp32-MFMA contractions.  A (row tile of <= 112
 // positives) x (all N negatives) score block does not fit on chip next to d-wide operand tiles,
 // so the scores go through a device buffer that stays in the L2 / Infinity cache (the paper keeps
@@ -136,7 +136,19 @@ struct SliceRegs {                            // [ROWS][80 columns] of row-major
             const int idx = tid + THREADS * k;
             const int row = idx / V4, c4 = idx - row * V4;
             const float* p = row < ROWS ? row_ptr(row) : nullptr;
-            v[k] = (p && c0 + 4 * c4 < d) ? *reinterpret_cast<const float4*>(p + c0 + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int c = c0 + 4 * c4;
+            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p && c < d) {
+                if ((d & 3) == 0) {           // rows are 16-byte aligned only then
+                    o = *reinterpret_cast<const float4*>(p + c);
+                } else {
+                    o.x = p[c];
+                    if (c + 1 < d) o.y = p[c + 1];
+                    if (c + 2 < d) o.z = p[c + 2];
+                    if (c + 3 < d) o.w = p[c + 3];
+                }
+            }
+            v[k] = o;
         }
     }
     __device__ void store(float* T, int tid) const {
@@ -479,7 +491,7 @@ k_gemm_chain(BatchGeom g, BucketParams bp, const float* __restrict__ Q, const fl
 int64_t gemm_npad(int N) { return ((int64_t)N + kGNeg - 1) / kGNeg * kGNeg; }
 
 hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    if (bp.dim <= kNarrowMaxDim || bp.dim > kWideMaxDim || (bp.dim & 3) || g.rows_tile > kGRows || !ws.gemm_Q)
+    if (bp.dim <= kNarrowMaxDim || bp.dim > kWideMaxDim || g.rows_tile > kGRows || !ws.gemm_Q)
         return hipErrorInvalidValue;
     const int64_t tiles = (int64_t)g.sides * g.nchunks * g.T;
     const int64_t rows = (int64_t)g.sides * g.P;

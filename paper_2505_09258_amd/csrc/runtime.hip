@@ -398,7 +398,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     if (cfg->num_nodes < 1 || cfg->dim < 1 || cfg->num_partitions < 1 || cfg->num_partitions > cfg->num_nodes)
         return fail(LEGEND_E_INVAL, "num_nodes, dim, num_partitions must be positive and num_partitions <= num_nodes");
     if (!dim_supported(cfg->dim))
-        return fail(LEGEND_E_INVAL, "dim %d is not supported (1..128, or a multiple of 4 up to %d)", cfg->dim, max_dim_supported());
+        return fail(LEGEND_E_INVAL, "dim %d is not supported (1..%d)", cfg->dim, max_dim_supported());
     if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 2 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
     if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)

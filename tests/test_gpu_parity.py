@@ -41,6 +41,8 @@ CASES = [
     _case("complex_d100_softmax_pos", COMPLEX, SOFTMAX_POS, BOTH, 5_000, 9, 100, 2, 0, 1, 600, 50, 200, 40, 1_300, 0.3),
     _case("dot_d48_softmax_pos", DOT, SOFTMAX_POS, DST, 3_000, 0, 48, 1, 0, 0, 500, 64, 100, 0, 1_100, 0.3),
     _case("distmult_d256_softmax_pos", DISTMULT, SOFTMAX_POS, SRC, 2_000, 5, 256, 1, 0, 0, 200, 40, 70, 0, 450, 0.2),
+    # a wide dimension that is not a multiple of four (rows only 8-byte aligned); chunks of 120 rows take two row tiles
+    _case("complex_d150_both", COMPLEX, SOFTMAX, BOTH, 2_500, 6, 150, 2, 1, 0, 300, 120, 90, 20, 700, 0.2),
 ]
 
 # One node row in 64 is four times larger than the rest, so that some chunks hold a score far
