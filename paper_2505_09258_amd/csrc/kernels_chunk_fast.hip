@@ -164,7 +164,7 @@ template <int SCORE, int D>
 __global__ void __launch_bounds__(kFThreads, 1)
 k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float* __restrict__ grad,
              double* __restrict__ loss_partial, uint32_t* __restrict__ redo, unsigned long long* __restrict__ redo_total,
-             float limit) {
+             float limit, int retry_in_place) {
     using Sh = FastShape<D>;
     using Item = RowItem<SCORE, D>;
     constexpr int QS = Sh::QS, KG = Sh::KG, KT = Sh::KT, NJ = Sh::NJ, STEPS = Sh::STEPS;
@@ -305,27 +305,12 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 
     f32x4 P[kFMaxSteps][4];                   // the chunk's softmax numerators owned by this wave
     f32x4 accB[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) accB[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float top = -1e30f;                       // largest S - reference seen
+    float top;                                // largest S - reference seen
+    bool bad = false;
 
-    __syncthreads();                          // ids, Q and the references are in LDS
-    if (tile_of(0) < ntiles) gather_issue(tile_of(0));
-
-    // scores and numerators of tile i of this group; P[i] is written
-    // With FIRST (tile 0, wave group 0) the reference is made on the way: the row maxima of this
-    // tile, exchanged between the four waves across one extra workgroup barrier.
-    auto score_tile = [&](auto I, auto FIRST) __attribute__((always_inline)) {
-        constexpr int i = decltype(I)::value;
-        constexpr bool first = decltype(FIRST)::value;
-        const int t = tile_of(i);
-        gather_commit(t);                     // own rows only; their last readers are a barrier behind
-        if (tile_of(i + 1) < ntiles) gather_issue(t + 2);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        f32x4 acc[4];
+    // scores of all 64 rows against the wave's own 16 negatives of its group's tile in LDS;
+    // columns past the last negative get -1e30
+    auto score_block = [&](int t, f32x4 (&acc)[4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
         const float* qa = Qs + l15 * QS + 4 * gq;
@@ -352,12 +337,41 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[r] = mfma16(Qs[(16 * r + l15) * QS + k], b, acc[r]);
         }
-        if (neg_of(t, 16 * wl + l15) >= N) {                  // columns past the last negative
+        if (neg_of(t, 16 * wl + l15) >= N) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[r] = f32x4{-1e30f, -1e30f, -1e30f, -1e30f};
         }
+    };
+
+    __syncthreads();                          // ids, Q and the positive scores are in LDS
+    // One pass in ordinary training.  If the sampled reference turns out too low for some score
+    // (or the positive, in the variant that counts it), the exact row maxima are taken in a
+    // scores-only pass and the sweep runs once more (a second copy of its code, EXACT): the
+    // workgroup pays, the launch does not.
+    auto sweep_and_sums = [&](auto EXACT) __attribute__((always_inline)) {
+    constexpr bool exact_ref = decltype(EXACT)::value;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) accB[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    top = -1e30f;
+    if (tile_of(0) < ntiles) gather_issue(tile_of(0));
+
+    // scores and numerators of tile i of this group; P[i] is written
+    // With FIRST (tile 0, wave group 0) the reference is made on the way: the row maxima of this
+    // tile, exchanged between the four waves across one extra workgroup barrier.
+    auto score_tile = [&](auto I, auto FIRST) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
+        constexpr bool first = decltype(FIRST)::value;
+        const int t = tile_of(i);
+        gather_commit(t);                     // own rows only; their last readers are a barrier behind
+        if (tile_of(i + 1) < ntiles) gather_issue(t + 2);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        f32x4 acc[4];
+        score_block(t, acc);
         float4 reff[4];
-        if constexpr (first) {
+        if (first && !exact_ref) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -444,7 +458,9 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                             score_tile(std::integral_constant<int, h / 2>{}, std::integral_constant<bool, h == 0>{});
                     }
                 } else {
-                    if constexpr (h == 0) __syncthreads();        // the barrier inside group 0's first tile
+                    if constexpr (h == 0) {
+                        if (!exact_ref) __syncthreads();          // the barrier inside group 0's first tile
+                    }
                     if constexpr (h >= 2) {
                         if (tile_of(h / 2 - 1) < ntiles) accumulate_tile(h / 2 - 1);
                     }
@@ -504,9 +520,60 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         mx_s[tid] = live ? pos_term / sum - 1.f : 0.f;      // dL/df (the maxima kept here are no longer needed)
     }
     __syncthreads();
-    bool bad = flag_s[8] != 0u;
+    bad = flag_s[8] != 0u;
 #pragma unroll
     for (int ww = 0; ww < kFWaves; ++ww) bad |= flag_s[ww] != 0u;
+    };
+    sweep_and_sums(std::false_type{});
+    if (bad && retry_in_place) {
+    // ---- exact row maxima: scores only, every wave on its own gathered rows, no workgroup barrier
+        if (tid == 0) atomicAdd(redo_total, 1ull);
+        f32x4 mxv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mxv[r] = f32x4{-1e30f, -1e30f, -1e30f, -1e30f};
+        if (tile_of(0) < ntiles) gather_issue(tile_of(0));
+        for (int i = 0; tile_of(i) < ntiles; ++i) {
+            const int t = tile_of(i);
+            gather_commit(t);
+            if (tile_of(i + 1) < ntiles) gather_issue(t + 2);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            f32x4 acc[4];
+            score_block(t, acc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) mxv[r][v] = fmaxf(mxv[r][v], acc[r][v]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        float* Mw = Ws;                       // [8 waves][64 rows]
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float m = mxv[r][v];
+                m = fmaxf(m, wave_shfl_xor(m, 1));
+                m = fmaxf(m, wave_shfl_xor(m, 2));
+                m = fmaxf(m, wave_shfl_xor(m, 4));
+                m = fmaxf(m, wave_shfl_xor(m, 8));
+                if (l15 == 0) Mw[w * kFRow + 16 * r + 4 * gq + v] = m;
+            }
+        }
+        __syncthreads();
+        if (tid < kFRow) {
+            float m = Mw[tid];
+#pragma unroll
+            for (int ww = 1; ww < kFWaves; ++ww) m = fmaxf(m, Mw[ww * kFRow + tid]);
+            if (bp.softmax_with_pos) m = fmaxf(m, f_s[tid]);
+            ref_s[tid] = tid < nrows ? m : 1e30f;
+        }
+        if (tid < 16) flag_s[tid] = 0;
+        __syncthreads();
+        sweep_and_sums(std::true_type{});
+    }
     if (tid == 0) {
         redo[blockIdx.x] = bad ? 1u : 0u;
         if (bad) atomicAdd(redo_total, 1ull);
@@ -670,7 +737,7 @@ static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const Buck
         configured = true;
     }
     hipLaunchKernelGGL((k_chunk_fast<SC, D>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,
-                       ws.loss_partial, ws.redo, ws.redo_total, ws.fast_limit);
+                       ws.loss_partial, ws.redo, ws.redo_total, ws.fast_limit, ws.fast_no_retry ? 0 : 1);
     return hipGetLastError();
 }
 
