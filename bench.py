@@ -24,7 +24,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 # HBM bytes per k_chunk_fast launch from the rocprofv3 counter runs summarised in
 # profiles/c2_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB, calibrated on a copy)
-CHUNK_TRAFFIC_BYTES = {"c2": int((275977.3 * 2.0 + 442509.5) * 1024)}
+CHUNK_TRAFFIC_BYTES = {"c2": int((303129.8 * 2.0 + 487898.9) * 1024)}
 
 
 def log(*a):
