@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblegend_hip.so")
 
-SOURCES = ["runtime.hip", "kernels_prepare.hip", "kernels_sort.hip", "kernels_chunk.hip", "kernels_chunk_gemm.hip", "kernels_chunk_fast.hip",
+SOURCES = ["runtime.hip", "kernels_prepare.hip", "kernels_sort.hip", "kernels_chunk.hip", "kernels_chunk_gemm.hip", "kernels_chunk_fast.hip", "kernels_chunk_fast_distmult.hip", "kernels_chunk_fast_complex.hip",
            "kernels_update.hip", "order_plan.cpp"]
 
 HIP_FLAGS = [
@@ -54,7 +54,7 @@ def build_library(verbose: bool = False) -> str:
             print(r.stderr, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     tmp = LIB_PATH + ".tmp"
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp],

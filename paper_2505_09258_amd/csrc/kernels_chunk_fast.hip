@@ -34,6 +34,10 @@
 
 #include "chunk_common.h"
 
+#ifndef LEGEND_FAST_SCORE
+#define LEGEND_FAST_SCORE 0     // 0 Dot (and the dispatch), 1 DistMult, 2 ComplEx: one translation unit each
+#endif
+
 namespace legend {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -718,13 +722,9 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 }
 
 // Built only for the dimension of the paper's large workloads (the fully unrolled sweep is
-// expensive to compile); every other shape takes the general kernel.
-bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp) {
-    if (bp.loss != LEGEND_LOSS_SOFTMAX || bp.atomic_mode != 0) return false;
-    if (g.N > 2 * kFMaxSteps * kFTile || g.N > kIdsLds || g.rows_tile > kFRow) return false;
-    return bp.dim == 100;
-}
-
+// expensive to compile); every other shape takes the general kernel.  Each score function is
+// compiled in a translation unit of its own (this file with LEGEND_FAST_SCORE set), so that the
+// three compile side by side.
 template <int SC, int D>
 static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     dim3 grid((unsigned)(g.sides * g.nchunks * g.T)), block(kFThreads);
@@ -741,11 +741,35 @@ static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const Buck
     return hipGetLastError();
 }
 
+hipError_t launch_fast_dot_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_fast_distmult_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_fast_complex_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+
+#if LEGEND_FAST_SCORE == 0
+hipError_t launch_fast_dot_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    return launch_fast_one<LEGEND_SCORE_DOT, 100>(st, g, bp, ws);
+}
+
+bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp) {
+    if (bp.loss != LEGEND_LOSS_SOFTMAX || bp.atomic_mode != 0) return false;
+    if (g.N > 2 * kFMaxSteps * kFTile || g.N > kIdsLds || g.rows_tile > kFRow) return false;
+    return bp.dim == 100;
+}
+
 hipError_t launch_chunks_fast(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     if (bp.dim != 100) return hipErrorInvalidValue;
-    if (bp.score == LEGEND_SCORE_DOT) return launch_fast_one<LEGEND_SCORE_DOT, 100>(st, g, bp, ws);
-    if (bp.score == LEGEND_SCORE_DISTMULT) return launch_fast_one<LEGEND_SCORE_DISTMULT, 100>(st, g, bp, ws);
+    if (bp.score == LEGEND_SCORE_DOT) return launch_fast_dot_100(st, g, bp, ws);
+    if (bp.score == LEGEND_SCORE_DISTMULT) return launch_fast_distmult_100(st, g, bp, ws);
+    return launch_fast_complex_100(st, g, bp, ws);
+}
+#elif LEGEND_FAST_SCORE == 1
+hipError_t launch_fast_distmult_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    return launch_fast_one<LEGEND_SCORE_DISTMULT, 100>(st, g, bp, ws);
+}
+#else
+hipError_t launch_fast_complex_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     return launch_fast_one<LEGEND_SCORE_COMPLEX, 100>(st, g, bp, ws);
 }
+#endif
 
 }  // namespace legend
