@@ -123,9 +123,9 @@ struct WTileRegs {
     }
 };
 
-template <int THREADS, int ROWS>
-struct SliceRegs {                            // [ROWS][80 columns] of row-major fp32 rows
-    static constexpr int V4 = kGSlice / 4;
+template <int THREADS, int ROWS, int WIDTH = kGSlice>
+struct SliceRegs {                            // [ROWS][WIDTH columns] of row-major fp32 rows, LDS row stride WIDTH + 4
+    static constexpr int V4 = WIDTH / 4;
     static constexpr int ITEMS = (ROWS * V4 + THREADS - 1) / THREADS;
     float4 v[ITEMS];
     // row_ptr(row) gives the start of the row or nullptr for a row that does not exist
@@ -156,7 +156,7 @@ struct SliceRegs {                            // [ROWS][80 columns] of row-major
         for (int k = 0; k < ITEMS; ++k) {
             const int idx = tid + THREADS * k;
             const int row = idx / V4, c4 = idx - row * V4;
-            if (row < ROWS) *reinterpret_cast<float4*>(T + row * kGSS + 4 * c4) = v[k];
+            if (row < ROWS) *reinterpret_cast<float4*>(T + row * (WIDTH + 4) + 4 * c4) = v[k];
         }
     }
 };
@@ -292,24 +292,31 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
 }
 
 // ---- G_Q = W Neg ---------------------------------------------------------------------------------
-// grid: (column tiles of 80, row tiles).  Five waves; wave w owns columns 16w..16w+15 of the tile
-// and all row blocks; the negatives are streamed 64 at a time, the next tile in flight.
-__global__ void __launch_bounds__(320, 2)
+// grid: (column tiles of CT, row tiles).  CT / 16 waves; wave w owns columns 16w..16w+15 of the
+// tile and all row blocks; the negatives are streamed 64 at a time, the next tile in flight.
+// (A multiple of four waves keeps the four SIMDs of a compute unit evenly loaded between the
+// workgroup barriers.)
+constexpr int kGColTile = 128;            // G_Q: eight waves, 64 KB of LDS, two workgroups per compute unit
+constexpr int kGNegColTile = 80;          // G_neg: five waves; a 128-column Q slice would leave room for one workgroup only (slower)
+template <int CT>
+__global__ void __launch_bounds__(CT * 4)
 k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ W, int Npad,
           float* __restrict__ GQ) {
-    __shared__ __align__(16) float Wt[kGRows * kGWS];
-    __shared__ __align__(16) float Nt[kGNeg * kGSS];
+    constexpr int THREADS = CT * 4, CS = CT + 4;
+    extern __shared__ __align__(16) float gq_smem[];
+    float* Wt = gq_smem;                      // [112][68]
+    float* Nt = Wt + kGRows * kGWS;           // [64][CT + 4]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
     const TileCoord tc = tile_coord(g, blockIdx.y);
-    const int c0 = blockIdx.x * kGSlice;
+    const int c0 = blockIdx.x * CT;
     const int N = g.N, d = bp.dim;
     const float* En = tc.side == 0 ? bp.E_dst : bp.E_src;
     const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
     const float* Wtile = W + (int64_t)tc.wgrow * g.rows_tile * Npad;
     const int rblocks = (tc.nrows + 15) >> 4;
 
-    WTileRegs<320> wr;
-    SliceRegs<320, kGNeg> nr;
+    WTileRegs<THREADS> wr;
+    SliceRegs<THREADS, kGNeg, CT> nr;
     auto neg_row = [&](int n0) {
         return [=](int row) -> const float* { return n0 + row < N ? En + (int64_t)my_negs[n0 + row] * d : nullptr; };
     };
@@ -327,13 +334,13 @@ k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, con
             wr.fetch(Wtile, Npad, tc.nrows, n0 + kGNeg, tid);
             nr.fetch(neg_row(n0 + kGNeg), c0, d, tid);
         }
-        const int groups = (min(kGNeg, N - n0) + 15) >> 4;
+        const int groups = c0 + 16 * w < d ? (min(kGNeg, N - n0) + 15) >> 4 : 0;    // nothing for a column block past d
         const float* wa = Wt + l15 * kGWS + 4 * gq;
-        const float* nb = Nt + (4 * gq) * kGSS + 16 * w + l15;
+        const float* nb = Nt + (4 * gq) * CS + 16 * w + l15;
         for (int G = 0; G < groups; ++G) {
             float b[4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) b[s] = nb[(16 * G + s) * kGSS];
+            for (int s = 0; s < 4; ++s) b[s] = nb[(16 * G + s) * CS];
 #pragma unroll
             for (int r = 0; r < kGRowBlocks; ++r) {
                 if (r < rblocks) {
@@ -362,18 +369,20 @@ k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, con
 }
 
 // ---- G_neg = W^T Q -------------------------------------------------------------------------------
-// grid: (column tiles of 80, row tiles).  The Q slice of the column tile stays in LDS; the
+// grid: (column tiles of CT, row tiles).  The Q slice of the column tile stays in LDS; the
 // negatives are walked 64 at a time; wave w owns columns 16w..16w+15 and the four 16-negative
 // blocks of a tile.  Both operands have the contraction index (the row) as the slow one.
-__global__ void __launch_bounds__(320, 2)
+template <int CT>
+__global__ void __launch_bounds__(CT * 4)
 k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ W, int Npad,
             const float* __restrict__ Q, float* __restrict__ grad) {
     extern __shared__ __align__(16) float gneg_smem[];
+    constexpr int THREADS = CT * 4, CS = CT + 4;
     float* Wt = gneg_smem;                    // [112][68]
-    float* Qs = Wt + kGRows * kGWS;           // [112][84]
+    float* Qs = Wt + kGRows * kGWS;           // [112][CT + 4]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
     const TileCoord tc = tile_coord(g, blockIdx.y);
-    const int c0 = blockIdx.x * kGSlice;
+    const int c0 = blockIdx.x * CT;
     const int N = g.N, d = bp.dim;
     const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
     const float* Wtile = W + (int64_t)tc.wgrow * g.rows_tile * Npad;
@@ -383,15 +392,16 @@ k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, c
     float* Gn = tc.side == 0 ? bp.G_dst : bp.G_src;
     const int64_t neg_base = (int64_t)tc.si * g.per_side + (int64_t)g.roles * g.P + ((int64_t)tc.c * g.T + tc.t_row) * N;
 
-    WTileRegs<320> wr;
+    WTileRegs<THREADS> wr;
     wr.fetch(Wtile, Npad, tc.nrows, 0, tid);
     {
-        SliceRegs<320, kGRows> qr;
+        SliceRegs<THREADS, kGRows, CT> qr;
         const int nrows = tc.nrows;
         qr.fetch([=](int row) -> const float* { return row < nrows ? Qrows + (int64_t)row * d : nullptr; }, c0, d, tid);
         qr.store(Qs, tid);
     }
     const int col = c0 + 16 * w + l15;
+    const bool col0_live = c0 + 16 * w < d;   // uniform per wave
     for (int n0 = 0; n0 < N; n0 += kGNeg) {
         __syncthreads();                      // the previous tile's W has been consumed
         wr.store(Wt, tid);
@@ -401,11 +411,11 @@ k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, c
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
         const float* wa = Wt + (4 * gq) * kGWS + l15;
-        const float* qb = Qs + (4 * gq) * kGSS + 16 * w + l15;
-        for (int G = 0; G < kgroups; ++G) {
+        const float* qb = Qs + (4 * gq) * CS + 16 * w + l15;
+        for (int G = 0; G < (col0_live ? kgroups : 0); ++G) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const float b = qb[(16 * G + s) * kGSS];
+                const float b = qb[(16 * G + s) * CS];
                 const float* arow = wa + (16 * G + s) * kGWS;
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma16g(arow[16 * mb], b, acc[mb]);
@@ -497,13 +507,18 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
     const int64_t rows = (int64_t)g.sides * g.P;
     const int Npad = (int)gemm_npad(g.N);
     const int ntiles = Npad / kGNeg;
-    const int coltiles = (bp.dim + kGSlice - 1) / kGSlice;
+    const int coltiles = (bp.dim + kGColTile - 1) / kGColTile;
     const bool softmax = bp.loss == LEGEND_LOSS_SOFTMAX;
-    const size_t gneg_lds = sizeof(float) * (kGRows * kGWS + kGRows * kGSS);
+    const int negtiles = (bp.dim + kGNegColTile - 1) / kGNegColTile;
+    const size_t gneg_lds = sizeof(float) * (kGRows * kGWS + kGRows * (kGNegColTile + 4));
+    const size_t gq_lds = sizeof(float) * (kGRows * kGWS + kGNeg * (kGColTile + 4));
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<kGNegColTile>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gq<kGColTile>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)gq_lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -526,9 +541,9 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
     else
         hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
                            ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
-    hipLaunchKernelGGL(k_gemm_gq, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), 0, st, g, bp, ws.neg_ids, ws.gemm_S, Npad,
+    hipLaunchKernelGGL(k_gemm_gq<kGColTile>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(kGColTile * 4), gq_lds, st, g, bp, ws.neg_ids, ws.gemm_S, Npad,
                        ws.gemm_G);
-    hipLaunchKernelGGL(k_gemm_gneg, dim3((unsigned)coltiles, (unsigned)tiles), dim3(320), gneg_lds, st, g, bp, ws.neg_ids,
+    hipLaunchKernelGGL(k_gemm_gneg<kGNegColTile>, dim3((unsigned)negtiles, (unsigned)tiles), dim3(kGNegColTile * 4), gneg_lds, st, g, bp, ws.neg_ids,
                        ws.gemm_S, Npad, ws.gemm_Q, ws.grad);
     switch (bp.score) {
         case LEGEND_SCORE_DOT:

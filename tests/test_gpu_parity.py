@@ -31,7 +31,7 @@ CASES = [
     _case("distmult_d6", DISTMULT, SOFTMAX, BOTH, 500, 3, 6, 2, 0, 1, 64, 7, 5, 2, 130, 0.5),
     _case("dot_d70_single_negative", DOT, SOFTMAX, DST, 900, 0, 70, 1, 0, 0, 100, 1, 1, 0, 150, 0.3),
     _case("complex_d34", COMPLEX, SOFTMAX, DST, 900, 4, 34, 1, 0, 0, 120, 33, 65, 0, 250, 0.4),
-    # dimensions above 128 take the wide kernel (32-row tiles, contraction split across waves)
+    # dimensions above 128 take the chain of tiled contractions (112-row tiles, scores in a device buffer)
     _case("distmult_d400_both", DISTMULT, SOFTMAX, BOTH, 3_000, 45, 400, 1, 0, 0, 400, 100, 130, 0, 900, 0.15),
     _case("complex_d132_offdiag", COMPLEX, SOFTMAX, BOTH, 2_000, 7, 132, 2, 1, 0, 150, 40, 33, 8, 320, 0.3),
     _case("dot_d512_logistic", DOT, LOGISTIC, SRC, 800, 0, 512, 1, 0, 0, 96, 32, 64, 0, 200, 0.1),
