@@ -32,6 +32,22 @@ constexpr int kGWS = kGNeg + 4;          // LDS row stride of a W tile
 
 static_assert(kGRows == kWideRowTile, "tile geometry");
 
+// Workgroup ids are dealt round-robin to the eight XCDs, each with its own L2.  The tiled
+// kernels launch a one-dimensional grid of 8 * ceil(total / 8) workgroups and turn the hardware
+// id into a virtual id such that consecutive virtual ids (the tiles that share a row tile's
+// operands) run on the same XCD.  Returns false for the padding workgroups.
+constexpr int kXcds = 8;
+__host__ __device__ inline int64_t xcd_grid(int64_t total) { return (total + kXcds - 1) / kXcds * kXcds; }
+__device__ inline bool xcd_tile(int64_t total, int nx, int* bx, int64_t* by) {
+    const int64_t lin = blockIdx.x;
+    const int64_t per = (total + kXcds - 1) / kXcds;
+    const int64_t v = (lin % kXcds) * per + lin / kXcds;
+    if (v >= total) return false;
+    *bx = (int)(v % nx);
+    *by = v / nx;
+    return true;
+}
+
 struct TileCoord {
     int si, side, c, t_row, nrows;
     int64_t e0;          // first edge of the tile inside the batch
@@ -104,12 +120,13 @@ struct WTileRegs {
     static constexpr int V4 = kGNeg / 4;
     static constexpr int ITEMS = (kGRows * V4 + THREADS - 1) / THREADS;
     float4 v[ITEMS];
-    __device__ void fetch(const float* Wtile, int Npad, int nrows, int n0, int tid) {
+    // Wtile: start of the row tile's block; the 64-negative tile n0 / 64 is the contiguous piece [rows_tile][64]
+    __device__ void fetch(const float* Wtile, int rows_tile, int nrows, int n0, int tid) {
 #pragma unroll
         for (int k = 0; k < ITEMS; ++k) {
             const int idx = tid + THREADS * k;
             const int row = idx / V4, c4 = idx - row * V4;
-            v[k] = row < nrows ? *reinterpret_cast<const float4*>(Wtile + (int64_t)row * Npad + n0 + 4 * c4)
+            v[k] = row < nrows ? *reinterpret_cast<const float4*>(Wtile + ((int64_t)(n0 / kGNeg) * rows_tile + row) * kGNeg + 4 * c4)
                                : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
@@ -163,16 +180,21 @@ struct SliceRegs {                            // [ROWS][WIDTH columns] of row-ma
 
 // ---- S = Q Neg^T ---------------------------------------------------------------------------------
 // grid: (negative tiles, row tiles).  Four waves; wave w owns negatives 16w..16w+15 of the tile
-// and all row blocks.  S is stored as [row tile][row][Npad].
+// and all row blocks.  S is stored as [row tile][64-negative tile][row][64], so that the tiles the
+// later kernels load are contiguous.
+template <int RB>                             // row blocks of 16 that the tile geometry needs
 __global__ void __launch_bounds__(256, 2)
 k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ Q,
-              float* __restrict__ S, int Npad) {
+              float* __restrict__ S, int Npad, int nx, int64_t ny) {
     __shared__ __align__(16) float Qs[kGRows * kGSS];
     __shared__ __align__(16) float Ns[kGNeg * kGSS];
     __shared__ int32_t ids_s[kGNeg];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
-    const TileCoord tc = tile_coord(g, blockIdx.y);
-    const int n0 = blockIdx.x * kGNeg;
+    int bx;
+    int64_t by;
+    if (!xcd_tile((int64_t)nx * ny, nx, &bx, &by)) return;       // uniform
+    const TileCoord tc = tile_coord(g, by);
+    const int n0 = bx * kGNeg;
     const int N = g.N, d = bp.dim;
     const float* En = tc.side == 0 ? bp.E_dst : bp.E_src;
     const float* Qrows = Q + ((int64_t)tc.si * g.P + tc.e0) * d;
@@ -180,10 +202,9 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
     if (tid < kGNeg) ids_s[tid] = my_negs[min(n0 + tid, N - 1)];
     __syncthreads();
 
-    f32x4 acc[kGRowBlocks];
+    f32x4 acc[RB];
 #pragma unroll
-    for (int r = 0; r < kGRowBlocks; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int rblocks = (tc.nrows + 15) >> 4;
+    for (int r = 0; r < RB; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int nrows = tc.nrows;
     auto q_row = [=](int row) -> const float* { return row < nrows ? Qrows + (int64_t)row * d : nullptr; };
     const int32_t* ids = ids_s;
@@ -205,18 +226,19 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
         const int groups = min(kGSlice, d - c0 + 15) >> 4;
         const float* nb = Ns + (16 * w + l15) * kGSS + 4 * gq;
         const float* qa = Qs + l15 * kGSS + 4 * gq;
-        for (int G = 0; G < groups; ++G) {
+        for (int G = 0; G < groups; ++G) {    // all operand reads of a group first, then its MFMAs
             const float4 b = lds4(nb + 16 * G);
+            float4 a[RB];
 #pragma unroll
-            for (int r = 0; r < kGRowBlocks; ++r) {
-                if (r < rblocks) {
-                    const float4 a = lds4(qa + 16 * r * kGSS + 16 * G);
-                    acc[r] = mfma16g(a.x, b.x, acc[r]);
-                    acc[r] = mfma16g(a.y, b.y, acc[r]);
-                    acc[r] = mfma16g(a.z, b.z, acc[r]);
-                    acc[r] = mfma16g(a.w, b.w, acc[r]);
-                }
-            }
+            for (int r = 0; r < RB; ++r) a[r] = lds4(qa + 16 * r * kGSS + 16 * G);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].x, b.x, acc[r]);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].y, b.y, acc[r]);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].z, b.z, acc[r]);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].w, b.w, acc[r]);
         }
         __syncthreads();
     }
@@ -224,11 +246,11 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
     float* Srow = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
     if (n < N) {
 #pragma unroll
-        for (int r = 0; r < kGRowBlocks; ++r) {
+        for (int r = 0; r < RB; ++r) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = 16 * r + 4 * gq + v;
-                if (row < tc.nrows) Srow[(int64_t)row * Npad + n] = acc[r][v];
+                if (row < tc.nrows) Srow[((int64_t)bx * g.rows_tile + row) * kGNeg + 16 * w + l15] = acc[r][v];
             }
         }
     }
@@ -252,16 +274,18 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
     float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
     double loss = 0.0;
     for (int row = w; row < tc.nrows; row += WAVES) {
-        float* s = Stile + (int64_t)row * Npad;
+        float* s = Stile + (int64_t)row * kGNeg;          // element n of the row sits at s[(n / 64) * tstride + n % 64]
+        const int64_t tstride = (int64_t)g.rows_tile * kGNeg;
+        auto at = [&](int n) -> float& { return s[(n >> 6) * tstride + (n & 63)]; };
         const int64_t ridx = (int64_t)tc.si * g.P + tc.e0 + row;
         const float f = fpos[ridx];
         if (LOSS == LEGEND_LOSS_SOFTMAX) {
             float m = -INFINITY;
-            for (int n = lane; n < N; n += kWave) m = fmaxf(m, s[n]);
+            for (int n = lane; n < N; n += kWave) m = fmaxf(m, at(n));
             for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
             if (bp.softmax_with_pos) m = fmaxf(m, f);
             float l = 0.f;
-            for (int n = lane; n < N; n += kWave) l += fast_exp(s[n] - m);
+            for (int n = lane; n < N; n += kWave) l += fast_exp(at(n) - m);
             for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, kWave);
             float a = -1.f;
             if (bp.softmax_with_pos) {
@@ -270,14 +294,14 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
                 a = pf / l - 1.f;
             }
             const float il = 1.f / l;
-            for (int n = lane; n < Npad; n += kWave) s[n] = n < N ? fast_exp(s[n] - m) * il : 0.f;
+            for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? fast_exp(at(n) - m) * il : 0.f;
             if (lane == 0) rowa[ridx] = a;
             loss += (double)(m + logf(l) - f);
         } else {
             float t = 0.f;
-            for (int n = lane; n < N; n += kWave) t += softplusf(s[n]);
+            for (int n = lane; n < N; n += kWave) t += softplusf(at(n));
             for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
-            for (int n = lane; n < Npad; n += kWave) s[n] = n < N ? bp.neg_weight * sigmoidf(s[n]) : 0.f;
+            for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? bp.neg_weight * sigmoidf(at(n)) : 0.f;
             if (lane == 0) rowa[ridx] = -sigmoidf(-f);
             loss += (double)(softplusf(-f) + bp.neg_weight * t);
         }
@@ -298,40 +322,42 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
 // workgroup barriers.)
 constexpr int kGColTile = 128;            // G_Q: eight waves, 64 KB of LDS, two workgroups per compute unit
 constexpr int kGNegColTile = 80;          // G_neg: five waves; a 128-column Q slice would leave room for one workgroup only (slower)
-template <int CT>
+template <int CT, int RB>
 __global__ void __launch_bounds__(CT * 4)
 k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ W, int Npad,
-          float* __restrict__ GQ) {
+          float* __restrict__ GQ, int nx, int64_t ny) {
     constexpr int THREADS = CT * 4, CS = CT + 4;
     extern __shared__ __align__(16) float gq_smem[];
     float* Wt = gq_smem;                      // [112][68]
     float* Nt = Wt + kGRows * kGWS;           // [64][CT + 4]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
-    const TileCoord tc = tile_coord(g, blockIdx.y);
-    const int c0 = blockIdx.x * CT;
+    int bx;
+    int64_t by;
+    if (!xcd_tile((int64_t)nx * ny, nx, &bx, &by)) return;       // uniform
+    const TileCoord tc = tile_coord(g, by);
+    const int c0 = bx * CT;
     const int N = g.N, d = bp.dim;
     const float* En = tc.side == 0 ? bp.E_dst : bp.E_src;
     const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
     const float* Wtile = W + (int64_t)tc.wgrow * g.rows_tile * Npad;
-    const int rblocks = (tc.nrows + 15) >> 4;
 
     WTileRegs<THREADS> wr;
     SliceRegs<THREADS, kGNeg, CT> nr;
     auto neg_row = [&](int n0) {
         return [=](int row) -> const float* { return n0 + row < N ? En + (int64_t)my_negs[n0 + row] * d : nullptr; };
     };
-    wr.fetch(Wtile, Npad, tc.nrows, 0, tid);
+    wr.fetch(Wtile, g.rows_tile, tc.nrows, 0, tid);
     nr.fetch(neg_row(0), c0, d, tid);
 
-    f32x4 acc[kGRowBlocks];
+    f32x4 acc[RB];
 #pragma unroll
-    for (int r = 0; r < kGRowBlocks; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < RB; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int n0 = 0; n0 < N; n0 += kGNeg) {
         wr.store(Wt, tid);
         nr.store(Nt, tid);
         __syncthreads();
         if (n0 + kGNeg < N) {
-            wr.fetch(Wtile, Npad, tc.nrows, n0 + kGNeg, tid);
+            wr.fetch(Wtile, g.rows_tile, tc.nrows, n0 + kGNeg, tid);
             nr.fetch(neg_row(n0 + kGNeg), c0, d, tid);
         }
         const int groups = c0 + 16 * w < d ? (min(kGNeg, N - n0) + 15) >> 4 : 0;    // nothing for a column block past d
@@ -341,16 +367,17 @@ k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, con
             float b[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) b[s] = nb[(16 * G + s) * CS];
+            float4 a[RB];
 #pragma unroll
-            for (int r = 0; r < kGRowBlocks; ++r) {
-                if (r < rblocks) {
-                    const float4 a = lds4(wa + 16 * r * kGWS + 16 * G);
-                    acc[r] = mfma16g(a.x, b[0], acc[r]);
-                    acc[r] = mfma16g(a.y, b[1], acc[r]);
-                    acc[r] = mfma16g(a.z, b[2], acc[r]);
-                    acc[r] = mfma16g(a.w, b[3], acc[r]);
-                }
-            }
+            for (int r = 0; r < RB; ++r) a[r] = lds4(wa + 16 * r * kGWS + 16 * G);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].x, b[0], acc[r]);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].y, b[1], acc[r]);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].z, b[2], acc[r]);
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = mfma16g(a[r].w, b[3], acc[r]);
         }
         __syncthreads();
     }
@@ -358,7 +385,7 @@ k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, con
     if (col < d) {
         float* out = GQ + ((int64_t)tc.si * g.P + tc.e0) * d + col;
 #pragma unroll
-        for (int r = 0; r < kGRowBlocks; ++r) {
+        for (int r = 0; r < RB; ++r) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = 16 * r + 4 * gq + v;
@@ -375,14 +402,17 @@ k_gemm_gq(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, con
 template <int CT>
 __global__ void __launch_bounds__(CT * 4)
 k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, const float* __restrict__ W, int Npad,
-            const float* __restrict__ Q, float* __restrict__ grad) {
+            const float* __restrict__ Q, float* __restrict__ grad, int nx, int64_t ny) {
     extern __shared__ __align__(16) float gneg_smem[];
     constexpr int THREADS = CT * 4, CS = CT + 4;
     float* Wt = gneg_smem;                    // [112][68]
     float* Qs = Wt + kGRows * kGWS;           // [112][CT + 4]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l15 = lane & 15, gq = lane >> 4;
-    const TileCoord tc = tile_coord(g, blockIdx.y);
-    const int c0 = blockIdx.x * CT;
+    int bx;
+    int64_t by;
+    if (!xcd_tile((int64_t)nx * ny, nx, &bx, &by)) return;       // uniform
+    const TileCoord tc = tile_coord(g, by);
+    const int c0 = bx * CT;
     const int N = g.N, d = bp.dim;
     const int32_t* my_negs = neg_ids + ((int64_t)tc.si * g.nchunks + tc.c) * N;
     const float* Wtile = W + (int64_t)tc.wgrow * g.rows_tile * Npad;
@@ -393,7 +423,7 @@ k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, c
     const int64_t neg_base = (int64_t)tc.si * g.per_side + (int64_t)g.roles * g.P + ((int64_t)tc.c * g.T + tc.t_row) * N;
 
     WTileRegs<THREADS> wr;
-    wr.fetch(Wtile, Npad, tc.nrows, 0, tid);
+    wr.fetch(Wtile, g.rows_tile, tc.nrows, 0, tid);
     {
         SliceRegs<THREADS, kGRows, CT> qr;
         const int nrows = tc.nrows;
@@ -406,20 +436,24 @@ k_gemm_gneg(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, c
         __syncthreads();                      // the previous tile's W has been consumed
         wr.store(Wt, tid);
         __syncthreads();
-        if (n0 + kGNeg < N) wr.fetch(Wtile, Npad, tc.nrows, n0 + kGNeg, tid);
+        if (n0 + kGNeg < N) wr.fetch(Wtile, g.rows_tile, tc.nrows, n0 + kGNeg, tid);
         f32x4 acc[4];
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) acc[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
         const float* wa = Wt + (4 * gq) * kGWS + l15;
         const float* qb = Qs + (4 * gq) * CS + 16 * w + l15;
-        for (int G = 0; G < (col0_live ? kgroups : 0); ++G) {
+        for (int G = 0; G < (col0_live ? kgroups : 0); ++G) {    // all operand reads of a group first, then its MFMAs
+            float b[4], a[4][4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const float b = qb[(16 * G + s) * CS];
-                const float* arow = wa + (16 * G + s) * kGWS;
+                b[s] = qb[(16 * G + s) * CS];
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma16g(arow[16 * mb], b, acc[mb]);
+                for (int mb = 0; mb < 4; ++mb) a[s][mb] = wa[(16 * G + s) * kGWS + 16 * mb];
             }
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) acc[mb] = mfma16g(a[s][mb], b[s], acc[mb]);
         }
         if (col < d) {
 #pragma unroll
@@ -516,9 +550,6 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<kGNegColTile>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gq<kGColTile>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)gq_lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -533,18 +564,42 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
             hipLaunchKernelGGL(k_gemm_compose<LEGEND_SCORE_COMPLEX>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_f);
             break;
     }
-    hipLaunchKernelGGL(k_gemm_scores, dim3((unsigned)ntiles, (unsigned)tiles), dim3(256), 0, st, g, bp, ws.neg_ids, ws.gemm_Q,
-                       ws.gemm_S, Npad);
+    const int rb = (g.rows_tile + 15) / 16;
+#define LEGEND_GEMM_RB(RB)                                                                                             \
+    case RB:                                                                                                           \
+        hipLaunchKernelGGL(k_gemm_scores<RB>, dim3((unsigned)xcd_grid(ntiles * tiles)), dim3(256), 0, st, g, bp, ws.neg_ids, \
+                           ws.gemm_Q, ws.gemm_S, Npad, ntiles, tiles);                                                 \
+        break;
+    switch (rb) {
+        LEGEND_GEMM_RB(1) LEGEND_GEMM_RB(2) LEGEND_GEMM_RB(3) LEGEND_GEMM_RB(4) LEGEND_GEMM_RB(5) LEGEND_GEMM_RB(6)
+        default: hipLaunchKernelGGL(k_gemm_scores<7>, dim3((unsigned)xcd_grid(ntiles * tiles)), dim3(256), 0, st, g, bp,
+                                    ws.neg_ids, ws.gemm_Q, ws.gemm_S, Npad, ntiles, tiles);
+    }
+#undef LEGEND_GEMM_RB
     if (softmax)
         hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
                            ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
     else
         hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
                            ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
-    hipLaunchKernelGGL(k_gemm_gq<kGColTile>, dim3((unsigned)coltiles, (unsigned)tiles), dim3(kGColTile * 4), gq_lds, st, g, bp, ws.neg_ids, ws.gemm_S, Npad,
-                       ws.gemm_G);
-    hipLaunchKernelGGL(k_gemm_gneg<kGNegColTile>, dim3((unsigned)negtiles, (unsigned)tiles), dim3(kGNegColTile * 4), gneg_lds, st, g, bp, ws.neg_ids,
-                       ws.gemm_S, Npad, ws.gemm_Q, ws.grad);
+#define LEGEND_GEMM_RB(RB)                                                                                             \
+    case RB:                                                                                                           \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gq<kGColTile, RB>),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)gq_lds);                              \
+        if (e != hipSuccess) return e;                                                                                 \
+        hipLaunchKernelGGL((k_gemm_gq<kGColTile, RB>), dim3((unsigned)xcd_grid(coltiles * tiles)), dim3(kGColTile * 4), gq_lds, \
+                           st, g, bp, ws.neg_ids, ws.gemm_S, Npad, ws.gemm_G, coltiles, tiles);                        \
+        break;
+    {
+        hipError_t e = hipSuccess;
+        switch (rb < 7 ? rb : 7) {
+            LEGEND_GEMM_RB(1) LEGEND_GEMM_RB(2) LEGEND_GEMM_RB(3) LEGEND_GEMM_RB(4) LEGEND_GEMM_RB(5) LEGEND_GEMM_RB(6)
+            LEGEND_GEMM_RB(7)
+        }
+    }
+#undef LEGEND_GEMM_RB
+    hipLaunchKernelGGL(k_gemm_gneg<kGNegColTile>, dim3((unsigned)xcd_grid(negtiles * tiles)), dim3(kGNegColTile * 4), gneg_lds, st, g,
+                       bp, ws.neg_ids, ws.gemm_S, Npad, ws.gemm_Q, ws.grad, negtiles, tiles);
     switch (bp.score) {
         case LEGEND_SCORE_DOT:
             hipLaunchKernelGGL(k_gemm_chain<LEGEND_SCORE_DOT>, dim3((unsigned)rows), dim3(128), 0, st, g, bp, ws.gemm_Q, ws.gemm_G, ws.gemm_a, ws.grad);
