@@ -56,6 +56,12 @@ struct legend_ctx {
     std::vector<int> slot_part, part_slot;
     std::vector<hipEvent_t> slot_ready;
     std::vector<char> slot_pending;
+    // With fewer logical slots than partitions there is one physical slot more: a partition is loaded
+    // into the free slot while the evicted one is still being written back (both PCIe directions at once).
+    int nslots = 0;                         // physical slots: cap, or cap + 1
+    hipStream_t copy_out = nullptr;         // device-to-host write-backs
+    std::vector<hipEvent_t> slot_drained;   // write-back of the slot's previous tenant complete
+    std::vector<char> slot_draining;
     float* E_rel = nullptr;
     float* S_rel = nullptr;
     float** d_part_emb = nullptr;           // device: embedding base per partition or null
@@ -209,23 +215,41 @@ int do_swap(legend_ctx* c, int evict, int load, bool fence_now) {
     if (evict < 0 && load < 0) return LEGEND_OK;
     if (evict >= 0 && c->part_slot[evict] < 0) return fail(LEGEND_E_NOT_RESIDENT, "partition %d is not resident", evict);
     if (load >= 0 && c->part_slot[load] >= 0) return fail(LEGEND_E_STATE, "partition %d is already resident", load);
-    int slot = -1;
-    if (evict >= 0) slot = c->part_slot[evict];
-    else
-        for (int s = 0; s < c->cap; ++s)
-            if (c->slot_part[s] < 0) { slot = s; break; }
-    if (slot < 0) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
     const size_t bytes = c->part_floats * sizeof(float);
+    if (load >= 0 && evict < 0) {
+        int resident = 0;
+        for (int p = 0; p < c->n; ++p) resident += c->part_slot[p] >= 0;
+        if (resident >= c->cap) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
+    }
     if (fence_now) {
         HIP_TRY(c, hipEventRecord(c->ev_fence, c->compute));
     }
-    HIP_TRY(c, hipStreamWaitEvent(c->copy, c->ev_fence, 0));
+    int out_slot = -1;
     if (evict >= 0) {
-        HIP_TRY(c, hipMemcpyAsync(c->host_part[evict], c->slot_mem[slot], bytes, hipMemcpyDeviceToHost, c->copy));
+        // write-back: after the compute work enqueued so far (it may still use the partition)
+        out_slot = c->part_slot[evict];
+        HIP_TRY(c, hipStreamWaitEvent(c->copy_out, c->ev_fence, 0));
+        if (c->slot_pending[out_slot]) HIP_TRY(c, hipStreamWaitEvent(c->copy_out, c->slot_ready[out_slot], 0));
+        HIP_TRY(c, hipMemcpyAsync(c->host_part[evict], c->slot_mem[out_slot], bytes, hipMemcpyDeviceToHost, c->copy_out));
+        HIP_TRY(c, hipEventRecord(c->slot_drained[out_slot], c->copy_out));
+        c->slot_draining[out_slot] = 1;
         c->part_slot[evict] = -1;
-        c->slot_part[slot] = -1;
+        c->slot_part[out_slot] = -1;
     }
     if (load >= 0) {
+        // into a free slot other than the one being written back when there is one
+        int slot = -1;
+        for (int sl = 0; sl < c->nslots; ++sl)
+            if (c->slot_part[sl] < 0 && sl != out_slot) { slot = sl; break; }
+        if (slot < 0) slot = out_slot;
+        if (slot < 0) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
+        // the slot's previous tenant must be back on the host, and the compute work that used it done
+        if (c->slot_draining[slot]) {
+            HIP_TRY(c, hipStreamWaitEvent(c->copy, c->slot_drained[slot], 0));
+            c->slot_draining[slot] = 0;
+        } else {
+            HIP_TRY(c, hipStreamWaitEvent(c->copy, c->ev_fence, 0));
+        }
         HIP_TRY(c, hipMemcpyAsync(c->slot_mem[slot], c->host_part[load], bytes, hipMemcpyHostToDevice, c->copy));
         HIP_TRY(c, hipEventRecord(c->slot_ready[slot], c->copy));
         c->slot_pending[slot] = 1;
@@ -241,6 +265,8 @@ void free_ctx(legend_ctx* c) {
     (void)hipSetDevice(c->cfg.device);
     if (c->compute) (void)hipStreamSynchronize(c->compute);
     if (c->copy) (void)hipStreamSynchronize(c->copy);
+    if (c->copy_out) { (void)hipStreamSynchronize(c->copy_out); (void)hipStreamDestroy(c->copy_out); }
+    for (hipEvent_t e : c->slot_drained) if (e) (void)hipEventDestroy(e);
     for (float* p : c->host_part) if (p) (void)hipHostFree(p);
     for (float* p : c->slot_mem) if (p) (void)hipFree(p);
     for (float* p : c->slot_grad) if (p) (void)hipFree(p);
@@ -436,12 +462,15 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     }
     c->nrel_rows = std::max(cfg->num_relations, 1);
     c->host_part.assign(c->n, nullptr);
-    c->slot_mem.assign(c->cap, nullptr);
-    c->slot_grad.assign(c->cap, nullptr);
-    c->slot_part.assign(c->cap, -1);
+    c->nslots = c->cap < c->n ? c->cap + 1 : c->cap;
+    c->slot_mem.assign(c->nslots, nullptr);
+    c->slot_grad.assign(c->nslots, nullptr);
+    c->slot_part.assign(c->nslots, -1);
     c->part_slot.assign(c->n, -1);
-    c->slot_ready.assign(c->cap, nullptr);
-    c->slot_pending.assign(c->cap, 0);
+    c->slot_ready.assign(c->nslots, nullptr);
+    c->slot_pending.assign(c->nslots, 0);
+    c->slot_drained.assign(c->nslots, nullptr);
+    c->slot_draining.assign(c->nslots, 0);
 
 #define INIT_TRY(expr)                                                                                   \
     do {                                                                                                 \
@@ -490,9 +519,11 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         std::memset(c->host_part[p] + (size_t)rows * c->d, 0, (c->part_floats - (size_t)rows * c->d) * sizeof(float));
         (void)half;
     }
-    for (int s = 0; s < c->cap; ++s) {
+    INIT_TRY(hipStreamCreateWithFlags(&c->copy_out, hipStreamNonBlocking));
+    for (int s = 0; s < c->nslots; ++s) {
         INIT_RC(dev_alloc(c, &c->slot_mem[s], c->part_floats));
         INIT_TRY(hipEventCreateWithFlags(&c->slot_ready[s], hipEventDisableTiming));
+        INIT_TRY(hipEventCreateWithFlags(&c->slot_drained[s], hipEventDisableTiming));
         if (cfg->update_mode == LEGEND_UPDATE_ATOMIC) {
             INIT_RC(dev_alloc(c, &c->slot_grad[s], (size_t)Rp * c->d));
             INIT_TRY(hipMemset(c->slot_grad[s], 0, (size_t)Rp * c->d * sizeof(float)));
@@ -604,6 +635,7 @@ int legend_sync(legend_ctx* c) {
     if (rc) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->copy_out));
     return LEGEND_OK;
 }
 
@@ -820,6 +852,7 @@ int legend_train_epoch(legend_ctx* c, const int32_t* const* bucket_edges, const 
     HIP_TRY(c, hipMemcpyAsync(&loss, c->ws.loss_sum, sizeof loss, hipMemcpyDeviceToHost, c->compute));
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->copy_out));
     if (stats) {
         stats->loss_sum = loss;
         stats->edges = edges;
@@ -889,7 +922,7 @@ int legend_score_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, co
     if (m == 0) return LEGEND_OK;
     if (!src || !dst || !out) return fail(LEGEND_E_INVAL, "NULL argument");
     if (c->uses_rel && !rel) return fail(LEGEND_E_INVAL, "rel must not be NULL for this score");
-    for (int s = 0; s < c->cap; ++s) {
+    for (int s = 0; s < c->nslots; ++s) {
         rc = wait_slot(c, s);
         if (rc) return rc;
     }
@@ -933,7 +966,8 @@ int legend_read_embeddings(legend_ctx* c, int32_t table, const int64_t* ids, int
     if (!out) return fail(LEGEND_E_INVAL, "out must not be NULL");
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
-    for (int s = 0; s < c->cap; ++s) c->slot_pending[s] = 0;
+    HIP_TRY(c, hipStreamSynchronize(c->copy_out));
+    for (int s = 0; s < c->nslots; ++s) { c->slot_pending[s] = 0; c->slot_draining[s] = 0; }
     if (c->part_tables_dirty) {
         rc = upload_part_tables(c);
         if (rc) return rc;
