@@ -113,7 +113,9 @@ typedef struct legend_bucket_stats {
  *                  only for LEGEND_SCORE_DOT, which ignores relations).
  *   out            receives the context.
  * Optimiser state starts at zero.  Allocates n pinned host blocks of
- * 2*R_p*dim floats, buffer_capacity device slots of the same size, the relation
+ * 2*R_p*dim floats, buffer_capacity device slots of the same size (one more when
+ * buffer_capacity < num_partitions: the slot a partition is loaded into while the
+ * one it replaces is still being written back), the relation
  * table and its state on the device, and the per-batch workspace.  No partition
  * is resident after the call.
  */
