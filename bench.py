@@ -44,18 +44,22 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
     ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
     K, W = max(args.steps, 1), args.warmup
     stats = None
+    pinned = {}
     if not args.pageable_edges:
         # the caller's edge arrays in pinned host memory: each bucket's copy to the device then runs at
         # PCIe speed (it still crosses PCIe inside the timed region)
         t_pin = time.time()
-        pinned = {}
-        for key in list(buckets.keys()):
-            e = buckets[key]
-            t = torch.empty(e.shape, dtype=torch.int32, pin_memory=True)
-            t.numpy()[...] = e
-            pinned[key] = t
-            buckets[key] = t.numpy()
-        log(f"[bench] bucket edges copied into pinned host memory in {time.time() - t_pin:.1f}s")
+        try:
+            for key in list(buckets.keys()):
+                e = buckets[key]
+                t = torch.empty(e.shape, dtype=torch.int32, pin_memory=True)
+                t.numpy()[...] = e
+                pinned[key] = t
+                buckets[key] = t.numpy()
+            log(f"[bench] bucket edges copied into pinned host memory in {time.time() - t_pin:.1f}s")
+        except RuntimeError as err:             # the box limits pinned memory: the rest stays pageable
+            log(f"[bench] pinned {len(pinned)} of {len(buckets)} bucket edge arrays, the rest stays pageable ({str(err).splitlines()[0]})")
+            args.pageable_edges = len(pinned) == 0
     for ep in range(W):
         L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=not args.no_overlap)
     torch.cuda.synchronize()
@@ -87,7 +91,8 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
         "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
                                f"{n} partitions, B={w.batch_size}, C={w.chunk_size}, N={w.num_negs}, sides={w.sides}, "
                                f"score={['dot', 'distmult', 'complex'][w.score]}; one step = one epoch, edges in "
-                               f"{'pageable' if args.pageable_edges else 'pinned'} host memory",
+                               f"{'pageable' if args.pageable_edges else 'pinned'} host memory"
+                               + ("" if args.pageable_edges or len(pinned) == len(buckets) else f" ({len(pinned)} of {len(buckets)} arrays)"),
                    "update_mode": args.update_mode, "resident_partitions": capacity,
                    "prefetch": not args.no_overlap},
         "fallback_chunks": L.legend_fallback_chunks_read(ctx),
