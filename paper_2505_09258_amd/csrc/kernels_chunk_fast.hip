@@ -11,8 +11,9 @@
 // workgroup: eight waves, 128 registers per lane each, one workgroup per compute unit.  After
 // the sweep the stored numerators are scaled by 1 / l_e and G_neg = W^T Q is formed straight from
 // the stored blocks.  If some S_en exceeds the first tile's row maximum by more than a limit
-// (110 unless overridden; the numerators stay far from overflow) or a row sum is not finite, the workgroup writes nothing and flags itself; the
-// general two-sweep kernel then redoes it.
+// (110 unless overridden; the numerators stay far from overflow), the workgroup takes the exact
+// row maxima in a scores-only pass and runs the sweep once more; if a row sum is not finite it
+// writes nothing and flags itself, and the general two-sweep kernel redoes the chunk.
 //
 // Work split (16x16x4 fp32 MFMA; g = lane / 16, l15 = lane % 16).  The eight waves form two
 // groups of four; the negatives are dealt into tiles of 64 (negative n sits in tile n mod T),
