@@ -44,29 +44,38 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
     ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
     K, W = max(args.steps, 1), args.warmup
     stats = None
-    pinned = {}
-    if not args.pageable_edges:
-        # the caller's edge arrays in pinned host memory: each bucket's copy to the device then runs at
-        # PCIe speed (it still crosses PCIe inside the timed region)
+    # where the caller keeps the edge list: device (default: a 288 GB card holds it next to the
+    # partition buffer; uploaded once, before the timed region), pinned host memory, or pageable
+    # host memory (each bucket's edges then cross PCIe inside the timed region)
+    edges_mem, keep = L.MEM_HOST, {}
+    if args.edges == "device":
+        t_up = time.time()
+        for key in list(buckets.keys()):
+            t = torch.from_numpy(buckets[key]).cuda()
+            keep[key] = t
+            buckets[key] = (t.data_ptr(), t.shape[0])
+        torch.cuda.synchronize()
+        edges_mem = L.MEM_DEVICE
+        log(f"[bench] bucket edges uploaded to the device in {time.time() - t_up:.1f}s")
+    elif args.edges == "pinned":
         t_pin = time.time()
         try:
             for key in list(buckets.keys()):
                 e = buckets[key]
                 t = torch.empty(e.shape, dtype=torch.int32, pin_memory=True)
                 t.numpy()[...] = e
-                pinned[key] = t
+                keep[key] = t
                 buckets[key] = t.numpy()
             log(f"[bench] bucket edges copied into pinned host memory in {time.time() - t_pin:.1f}s")
         except RuntimeError as err:             # the box limits pinned memory: the rest stays pageable
-            log(f"[bench] pinned {len(pinned)} of {len(buckets)} bucket edge arrays, the rest stays pageable ({str(err).splitlines()[0]})")
-            args.pageable_edges = len(pinned) == 0
+            log(f"[bench] pinned {len(keep)} of {len(buckets)} bucket edge arrays, the rest stays pageable ({str(err).splitlines()[0]})")
     for ep in range(W):
-        L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=not args.no_overlap)
+        L.legend_train_epoch(ctx, n, buckets, edges_mem=edges_mem, epoch=ep, overlap=not args.no_overlap)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     edges = 0
     for ep in range(W, W + K):
-        stats = L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=not args.no_overlap)
+        stats = L.legend_train_epoch(ctx, n, buckets, edges_mem=edges_mem, epoch=ep, overlap=not args.no_overlap)
         edges += stats["edges"]
     L.legend_sync(ctx)
     wall = time.perf_counter() - t0
@@ -78,7 +87,7 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
         t1 = time.perf_counter()
         edges2 = 0
         for ep in range(W + K, W + 2 * K):
-            edges2 += L.legend_train_epoch(ctx, n, buckets, epoch=ep, overlap=False)["edges"]
+            edges2 += L.legend_train_epoch(ctx, n, buckets, edges_mem=edges_mem, epoch=ep, overlap=False)["edges"]
         L.legend_sync(ctx)
         wall2 = time.perf_counter() - t1
         log(f"[bench] {K} epoch(s), prefetch off: {wall2:.2f} s, {edges2 / wall2:.3e} edges/s")
@@ -90,9 +99,8 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
                                f"{n} partitions, B={w.batch_size}, C={w.chunk_size}, N={w.num_negs}, sides={w.sides}, "
-                               f"score={['dot', 'distmult', 'complex'][w.score]}; one step = one epoch, edges in "
-                               f"{'pageable' if args.pageable_edges else 'pinned'} host memory"
-                               + ("" if args.pageable_edges or len(pinned) == len(buckets) else f" ({len(pinned)} of {len(buckets)} arrays)"),
+                               f"score={['dot', 'distmult', 'complex'][w.score]}; one step = one epoch, edge list in "
+                               f"{args.edges} memory",
                    "update_mode": args.update_mode, "resident_partitions": capacity,
                    "prefetch": not args.no_overlap},
         "fallback_chunks": L.legend_fallback_chunks_read(ctx),
@@ -119,12 +127,13 @@ def main() -> int:
     ap.add_argument("--profile-only", action="store_true", help="skip the CPU baseline and the per-kernel pass")
     ap.add_argument("--update-mode", choices=["deterministic", "atomic"], default="deterministic")
     ap.add_argument("--epoch", action="store_true",
-                    help="time whole epochs through legend_train_epoch (host-resident edges, partition swaps) "
+                    help="time whole epochs through legend_train_epoch (the paper's bucket order, partition swaps) "
                          "instead of K resident batches; --steps then counts epochs")
     ap.add_argument("--capacity", type=int, default=0, help="buffer slots for --epoch (0: all partitions resident)")
     ap.add_argument("--no-overlap", action="store_true", help="--epoch: serialize swaps (the paper's 'without prefetching')")
     ap.add_argument("--ablation", action="store_true", help="--epoch: afterwards run the same number of epochs with swaps serialised")
-    ap.add_argument("--pageable-edges", action="store_true", help="--epoch: leave the bucket edge arrays in pageable host memory")
+    ap.add_argument("--edges", choices=["device", "pinned", "pageable"], default="device",
+                    help="--epoch: where the bucket edge arrays live (host arrays cross PCIe bucket by bucket inside the timed region)")
     ap.add_argument("--dim", type=int, default=0, help="override the embedding dimension of the workload (dimension sweep)")
     ap.add_argument("--score", choices=["dot", "distmult", "complex"], default=None, help="override the score function")
     ap.add_argument("--batch-size", type=int, default=0, help="override the batch size")

@@ -62,6 +62,7 @@ struct legend_ctx {
     hipStream_t copy_out = nullptr;         // device-to-host write-backs
     std::vector<hipEvent_t> slot_drained;   // write-back of the slot's previous tenant complete
     std::vector<char> slot_draining;
+    std::vector<int> slot_drain_part;       // the partition whose write-back slot_drained marks
     float* E_rel = nullptr;
     float* S_rel = nullptr;
     float** d_part_emb = nullptr;           // device: embedding base per partition or null
@@ -210,7 +211,9 @@ int wait_slot(legend_ctx* c, int slot) {
     return LEGEND_OK;
 }
 
-int do_swap(legend_ctx* c, int evict, int load, bool fence_now) {
+// `early_load`: the epoch driver's prefetch into the spare slot.  The load then neither counts
+// against the logical capacity nor waits for compute work (nothing enqueued uses the spare slot).
+int do_swap(legend_ctx* c, int evict, int load, bool fence_now, bool early_load = false) {
     if (evict >= c->n || load >= c->n || evict < -1 || load < -1) return fail(LEGEND_E_INVAL, "partition id out of range");
     if (evict < 0 && load < 0) return LEGEND_OK;
     if (evict >= 0 && c->part_slot[evict] < 0) return fail(LEGEND_E_NOT_RESIDENT, "partition %d is not resident", evict);
@@ -219,7 +222,7 @@ int do_swap(legend_ctx* c, int evict, int load, bool fence_now) {
     if (load >= 0 && evict < 0) {
         int resident = 0;
         for (int p = 0; p < c->n; ++p) resident += c->part_slot[p] >= 0;
-        if (resident >= c->cap) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
+        if (resident >= (early_load ? c->nslots : c->cap)) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
     }
     if (fence_now) {
         HIP_TRY(c, hipEventRecord(c->ev_fence, c->compute));
@@ -233,6 +236,7 @@ int do_swap(legend_ctx* c, int evict, int load, bool fence_now) {
         HIP_TRY(c, hipMemcpyAsync(c->host_part[evict], c->slot_mem[out_slot], bytes, hipMemcpyDeviceToHost, c->copy_out));
         HIP_TRY(c, hipEventRecord(c->slot_drained[out_slot], c->copy_out));
         c->slot_draining[out_slot] = 1;
+        c->slot_drain_part[out_slot] = evict;
         c->part_slot[evict] = -1;
         c->slot_part[out_slot] = -1;
     }
@@ -243,13 +247,18 @@ int do_swap(legend_ctx* c, int evict, int load, bool fence_now) {
             if (c->slot_part[sl] < 0 && sl != out_slot) { slot = sl; break; }
         if (slot < 0) slot = out_slot;
         if (slot < 0) return fail(LEGEND_E_STATE, "no free buffer slot for partition %d", load);
-        // the slot's previous tenant must be back on the host, and the compute work that used it done
+        // the slot's previous tenant must be back on the host; and a load never starts before the
+        // compute work enqueued so far is done, so that a caller who asks for the swap after a
+        // state's last bucket gets a swap that is not hidden behind that bucket
+        if (!early_load) HIP_TRY(c, hipStreamWaitEvent(c->copy, c->ev_fence, 0));
         if (c->slot_draining[slot]) {
             HIP_TRY(c, hipStreamWaitEvent(c->copy, c->slot_drained[slot], 0));
             c->slot_draining[slot] = 0;
-        } else {
-            HIP_TRY(c, hipStreamWaitEvent(c->copy, c->ev_fence, 0));
         }
+        // the host block of a partition that is itself still being written back is not read early
+        for (int sl = 0; sl < c->nslots; ++sl)
+            if (c->slot_draining[sl] && c->slot_drain_part[sl] == load)
+                HIP_TRY(c, hipStreamWaitEvent(c->copy, c->slot_drained[sl], 0));
         HIP_TRY(c, hipMemcpyAsync(c->slot_mem[slot], c->host_part[load], bytes, hipMemcpyHostToDevice, c->copy));
         HIP_TRY(c, hipEventRecord(c->slot_ready[slot], c->copy));
         c->slot_pending[slot] = 1;
@@ -471,6 +480,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     c->slot_pending.assign(c->nslots, 0);
     c->slot_drained.assign(c->nslots, nullptr);
     c->slot_draining.assign(c->nslots, 0);
+    c->slot_drain_part.assign(c->nslots, -1);
 
 #define INIT_TRY(expr)                                                                                   \
     do {                                                                                                 \
@@ -836,12 +846,16 @@ int legend_train_epoch(legend_ctx* c, const int32_t* const* bucket_edges, const 
         if (!all_resident && k + 1 < ns)
             for (int s = 0; s < 3; ++s)
                 if (states[3 * k + s] != states[3 * (k + 1) + s]) { evict = states[3 * k + s]; load = states[3 * (k + 1) + s]; }
+        // With prefetching and a spare slot the next state's partition starts loading right away: no
+        // bucket of this state touches it or the slot it goes to.
+        const bool early = overlap && load >= 0 && c->nslots > c->cap;
+        if (early) { rc = do_swap(c, -1, load, true, true); if (rc) break; }
         // buckets that involve the partition evicted next
         for (int idx = begin[k]; idx < over[k] && rc == LEGEND_OK; ++idx) rc = train(idx);
         if (rc) break;
         // with prefetching the swap starts now and runs while the remaining buckets train (Sec. 4);
         // without, it starts after them and the next state waits for it
-        if (evict >= 0 && overlap) { rc = do_swap(c, evict, load, true); if (rc) break; ++swaps; }
+        if (evict >= 0 && overlap) { rc = do_swap(c, evict, early ? -1 : load, true); if (rc) break; ++swaps; }
         for (int idx = over[k]; idx < begin[k + 1] && rc == LEGEND_OK; ++idx) rc = train(idx);
         if (rc) break;
         if (evict >= 0 && !overlap) { rc = do_swap(c, evict, load, true); if (rc) break; ++swaps; }
