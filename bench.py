@@ -32,7 +32,7 @@ def log(*a):
 
 
 def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
-    """Whole epochs with edges in host memory and partitions staged through the HBM buffer."""
+    """Whole epochs in the paper's bucket order, partitions staged through the HBM buffer."""
     n = w.num_partitions
     capacity = args.capacity if args.capacity else n
     uses_rel = w.score != graphs.SCORE_DOT

@@ -283,9 +283,10 @@ int legend_batch_shape_of(legend_ctx* ctx, legend_batch_shape* out);
 /* Unique rows updated by the batches since the last call (sum), then cleared. */
 int legend_unique_rows_read(legend_ctx* ctx, int64_t* unique_rows, int64_t* batches);
 
-/* Chunk workgroups that the single-sweep batch kernel handed over to the two-sweep
- * kernel (scores too far above the softmax reference) since the last call, then
- * cleared.  A tuning aid: 0 in ordinary training. */
+/* Workgroups (one row tile of one chunk) of the single-sweep batch kernel that
+ * needed a second pass (scores too far above the softmax reference: repeated in
+ * place with the exact row maxima, or handed over to the two-sweep kernel) since
+ * the last call, then cleared.  A tuning aid: 0 early in training. */
 int legend_fallback_chunks_read(legend_ctx* ctx, int64_t* chunks);
 
 /* Message of the last error on this thread ("" if none). */
