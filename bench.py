@@ -114,6 +114,83 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
     return 0
 
 
+def run_rank(args, w, L, graphs, torch, np) -> int:
+    """Ranking throughput (Sec. 7 "Metrics"): K calls of legend_rank_edges per corrupted side over a fixed
+    set of synthetic test triples, every partition resident."""
+    n = w.num_partitions
+    node, rel = graphs.init_tables(w, args.seed)
+    node *= 300.0
+    rel = rel * 300.0 + np.float32(0.5)
+    uses_rel = w.score != graphs.SCORE_DOT
+    cfg = L.make_config(num_nodes=w.num_nodes, dim=w.dim, num_partitions=n, buffer_capacity=n,
+                        num_relations=w.num_relations, score=w.score, loss=w.loss, corrupt=w.corrupt,
+                        batch_size=w.batch_size, chunk_size=w.chunk_size, num_negs=w.num_negs,
+                        num_degree_negs=w.num_degree_negs, seed=args.seed)
+    ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
+    for p in range(n):
+        L.legend_swap_partition(ctx, -1, p)
+    L.legend_sync(ctx)
+    rng = np.random.default_rng(args.seed)
+    m = args.rank_triples
+    src = rng.integers(0, w.num_nodes, m)
+    dst = rng.integers(0, w.num_nodes, m)
+    r = rng.integers(0, max(w.num_relations, 1), m).astype(np.int32) if uses_rel else None
+    cand = None if args.rank_candidates == 0 else rng.integers(0, w.num_nodes, args.rank_candidates)
+    n_cand = w.num_nodes if cand is None else len(cand)
+    sides = [L.CORRUPT_DST, L.CORRUPT_SRC] if w.corrupt == graphs.CORRUPT_BOTH else [L.CORRUPT_DST]
+    K, W = args.steps, args.warmup
+    for _ in range(W):
+        for side in sides:
+            L.legend_rank_edges(ctx, src, r, dst, side, cand)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    dev_ms = 0.0
+    for _ in range(K):
+        for side in sides:
+            g, q, mt = L.legend_rank_edges(ctx, src, r, dst, side, cand)
+            dev_ms += mt["ms"]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    flops = 2.0 * m * n_cand * w.dim
+    launch_ms = dev_ms / (K * len(sides))
+    log(f"[bench] rank: {K} steps, wall {wall * 1e3:.1f} ms, device {dev_ms:.1f} ms, MRR {mt['mrr']:.4f}")
+    out = {
+        "metric": "test triples ranked/sec (1 GPU)", "value": round(m * K / wall, 1), "unit": "triples/s", "n_gpus": 1,
+        "steps": K, "warmup": W, "ms_per_step": round(wall * 1e3 / K, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name} ({w.stands_for}) ranking: {m} test triples against {n_cand} candidates "
+                               f"({'every node' if cand is None else 'a shared uniform sample'}), {len(sides)} side(s) per step, "
+                               f"d={w.dim}, score={['dot', 'distmult', 'complex'][w.score]}; ids cross PCIe in, counts out, "
+                               f"inside the timed region"},
+        "candidate_scores_per_s": round(m * n_cand * len(sides) * K / wall, 1),
+        "roofline": {"kernel": "k_rank (gather + scores + compare-and-count, fp32 MFMA)", "bound": "mfma",
+                     "achieved": round(flops / (launch_ms * 1e-3) / 1e12, 3), "peak": 157.3, "unit": "TFLOP/s",
+                     "frac": round(flops / (launch_ms * 1e-3) / 1e12 / 157.3, 4), "traffic": None,
+                     "flops_per_launch": int(flops), "avg_launch_ms": round(launch_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import rank as orank
+        t1 = time.perf_counter()
+        done = 0
+        while done < min(m, 4) or (time.perf_counter() - t1 < 10 and done < m):
+            e = slice(done, done + 1)
+            orank.rank_counts(w.score, node, rel if uses_rel else None, src[e], None if r is None else r[e], dst[e],
+                              orank.SIDE_DST, cand)
+            done += 1
+        cpu_s = time.perf_counter() - t1
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        out["cpu_baseline"] = {"value": round(done / cpu_s / len(sides), 1), "unit": "triples/s", "cores": cores,
+                               "kind": "oracle", "sample": f"{done} of the same triples against the same candidates, one side "
+                               f"timed and scaled to {len(sides)}, numpy float64, {cpu_s:.1f} s"}
+    L.legend_destroy(ctx)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +211,11 @@ def main() -> int:
     ap.add_argument("--ablation", action="store_true", help="--epoch: afterwards run the same number of epochs with swaps serialised")
     ap.add_argument("--edges", choices=["device", "pinned", "pageable"], default="device",
                     help="--epoch: where the bucket edge arrays live (host arrays cross PCIe bucket by bucket inside the timed region)")
+    ap.add_argument("--rank", action="store_true",
+                    help="time legend_rank_edges (ranks for MRR / Hits@k) instead of training; a step ranks "
+                         "--rank-triples triples on every corrupted side of the workload")
+    ap.add_argument("--rank-triples", type=int, default=10_000)
+    ap.add_argument("--rank-candidates", type=int, default=0, help="--rank: size of the shared candidate sample (0: every node)")
     ap.add_argument("--dim", type=int, default=0, help="override the embedding dimension of the workload (dimension sweep)")
     ap.add_argument("--score", choices=["dot", "distmult", "complex"], default=None, help="override the score function")
     ap.add_argument("--batch-size", type=int, default=0, help="override the batch size")
@@ -166,6 +248,10 @@ def main() -> int:
     if over:
         import dataclasses
         w = dataclasses.replace(w, name=w.name + "+" + ",".join(f"{k}={v}" for k, v in over.items()), **over)
+
+    if args.rank:
+        torch.cuda.set_device(0)
+        return run_rank(args, w, L, graphs, torch, np)
 
     t0 = time.time()
     last = [time.time()]

@@ -193,10 +193,12 @@ typedef struct legend_epoch_stats {
  *   bucket_edges  [n*n] pointers, bucket (i, j) at index i*n + j, each [size][3] int32
  *                 as in legend_train_bucket (all host or all device, edges_mem);
  *   bucket_sizes  [n*n] edge counts (0 allowed, pointer then ignored);
- *   overlap       1: each swap is enqueued as soon as the buckets of the state that
- *                 involve the evicted partition are trained and runs while the rest
- *                 of the state trains (prefetching, Sec. 4); 0: swaps run after the
- *                 state's last bucket (the paper's "without prefetching" ablation).
+ *   overlap       1: the write-back of the evicted partition is enqueued as soon as the
+ *                 buckets of the state that involve it are trained and runs while the
+ *                 rest of the state trains (prefetching, Sec. 4); the load of the next
+ *                 partition goes into the extra device slot and starts with the state;
+ *                 0: swaps run after the state's last bucket has finished (the paper's
+ *                 "without prefetching" ablation).
  * With buffer_capacity == num_partitions every partition is made resident and no
  * swap happens during the epoch; otherwise buffer_capacity must be 3 (the paper's
  * setting) and the planner's loading order is followed.  Partitions resident on
@@ -288,6 +290,33 @@ int legend_unique_rows_read(legend_ctx* ctx, int64_t* unique_rows, int64_t* batc
  * place with the exact row maxima, or handed over to the two-sweep kernel) since
  * the last call, then cleared.  A tuning aid: 0 early in training. */
 int legend_fallback_chunks_read(legend_ctx* ctx, int64_t* chunks);
+
+/*
+ * Link-prediction ranks of m triples (Sec. 7, "Metrics": MRR and Hits@k are functions
+ * of these ranks; the protocol itself is not printed, the textbook one is used).
+ * The `side` endpoint of every triple (LEGEND_CORRUPT_DST or LEGEND_CORRUPT_SRC) is
+ * replaced by each candidate node in turn and scored with f (Sec. 2.1):
+ *   greater[e] = number of candidates other than the true endpoint whose score is
+ *                strictly above the triple's own, equal[e] = those that tie with it
+ *                (fp32 comparisons of fp32 scores; no filtering of true edges);
+ *   rank = 1 + greater + equal / 2, MRR = mean 1/rank, Hits@k = mean [rank <= k].
+ *   src/rel/dst   as in legend_score_edges (global ids, host);
+ *   candidates    [num_candidates] global node ids (host), shared by all triples, a
+ *                 node listed twice counts twice; NULL: every node 0..num_nodes-1
+ *                 (num_candidates is then ignored);
+ *   greater/equal [m] int32 (host), either may be NULL;
+ *   metrics       may be NULL; ms = device time of the kernels.
+ * Every partition that a triple or a candidate refers to must be resident
+ * (LEGEND_E_NOT_RESIDENT); ids out of range give LEGEND_E_RANGE; num_nodes must be
+ * below 2^31.  Embeddings are not modified.  Returns when the results are final.
+ */
+typedef struct legend_rank_metrics {
+    double mrr, hits1, hits3, hits10;
+    float ms;
+} legend_rank_metrics;
+int legend_rank_edges(legend_ctx* ctx, const int64_t* src, const int32_t* rel, const int64_t* dst,
+                      int64_t m, int32_t side, const int64_t* candidates, int64_t num_candidates,
+                      int32_t* greater, int32_t* equal, legend_rank_metrics* metrics);
 
 /* Message of the last error on this thread ("" if none). */
 const char* legend_last_error(void);

@@ -28,7 +28,7 @@ TABLE_NODE_EMB, TABLE_NODE_STATE, TABLE_REL_EMB, TABLE_REL_STATE = 0, 1, 2, 3
 
 EXPORTS = [
     "legend_init_partitions", "legend_destroy", "legend_swap_partition", "legend_partition_slot",
-    "legend_train_bucket", "legend_train_bucket_range", "legend_train_epoch", "legend_score_edges", "legend_read_embeddings", "legend_debug_batch_indices",
+    "legend_train_bucket", "legend_train_bucket_range", "legend_train_epoch", "legend_score_edges", "legend_rank_edges", "legend_read_embeddings", "legend_debug_batch_indices",
     "legend_plan_order", "legend_sync", "legend_profile_enable", "legend_profile_read",
     "legend_profile_name", "legend_batch_shape_of", "legend_unique_rows_read", "legend_fallback_chunks_read",
     "legend_last_error",
@@ -49,6 +49,11 @@ class legend_config(C.Structure):
 
 class legend_prefetch(C.Structure):
     _fields_ = [("evict", C.c_int32), ("load", C.c_int32)]
+
+
+class legend_rank_metrics(C.Structure):
+    _fields_ = [("mrr", C.c_double), ("hits1", C.c_double), ("hits3", C.c_double), ("hits10", C.c_double),
+                ("ms", C.c_float)]
 
 
 class legend_bucket_stats(C.Structure):
@@ -86,6 +91,7 @@ def _load() -> C.CDLL:
                                               C.POINTER(legend_bucket_stats)]
     lib.legend_train_epoch.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(legend_epoch_stats)]
     lib.legend_score_edges.argtypes = [vp, vp, vp, vp, i64, vp]
+    lib.legend_rank_edges.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, vp, vp, C.POINTER(legend_rank_metrics)]
     lib.legend_read_embeddings.argtypes = [vp, i32, vp, i64, vp]
     lib.legend_debug_batch_indices.argtypes = [vp, i32, i32, vp, i64, i32, i32, i64, vp, i64, vp, i64,
                                                C.POINTER(i64)]
@@ -232,6 +238,23 @@ def legend_score_edges(ctx, src, rel, dst) -> np.ndarray:
     out = np.empty(s.shape[0], np.float32)
     _check(_lib.legend_score_edges(ctx, _ptr(s), _ptr(r), _ptr(d), s.shape[0], _ptr(out)))
     return out
+
+
+def legend_rank_edges(ctx, src, rel, dst, side: int = CORRUPT_DST, candidates=None):
+    """(greater, equal, metrics) of the triples against the candidates (None: all nodes)."""
+    s = _as(src, np.int64)
+    d = _as(dst, np.int64)
+    r = _as(rel, np.int32)
+    cand = _as(candidates, np.int64)
+    if cand is not None and cand.shape[0] == 0:
+        cand = np.zeros(1, np.int64)[:0]          # an empty list still needs a non-NULL pointer (NULL means all nodes)
+    m = s.shape[0]
+    greater = np.empty(m, np.int32)
+    equal = np.empty(m, np.int32)
+    mt = legend_rank_metrics()
+    _check(_lib.legend_rank_edges(ctx, _ptr(s), _ptr(r), _ptr(d), m, side, _ptr(cand),
+                                  0 if cand is None else cand.shape[0], _ptr(greater), _ptr(equal), C.byref(mt)))
+    return greater, equal, {k: getattr(mt, k) for k, _ in legend_rank_metrics._fields_}
 
 
 def legend_read_embeddings(ctx, table: int, ids, m: int, dim: int) -> np.ndarray:

@@ -116,6 +116,14 @@ hipError_t launch_score(hipStream_t st, const int64_t* src, const int32_t* rel, 
                         float* const* part_emb, int32_t rows_per_partition, int32_t num_partitions,
                         int64_t num_nodes, const float* E_rel, int32_t num_relations, int32_t dim,
                         int32_t score, float* out, uint32_t* err_flag);
+// ranks of m triples against a candidate set: q rows, own scores, greater/equal counts, MRR and Hits@k
+int64_t rank_rows_padded(int64_t m);
+int rank_dim_padded(int d);
+hipError_t launch_rank(hipStream_t st, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m,
+                       int32_t side, const int64_t* cand, int64_t n_cand, float* const* part_emb,
+                       int32_t rows_per_partition, int64_t num_nodes, const float* E_rel, int32_t num_relations,
+                       int32_t dim, int32_t score, float* Q, float* f, int32_t* true_id, int32_t* greater,
+                       int32_t* equal, double* metrics, uint32_t* err_flag);
 hipError_t launch_gather_rows(hipStream_t st, const int64_t* ids, int64_t m, float* const* part_base,
                               int32_t rows_per_partition, int64_t num_rows, int32_t dim, float* out,
                               uint32_t* err_flag);

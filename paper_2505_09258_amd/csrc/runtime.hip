@@ -971,6 +971,82 @@ int legend_score_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, co
     return LEGEND_OK;
 }
 
+int legend_rank_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m, int32_t side,
+                      const int64_t* candidates, int64_t num_candidates, int32_t* greater, int32_t* equal,
+                      legend_rank_metrics* metrics) {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (m < 0 || num_candidates < 0) return fail(LEGEND_E_INVAL, "m < 0 or num_candidates < 0");
+    if (side != LEGEND_CORRUPT_DST && side != LEGEND_CORRUPT_SRC)
+        return fail(LEGEND_E_INVAL, "side must be LEGEND_CORRUPT_DST or LEGEND_CORRUPT_SRC");
+    if (c->V > 0x7fffffffll) return fail(LEGEND_E_INVAL, "ranking needs num_nodes < 2^31");
+    if (metrics) *metrics = legend_rank_metrics{};
+    if (m == 0) return LEGEND_OK;
+    if (!src || !dst) return fail(LEGEND_E_INVAL, "NULL argument");
+    if (c->uses_rel && !rel) return fail(LEGEND_E_INVAL, "rel must not be NULL for this score");
+    const int64_t n_cand = candidates ? num_candidates : c->V;
+    if (n_cand > 0x7fffffffll) return fail(LEGEND_E_INVAL, "too many candidates");
+    for (int s = 0; s < c->nslots; ++s) {
+        rc = wait_slot(c, s);
+        if (rc) return rc;
+    }
+    if (c->part_tables_dirty) {
+        rc = upload_part_tables(c);
+        if (rc) return rc;
+    }
+    const int64_t m_pad = rank_rows_padded(m);
+    const int dp = rank_dim_padded(c->d);
+    auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
+    const size_t b_ids = up((size_t)m * sizeof(int64_t)), b_rel = up((size_t)m * sizeof(int32_t));
+    const size_t b_cand = up(candidates ? (size_t)n_cand * sizeof(int64_t) : 0);
+    const size_t b_q = up((size_t)m_pad * dp * sizeof(float)), b_row = up((size_t)m_pad * sizeof(int32_t));
+    rc = ensure_io(c, 2 * b_ids + b_rel + b_cand + b_q + 4 * b_row + 256);
+    if (rc) return rc;
+    char* p = static_cast<char*>(c->io_dev);
+    int64_t* d_src = reinterpret_cast<int64_t*>(p); p += b_ids;
+    int64_t* d_dst = reinterpret_cast<int64_t*>(p); p += b_ids;
+    int64_t* d_cand = reinterpret_cast<int64_t*>(p); p += b_cand;
+    float* d_q = reinterpret_cast<float*>(p); p += b_q;
+    float* d_f = reinterpret_cast<float*>(p); p += b_row;
+    int32_t* d_true = reinterpret_cast<int32_t*>(p); p += b_row;
+    int32_t* d_gt = reinterpret_cast<int32_t*>(p); p += b_row;
+    int32_t* d_eq = reinterpret_cast<int32_t*>(p); p += b_row;
+    int32_t* d_rel = reinterpret_cast<int32_t*>(p); p += b_rel;
+    double* d_metrics = reinterpret_cast<double*>(p);
+    uint32_t* flag = c->ws.counters + 1;
+    HIP_TRY(c, hipMemsetAsync(flag, 0, sizeof(uint32_t), c->compute));
+    HIP_TRY(c, hipMemsetAsync(d_gt, 0, 2 * b_row, c->compute));       // greater and equal are adjacent
+    HIP_TRY(c, hipMemcpyAsync(d_src, src, (size_t)m * sizeof(int64_t), hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(d_dst, dst, (size_t)m * sizeof(int64_t), hipMemcpyHostToDevice, c->compute));
+    if (rel) HIP_TRY(c, hipMemcpyAsync(d_rel, rel, (size_t)m * sizeof(int32_t), hipMemcpyHostToDevice, c->compute));
+    if (candidates && n_cand > 0)
+        HIP_TRY(c, hipMemcpyAsync(d_cand, candidates, (size_t)n_cand * sizeof(int64_t), hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(c, hipEventRecord(c->ev_t0, c->compute));
+    {
+        ProfScope ps(c, KC_MISC);
+        HIP_TRY(c, launch_rank(c->compute, d_src, rel ? d_rel : nullptr, d_dst, m, side, candidates ? d_cand : nullptr, n_cand,
+                               c->d_part_emb, (int32_t)c->Rp, c->V, c->E_rel, c->cfg.num_relations, c->d, c->cfg.score,
+                               d_q, d_f, d_true, d_gt, d_eq, d_metrics, flag));
+    }
+    HIP_TRY(c, hipEventRecord(c->ev_t1, c->compute));
+    uint32_t h = 0;
+    double mt[4] = {0, 0, 0, 0};
+    HIP_TRY(c, hipMemcpyAsync(&h, flag, sizeof h, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(mt, d_metrics, sizeof mt, hipMemcpyDeviceToHost, c->compute));
+    if (greater) HIP_TRY(c, hipMemcpyAsync(greater, d_gt, (size_t)m * sizeof(int32_t), hipMemcpyDeviceToHost, c->compute));
+    if (equal) HIP_TRY(c, hipMemcpyAsync(equal, d_eq, (size_t)m * sizeof(int32_t), hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    if (h & 1u) return fail(LEGEND_E_RANGE, "a node, relation or candidate id is out of range");
+    if (h & 2u) return fail(LEGEND_E_NOT_RESIDENT, "a triple or a candidate refers to a partition that is not resident");
+    if (metrics) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, c->ev_t0, c->ev_t1));
+        metrics->mrr = mt[0]; metrics->hits1 = mt[1]; metrics->hits3 = mt[2]; metrics->hits10 = mt[3];
+        metrics->ms = ms;
+    }
+    return LEGEND_OK;
+}
+
 int legend_read_embeddings(legend_ctx* c, int32_t table, const int64_t* ids, int64_t m, float* out) {
     int rc = check_ctx(c);
     if (rc) return rc;

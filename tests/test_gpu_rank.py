@@ -1,0 +1,173 @@
+"""GPU parity of legend_rank_edges (ranks behind MRR / Hits@k, Sec. 7 "Metrics") against oracle/rank.py.
+
+The counts are integers decided by fp32 comparisons.  Two kinds of cases:
+  * small-integer embeddings: every product and sum is exact in fp32 in any order, so the
+    counts (ties included) must equal the oracle's exactly;
+  * real-valued embeddings: a candidate whose float64 score lies within the fp32 error band of
+    the triple's own score may fall on either side; the counts must lie between the oracle's
+    counts taken with that band excluded and included, everything else being exact.
+"""
+
+import numpy as np
+import pytest
+
+from oracle import model, rank
+
+pytestmark = pytest.mark.gpu
+
+DST, SRC = rank.SIDE_DST, rank.SIDE_SRC
+
+
+def _ctx(V, d, n, score, node, rel, nrel, capacity=None):
+    from paper_2505_09258_amd import binding as L
+    cfg = L.make_config(num_nodes=V, dim=d, num_partitions=n, buffer_capacity=capacity, num_relations=nrel, score=score,
+                        batch_size=100, chunk_size=10, num_negs=10, seed=1)
+    ctx = L.legend_init_partitions(cfg, node, rel if score else None)
+    return L, ctx
+
+
+def _triples(rng, V, nrel, m):
+    src, dst = rng.integers(0, V, m), rng.integers(0, V, m)
+    if m >= 2:
+        src[:2] = [0, V - 1]
+        dst[:2] = [V - 1, 0]
+    r = rng.integers(0, max(nrel, 1), m).astype(np.int32)
+    return src, r, dst
+
+
+def _check_metrics(greater, equal, mt):
+    want = rank.metrics_from_ranks(rank.ranks_from_counts(greater, equal))
+    for k in ("mrr", "hits1", "hits3", "hits10"):
+        assert mt[k] == pytest.approx(want[k], rel=1e-12, abs=1e-15), k
+
+
+@pytest.mark.parametrize("score,d,side", [
+    (model.DOT, 20, DST), (model.DOT, 100, SRC), (model.DISTMULT, 36, DST), (model.DISTMULT, 30, SRC),
+    (model.COMPLEX, 100, DST), (model.COMPLEX, 34, SRC), (model.DISTMULT, 400, DST), (model.COMPLEX, 150, SRC)])
+def test_exact_counts_on_integer_embeddings(score, d, side):
+    rng = np.random.default_rng(100 * score + d + side)
+    V, n, nrel, m = 3_001, 2, 7, 150
+    node = rng.integers(-2, 3, size=(V, d)).astype(np.float32)
+    rel = rng.integers(-1, 2, size=(nrel, d)).astype(np.float32)
+    L, ctx = _ctx(V, d, n, score, node, rel, nrel)
+    try:
+        for p in range(n):
+            L.legend_swap_partition(ctx, -1, p)
+        src, r, dst = _triples(rng, V, nrel, m)
+        # every node as candidate
+        g, q, mt = L.legend_rank_edges(ctx, src, r, dst, side, None)
+        wg, wq = rank.rank_counts(score, node, rel, src, r, dst, side, None)
+        assert (g == wg).all() and (q == wq).all()
+        assert wq.sum() > 0                                   # the case does exercise ties
+        _check_metrics(g, q, mt)
+        # an explicit list with repeats, the true endpoints among it, a ragged length
+        cand = np.concatenate([rng.integers(0, V, 700), dst[:40], src[:37]])
+        g, q, mt = L.legend_rank_edges(ctx, src, r, dst, side, cand)
+        wg, wq = rank.rank_counts(score, node, rel, src, r, dst, side, cand)
+        assert (g == wg).all() and (q == wq).all()
+        _check_metrics(g, q, mt)
+        # the call does not touch the tables
+        after = L.legend_read_embeddings(ctx, L.TABLE_NODE_EMB, None, V, d)
+        assert (after == node).all()
+    finally:
+        L.legend_destroy(ctx)
+
+
+def _band(score, node, rel, src, r, dst, side):
+    """fp32 error bound of a d-term dot product, norm-wise: 1e-5 * |q| * max|c| (the bar of the score parity)."""
+    E = node.astype(np.float64)
+    R = rel.astype(np.float64)
+    stay = E[src] if side == DST else E[dst]
+    q = np.abs(stay) if score == model.DOT else model.abs_compose(score, stay, R[r])
+    return 1e-5 * np.linalg.norm(q, axis=1) * np.linalg.norm(E, axis=1).max()
+
+
+@pytest.mark.parametrize("score,d,side,m", [(model.DOT, 100, DST, 130), (model.COMPLEX, 100, SRC, 64),
+                                             (model.DISTMULT, 400, DST, 70), (model.COMPLEX, 50, DST, 1)])
+def test_counts_within_the_fp32_band_on_real_embeddings(score, d, side, m):
+    rng = np.random.default_rng(7 * score + d + side)
+    V, n, nrel = 5_003, 4, 11
+    node = rng.normal(0, 0.5, size=(V, d)).astype(np.float32)
+    rel = rng.normal(0, 0.5, size=(nrel, d)).astype(np.float32)
+    L, ctx = _ctx(V, d, n, score, node, rel, nrel)
+    try:
+        for p in range(n):
+            L.legend_swap_partition(ctx, -1, p)
+        src, r, dst = _triples(rng, V, nrel, m)
+        g, q, mt = L.legend_rank_edges(ctx, src, r, dst, side, None)
+        band = _band(score, node, rel, src, r, dst, side)
+        exact_g, exact_q = rank.rank_counts(score, node, rel, src, r, dst, side, None)
+        undecided = 0
+        for e in range(m):
+            lo, mid = rank.rank_counts(score, node, rel, src[e:e + 1], r[e:e + 1], dst[e:e + 1], side, None, band=band[e])
+            assert lo[0] <= g[e] <= lo[0] + mid[0], (e, lo[0], g[e], mid[0])
+            assert lo[0] <= g[e] + q[e] <= lo[0] + mid[0]
+            undecided += mid[0]
+        assert undecided <= 0.002 * m * V                      # the band leaves almost every comparison decided
+        assert np.count_nonzero(g != exact_g) <= max(1, m // 20)
+        _check_metrics(g, q, mt)
+        want = rank.metrics_from_ranks(rank.ranks_from_counts(exact_g, exact_q))
+        assert mt["mrr"] == pytest.approx(want["mrr"], rel=0.02, abs=1e-6)
+    finally:
+        L.legend_destroy(ctx)
+
+
+def test_full_benchmark_shape_sampled_rows():
+    """The FB15k-shaped workload as bench.py --rank runs it (d = 400, DistMult, every node a candidate,
+    2 000 triples): the oracle checks a sample of the triples one by one."""
+    from workloads import graphs
+    w = graphs.WORKLOADS["c3"]
+    node, rel = graphs.init_tables(w, seed=2)
+    node = (node * 300).astype(np.float32)
+    rel = (rel * 300 + np.float32(0.5)).astype(np.float32)
+    L, ctx = _ctx(w.num_nodes, w.dim, 1, w.score, node, rel, w.num_relations)
+    try:
+        L.legend_swap_partition(ctx, -1, 0)
+        rng = np.random.default_rng(4)
+        m = 2_000
+        src, r, dst = _triples(rng, w.num_nodes, w.num_relations, m)
+        for side in (DST, SRC):
+            g, q, mt = L.legend_rank_edges(ctx, src, r, dst, side, None)
+            pick = rng.choice(m, 40, replace=False)
+            band = _band(w.score, node, rel, src[pick], r[pick], dst[pick], side)
+            for k, e in enumerate(pick):
+                lo, mid = rank.rank_counts(w.score, node, rel, src[e:e + 1], r[e:e + 1], dst[e:e + 1], side, None, band=band[k])
+                assert lo[0] <= g[e] <= lo[0] + mid[0]
+                assert lo[0] <= g[e] + q[e] <= lo[0] + mid[0]
+            _check_metrics(g, q, mt)
+    finally:
+        L.legend_destroy(ctx)
+
+
+def test_errors_and_empty_inputs():
+    rng = np.random.default_rng(1)
+    V, d, n = 1_000, 16, 4
+    node = rng.normal(size=(V, d)).astype(np.float32)
+    L, ctx = _ctx(V, d, n, model.DOT, node, None, 0, capacity=3)
+    try:
+        for p in range(3):
+            L.legend_swap_partition(ctx, -1, p)
+        src, dst = np.array([1, 2, 3]), np.array([4, 5, 6])
+        g, q, mt = L.legend_rank_edges(ctx, src, None, dst, DST, np.array([7, 8, 9, 10]))
+        wg, wq = rank.rank_counts(model.DOT, node, None, src, None, dst, DST, [7, 8, 9, 10])
+        assert (g == wg).all() and (q == wq).all()
+        # no candidates: every rank is 1
+        g, q, mt = L.legend_rank_edges(ctx, src, None, dst, DST, np.zeros(0, np.int64))
+        assert (g == 0).all() and (q == 0).all() and mt["mrr"] == 1.0 and mt["hits1"] == 1.0
+        # no triples
+        g, q, mt = L.legend_rank_edges(ctx, np.zeros(0, np.int64), None, np.zeros(0, np.int64), DST, None)
+        assert g.shape == (0,) and mt["mrr"] == 0.0
+        with pytest.raises(L.LegendError) as ei:                  # a candidate in the partition that is not resident
+            L.legend_rank_edges(ctx, src, None, dst, DST, np.array([7, 999]))
+        assert ei.value.code == L.LEGEND_E_NOT_RESIDENT
+        with pytest.raises(L.LegendError) as ei:                  # all nodes as candidates need all partitions
+            L.legend_rank_edges(ctx, src, None, dst, DST, None)
+        assert ei.value.code == L.LEGEND_E_NOT_RESIDENT
+        with pytest.raises(L.LegendError) as ei:
+            L.legend_rank_edges(ctx, src, None, dst, DST, np.array([7, V]))
+        assert ei.value.code == L.LEGEND_E_RANGE
+        with pytest.raises(L.LegendError) as ei:
+            L.legend_rank_edges(ctx, src, None, dst, 2, np.array([7]))
+        assert ei.value.code == L.LEGEND_E_INVAL
+    finally:
+        L.legend_destroy(ctx)
