@@ -42,6 +42,7 @@ class OracleConfig:
     eps: float = 1e-10
     neg_weight: float = -1.0      # logistic only; < 0 means 1 / num_negs
     seed: int = 0
+    round_composed: bool = True   # translational score: u, v as fp32 numbers (False only for derivative checks)
 
     @property
     def rows_per_partition(self) -> int:
@@ -142,7 +143,8 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
             ids = neg[si, c]
             out = model.chunk_side(cfg.score, cfg.loss, cfg.w_neg, is_dst,
                                    s_all[sl], r_all[sl] if uses_rel else None, d_all[sl],
-                                   neg_table[ids].astype(np.float64), with_magnitudes=want_mags)
+                                   neg_table[ids].astype(np.float64), with_magnitudes=want_mags,
+                                   rounded=cfg.round_composed)
             loss += float(out["loss"].sum())
             if want_mags:
                 node_mags[ti].append(out["m_s"]); node_mags[tj].append(out["m_d"])

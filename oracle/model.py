@@ -8,6 +8,15 @@ mirror for source-side corruption is v = conj(theta_r) (x) theta_d, so that
 f = <u, theta_d> = <theta_s, v>.  Embeddings of dimension d hold ComplEx numbers
 as [real half | imaginary half] (Sec. 6, "first half / last half").
 
+A translational score (Sec. 8 of the paper names such models as easy to integrate;
+the form is the textbook one) fits the same frame with (x) an addition and (+) a
+negative L1 distance: u = theta_s + theta_r, v = theta_d - theta_r,
+f = -|u - theta_d|_1 = -|theta_s - v|_1; the negative block is then no matrix
+product.  Its gradient is a sum of signs, a discrete decision: u and v are rounded to
+fp32 (the storage precision, one IEEE addition of two fp32 numbers, so every
+implementation gets the same u and v), after which the sign of u_j - n_j is exact in
+any precision; sign(0) = 0.
+
 Loss: Eq. 1 as printed (the log-sum-exp runs over the sampled negatives only),
 the variant of Eq. 1 whose log-sum-exp also contains the positive score (the
 usual sampled softmax / cross-entropy; not the paper's default), or a logistic
@@ -18,7 +27,7 @@ from __future__ import annotations
 
 import numpy as np
 
-DOT, DISTMULT, COMPLEX = 0, 1, 2
+DOT, DISTMULT, COMPLEX, TRANSE = 0, 1, 2, 3
 SOFTMAX, LOGISTIC, SOFTMAX_POS = 0, 1, 2
 
 
@@ -41,8 +50,15 @@ def cmul_conj(a, b):
     return np.concatenate([ar * br + ai * bi, ar * bi - ai * br], axis=-1)
 
 
-def compose_u(score, s, r):
-    """u = theta_s (x) theta_r."""
+def _fp32(x):
+    return np.asarray(x, dtype=np.float32).astype(np.float64)
+
+
+def compose_u(score, s, r, rounded=True):
+    """u = theta_s (x) theta_r.  rounded: the translational u as the fp32 number (see above);
+    False leaves it exact, for derivative checks, which perturb below fp32 resolution."""
+    if score == TRANSE:
+        return _fp32(np.asarray(s, np.float32) + np.asarray(r, np.float32)) if rounded else s + r
     if score == DOT:
         return s.copy()
     if score == DISTMULT:
@@ -50,8 +66,10 @@ def compose_u(score, s, r):
     return cmul(s, r)
 
 
-def compose_v(score, r, d):
+def compose_v(score, r, d, rounded=True):
     """v = conj(theta_r) (x) theta_d  (the operand that meets theta_s)."""
+    if score == TRANSE:
+        return _fp32(np.asarray(d, np.float32) - np.asarray(r, np.float32)) if rounded else d - r
     if score == DOT:
         return d.copy()
     if score == DISTMULT:
@@ -59,7 +77,16 @@ def compose_v(score, r, d):
     return cmul_conj(r, d)
 
 
-def positive_scores(score, s, r, d):
+def pair_scores(score, q, rows):
+    """q (+) row for every pair: q [C, dim], rows [N, dim] -> [C, N]."""
+    if score == TRANSE:
+        return -np.abs(q[:, None, :] - rows[None, :, :]).sum(axis=-1)
+    return q @ rows.T
+
+
+def positive_scores(score, s, r, d, rounded=True):
+    if score == TRANSE:
+        return -np.abs(compose_u(score, s, r, rounded) - d).sum(axis=-1)
     return np.sum(compose_u(score, s, r) * d, axis=-1)
 
 
@@ -91,6 +118,8 @@ def side_loss(loss, f, S, neg_weight):
 
 def chain_from_u(score, g_u, s, r):
     """(g_s, g_r) from the gradient with respect to u = s (x) r."""
+    if score == TRANSE:
+        return g_u, g_u
     if score == DOT:
         return g_u, None
     if score == DISTMULT:
@@ -100,6 +129,8 @@ def chain_from_u(score, g_u, s, r):
 
 def chain_from_v(score, g_v, r, d):
     """(g_d, g_r) from the gradient with respect to v = conj(r) (x) d."""
+    if score == TRANSE:
+        return g_v, -g_v
     if score == DOT:
         return g_v, None
     if score == DISTMULT:
@@ -120,7 +151,7 @@ def abs_compose(score, a, b):
     return np.concatenate([ar * br + ai * bi, ar * bi + ai * br], axis=-1)
 
 
-def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitudes=False):
+def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitudes=False, rounded=True):
     """Loss and gradients of one chunk for one corrupted side.
 
     s, r, d: [C, dim] float64 rows of the chunk's positive edges (r ignored for Dot).
@@ -130,11 +161,13 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitu
     the absolute values of the elementary products it is made of (a forward error bound of
     any floating-point evaluation of that element is a small multiple of roundoff times this)."""
     if side_is_dst:
-        q = compose_u(score, s, r)       # meets destination-like rows
+        q = compose_u(score, s, r, rounded) if score == TRANSE else compose_u(score, s, r)       # meets destination-like rows
         other = d
     else:
-        q = compose_v(score, r, d)       # meets source-like rows
+        q = compose_v(score, r, d, rounded) if score == TRANSE else compose_v(score, r, d)       # meets source-like rows
         other = s
+    if score == TRANSE:
+        return _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, with_magnitudes)
     f = np.sum(q * other, axis=1)
     S = q @ negs.T
     l, a, W = side_loss(loss, f, S, neg_weight)
@@ -157,4 +190,28 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitu
         m_r = None if score == DOT else abs_compose(score, x, m_q)
         out.update(m_neg=np.abs(W).T @ aq, m_r=m_r,
                    m_s=m_x if side_is_dst else m_other, m_d=m_other if side_is_dst else m_x)
+    return out
+
+
+def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, with_magnitudes):
+    """chunk_side for the translational score: pair score -|q - row|_1,
+    d(pair)/dq = -sign(q - row), d(pair)/drow = +sign(q - row)."""
+    f = -np.abs(q - other).sum(axis=1)
+    sg = np.sign(q[:, None, :] - negs[None, :, :])            # [C, N, dim]
+    S = -np.abs(q[:, None, :] - negs[None, :, :]).sum(axis=-1)
+    l, a, W = side_loss(loss, f, S, neg_weight)
+    sg_pos = np.sign(q - other)
+    g_q = -a[:, None] * sg_pos - np.einsum("ck,ckj->cj", W, sg)
+    g_other = a[:, None] * sg_pos
+    g_neg = np.einsum("ck,ckj->kj", W, sg)
+    if side_is_dst:                                            # q = s + r
+        out = dict(loss=l, f=f, S=S, W=W, g_s=g_q, g_r=g_q, g_d=g_other, g_neg=g_neg)
+    else:                                                      # q = d - r
+        out = dict(loss=l, f=f, S=S, W=W, g_s=g_other, g_r=-g_q, g_d=g_q, g_neg=g_neg)
+    if with_magnitudes:
+        nz = np.abs(sg)
+        m_q = np.abs(a)[:, None] * np.abs(sg_pos) + np.einsum("ck,ckj->cj", np.abs(W), nz)
+        m_other = np.abs(a)[:, None] * np.abs(sg_pos)
+        out.update(m_neg=np.einsum("ck,ckj->kj", np.abs(W), nz), m_r=m_q,
+                   m_s=m_q if side_is_dst else m_other, m_d=m_other if side_is_dst else m_q)
     return out

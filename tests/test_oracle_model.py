@@ -146,13 +146,17 @@ def _loss_only(cfg, node, rel, edges, i, j):
     return batch_gradients(tab, i, j, edges, 0, 0)[0]
 
 
-@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
+@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX, model.TRANSE])
 @pytest.mark.parametrize("loss", [model.SOFTMAX, model.LOGISTIC, model.SOFTMAX_POS])
 @pytest.mark.parametrize("corrupt", [0, 1, 2])
 @pytest.mark.parametrize("bucket", [(0, 0), (0, 1), (1, 0)])
 def test_gradients_match_central_finite_differences(score, loss, corrupt, bucket):
     i, j = bucket
     cfg, node32, rel32, edges = _tiny(score, loss, corrupt, i, j, degree_negs=1)
+    # the translational u, v are exact here: the differences perturb below fp32 resolution.  Its
+    # kinks (a component of u equal to that of a row it meets: a negative that is the edge's own
+    # endpoint and a zero relation component) do not occur in these continuous random tables.
+    cfg.round_composed = False
     node, rel = node32.astype(np.float64), rel32.astype(np.float64)
     tab = Tables(cfg, node32, rel32)
     _, gnode, grel = batch_gradients(tab, i, j, edges, 0, 0)
@@ -188,18 +192,21 @@ def _torch_score(score, s, r, d):
         return (s * d).sum(-1)
     if score == model.DISTMULT:
         return (s * r * d).sum(-1)
+    if score == model.TRANSE:
+        return -(s + r - d).abs().sum(-1)
     h = s.shape[-1] // 2
     cs, cr, cd = (torch.complex(x[..., :h], x[..., h:]) for x in (s, r, d))
     return (cs * cr * torch.conj(cd)).real.sum(-1)
 
 
-@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX])
+@pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX, model.TRANSE])
 @pytest.mark.parametrize("bucket", [(0, 0), (1, 0)])
 def test_gradients_match_autograd_on_eq1_written_edge_by_edge(score, bucket):
     # Eq. 1 with the sampled negatives, written per positive edge and per
     # corrupted triple with no shared intermediates, differentiated by autograd.
     i, j = bucket
     cfg, node32, rel32, edges = _tiny(score, model.SOFTMAX, 2, i, j, seed=4)
+    cfg.round_composed = False            # autograd forms s + r - d in float64
     tab = Tables(cfg, node32, rel32)
     loss, gnode, grel = batch_gradients(tab, i, j, edges, 0, 0)
     neg = negatives.batch_negatives(cfg, 0, i, j, 0, edges, edges)
@@ -242,3 +249,46 @@ def test_softmax_gradient_invariants():
     assert (out["W"] >= 0).all()
     # g_d = -u for Eq. 1
     np.testing.assert_allclose(out["g_d"], -u, rtol=1e-15)
+
+
+# ---------------------------------------------------------------- translational score
+
+def test_translational_closed_forms():
+    # d = 2, integers: s + r = (3, 1); f = -(|3-1| + |1-4|) = -5
+    s, r, d = np.array([[1.0, 2.0]]), np.array([[2.0, -1.0]]), np.array([[1.0, 4.0]])
+    assert model.positive_scores(model.TRANSE, s, r, d)[0] == -5.0
+    # u meets d (destination side), s meets v = d - r (source side): the same number
+    assert -np.abs(s - model.compose_v(model.TRANSE, r, d)).sum() == -5.0
+    negs = np.array([[3.0, 1.0], [0.0, 0.0], [5.0, 1.0]])            # distances 0, 4, 2 from u
+    out = model.chunk_side(model.TRANSE, model.SOFTMAX, 1.0, True, s, r, d, negs)
+    np.testing.assert_array_equal(out["S"], [[0.0, -4.0, -2.0]])
+    W = np.exp([0.0, -4.0, -2.0]) / np.exp([0.0, -4.0, -2.0]).sum()
+    np.testing.assert_allclose(out["W"][0], W, rtol=1e-15)
+    # d(-|u - n|)/dn = sign(u - n): (0,0) for the negative equal to u, (+,+) for the origin, (-,0) for (5,1)
+    np.testing.assert_allclose(out["g_neg"], [[0, 0], [W[1], W[1]], [-W[2], 0]], rtol=1e-15)
+    # Eq. 1: a = -1, d f/du = -sign(u - d) = (-1, +1); negatives pull u towards themselves
+    want_gu = np.array([1.0, -1.0]) - (W[1] * np.array([1, 1]) + W[2] * np.array([-1, 0]))
+    np.testing.assert_allclose(out["g_s"][0], want_gu, rtol=1e-15)
+    np.testing.assert_allclose(out["g_r"][0], want_gu, rtol=1e-15)
+    np.testing.assert_allclose(out["g_d"][0], [-1.0, 1.0], rtol=1e-15)   # a * sign(u - d)
+    # source side: v = d - r = (-1, 5); the relation gradient changes sign
+    out = model.chunk_side(model.TRANSE, model.SOFTMAX, 1.0, False, s, r, d, negs)
+    np.testing.assert_allclose(out["g_r"], -out["g_d"], rtol=0, atol=0)
+
+
+def test_translational_negative_block_is_the_score_of_the_corrupted_triple_and_scipy_cityblock():
+    from scipy.spatial.distance import cdist
+    rng = np.random.default_rng(12)
+    s, r, d = (rng.standard_normal((4, 6)).astype(np.float32).astype(np.float64) for _ in range(3))
+    negs = rng.standard_normal((5, 6)).astype(np.float32).astype(np.float64)
+    out_d = model.chunk_side(model.TRANSE, model.SOFTMAX, 1.0, True, s, r, d, negs)
+    out_s = model.chunk_side(model.TRANSE, model.SOFTMAX, 1.0, False, s, r, d, negs)
+    for e, k in itertools.product(range(4), range(5)):
+        assert out_d["S"][e, k] == model.positive_scores(model.TRANSE, s[e:e + 1], r[e:e + 1], negs[k:k + 1])[0]
+        # source side through v = d - r: |n + r - d| and |n - fl(d - r)| agree to fp32 rounding of v
+        f_s = model.positive_scores(model.TRANSE, negs[k:k + 1], r[e:e + 1], d[e:e + 1], rounded=False)[0]
+        assert abs(out_s["S"][e, k] - f_s) < 1e-6
+    u = model.compose_u(model.TRANSE, s, r)
+    np.testing.assert_allclose(-out_d["S"], cdist(u, negs, metric="cityblock"), rtol=1e-14)
+    # the composed operands are fp32 numbers, within half an ulp of the exact sums
+    assert (u == u.astype(np.float32)).all() and np.abs(u - (s + r)).max() <= 2.0 ** -24 * np.abs(s + r).max()
