@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+VALU_F32_PEAK_TFLOPS = 157.3      # fp32 vector peak with every operation a fused multiply-add (256 CUs x 128 lanes x 2 x 2.4 GHz)
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 # HBM bytes per k_chunk_fast launch from the rocprofv3 counter runs summarised in
 # profiles/c2_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB, calibrated on a copy)
@@ -99,7 +100,7 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
                                f"{n} partitions, B={w.batch_size}, C={w.chunk_size}, N={w.num_negs}, sides={w.sides}, "
-                               f"score={['dot', 'distmult', 'complex'][w.score]}; one step = one epoch, edge list in "
+                               f"score={['dot', 'distmult', 'complex', 'transe-l1'][w.score]}; one step = one epoch, edge list in "
                                f"{args.edges} memory",
                    "update_mode": args.update_mode, "resident_partitions": capacity,
                    "prefetch": not args.no_overlap},
@@ -160,7 +161,7 @@ def run_rank(args, w, L, graphs, torch, np) -> int:
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name} ({w.stands_for}) ranking: {m} test triples against {n_cand} candidates "
                                f"({'every node' if cand is None else 'a shared uniform sample'}), {len(sides)} side(s) per step, "
-                               f"d={w.dim}, score={['dot', 'distmult', 'complex'][w.score]}; ids cross PCIe in, counts out, "
+                               f"d={w.dim}, score={['dot', 'distmult', 'complex', 'transe-l1'][w.score]}; ids cross PCIe in, counts out, "
                                f"inside the timed region"},
         "candidate_scores_per_s": round(m * n_cand * len(sides) * K / wall, 1),
         "roofline": {"kernel": "k_rank (gather + scores + compare-and-count, fp32 MFMA)", "bound": "mfma",
@@ -217,7 +218,7 @@ def main() -> int:
     ap.add_argument("--rank-triples", type=int, default=10_000)
     ap.add_argument("--rank-candidates", type=int, default=0, help="--rank: size of the shared candidate sample (0: every node)")
     ap.add_argument("--dim", type=int, default=0, help="override the embedding dimension of the workload (dimension sweep)")
-    ap.add_argument("--score", choices=["dot", "distmult", "complex"], default=None, help="override the score function")
+    ap.add_argument("--score", choices=["dot", "distmult", "complex", "transe"], default=None, help="override the score function")
     ap.add_argument("--batch-size", type=int, default=0, help="override the batch size")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -240,7 +241,8 @@ def main() -> int:
     if args.dim:
         over["dim"] = args.dim
     if args.score:
-        over["score"] = {"dot": graphs.SCORE_DOT, "distmult": graphs.SCORE_DISTMULT, "complex": graphs.SCORE_COMPLEX}[args.score]
+        over["score"] = {"dot": graphs.SCORE_DOT, "distmult": graphs.SCORE_DISTMULT, "complex": graphs.SCORE_COMPLEX,
+                         "transe": graphs.SCORE_TRANSE_L1}[args.score]
         if over["score"] != graphs.SCORE_DOT and w.num_relations == 0:
             over["num_relations"] = 1
     if args.batch_size:
@@ -393,6 +395,17 @@ def main() -> int:
                 "frac": round(achieved_tflops / MFMA_F32_PEAK_TFLOPS, 4),
                 "traffic": CHUNK_TRAFFIC_BYTES.get(w.name) if single_sweep else None,
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": round(chunk_ms, 4)}
+    translational = w.score == graphs.SCORE_TRANSE_L1
+    if translational:
+        # No matrix product: per (positive, negative, component) one subtraction and one |.|-add for the
+        # score, and for the backward pass a subtraction, a sign transfer and two accumulations: six
+        # vector operations, none of them fused multiply-adds (peak = half the fp32 FMA figure).
+        flops_per_launch = sides * 6 * P * N * d
+        achieved_tflops = flops_per_launch / (chunk_ms * 1e-3) / 1e12
+        roofline = {"kernel": "k_chunk_trans (gather + L1 scores + loss + backward, vector ALU)", "bound": "alu",
+                    "achieved": round(achieved_tflops, 3), "peak": VALU_F32_PEAK_TFLOPS / 2, "unit": "TFLOP/s",
+                    "frac": round(achieved_tflops / (VALU_F32_PEAK_TFLOPS / 2), 4), "traffic": None,
+                    "flops_per_launch": flops_per_launch, "avg_launch_ms": round(chunk_ms, 4)}
 
     # ---- second pass with every kernel class event-timed (separate from the timed region) ----
     kernels = {}
@@ -427,7 +440,7 @@ def main() -> int:
         if "chunk" in kernels:
             gather_bytes = 4 * d * (2 * P + Q)
             ms = kernels["chunk"]["ms_per_batch"]
-            kernels["chunk"].update({"bound": "mfma", "TFLOPs": round(flops_per_launch / ms / 1e9, 2),
+            kernels["chunk"].update({"bound": "alu" if translational else "mfma", "TFLOPs": round(flops_per_launch / ms / 1e9, 2),
                                      "gather_GBs": round(gather_bytes / ms / 1e6, 1)})
 
     out = {
@@ -436,7 +449,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name} ({w.stands_for}): {w.num_nodes} nodes, {w.num_edges} edges, d={w.dim}, "
                                f"{n} partitions, B={B}, C={w.chunk_size}, N={w.num_negs} ({w.num_degree_negs} degree-weighted), "
-                               f"sides={sides}, score={['dot', 'distmult', 'complex'][w.score]}",
+                               f"sides={sides}, score={['dot', 'distmult', 'complex', 'transe-l1'][w.score]}",
                    "update_mode": args.update_mode, "resident_partitions": capacity},
         "device_ms_per_step": round(dev_ms / K, 4),
         "algorithmic_bytes_per_step": int(alg_bytes), "unique_rows_per_step": round(u_b),

@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("LEGEND_HIP_LIB") or os.path.join(_HERE, "liblegend_hi
 LEGEND_OK = 0
 LEGEND_E_INVAL, LEGEND_E_NOMEM, LEGEND_E_NOT_RESIDENT = -1, -2, -3
 LEGEND_E_RANGE, LEGEND_E_HIP, LEGEND_E_STATE = -4, -5, -6
-SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX = 0, 1, 2
+SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX, SCORE_TRANSE_L1 = 0, 1, 2, 3
 LOSS_SOFTMAX, LOSS_LOGISTIC, LOSS_SOFTMAX_POS = 0, 1, 2
 CORRUPT_DST, CORRUPT_SRC, CORRUPT_BOTH = 0, 1, 2
 UPDATE_DETERMINISTIC, UPDATE_ATOMIC = 0, 1

@@ -19,7 +19,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblegend_hip.so")
 
 SOURCES = ["runtime.hip", "kernels_prepare.hip", "kernels_sort.hip", "kernels_chunk.hip", "kernels_chunk_gemm.hip", "kernels_chunk_fast.hip", "kernels_chunk_fast_distmult.hip", "kernels_chunk_fast_complex.hip",
-           "kernels_update.hip", "kernels_rank.hip", "order_plan.cpp"]
+           "kernels_update.hip", "kernels_rank.hip", "kernels_chunk_trans.hip", "order_plan.cpp"]
 
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -54,6 +54,7 @@ __device__ inline float4 lds4(const float* p) { return *reinterpret_cast<const f
 
 bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp);
 hipError_t launch_chunks_fast(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_chunks_trans(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 
 }  // namespace legend

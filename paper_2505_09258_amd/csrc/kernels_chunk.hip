@@ -589,7 +589,7 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
 }
 
 bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    return g.P > 0 && chunk_fast_applies(g, bp) && !ws.no_fast_path;
+    return g.P > 0 && bp.score != LEGEND_SCORE_TRANSE_L1 && chunk_fast_applies(g, bp) && !ws.no_fast_path;
 }
 
 // redo = false: the batch computation proper.  redo = true (only after a single-sweep launch):
@@ -599,6 +599,7 @@ hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams&
     const bool single = chunks_use_single_sweep(g, bp, ws);
     if (redo && !single) return hipSuccess;
     if (!redo && single) return launch_chunks_fast(st, g, bp, ws);
+    if (bp.score == LEGEND_SCORE_TRANSE_L1) return launch_chunks_trans(st, g, bp, ws);
     const uint32_t* only_if = redo ? ws.redo : nullptr;
     // the dimensions of the paper's workloads get kernels with the dimension folded in
     if (bp.dim == 100) return launch_chunks_nb<4, 100>(st, g, bp, ws, only_if);

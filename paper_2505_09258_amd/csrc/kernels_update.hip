@@ -350,6 +350,8 @@ k_score(const int64_t* __restrict__ src, const int32_t* __restrict__ rel, const 
             float qi = sp[k] * rp[k + h] + sp[k + h] * rp[k];
             acc += qr * tp[k] + qi * tp[k + h];
         }
+    } else if (score == LEGEND_SCORE_TRANSE_L1) {
+        for (int k = lane; k < d; k += kWave) acc -= fabsf((sp[k] + rp[k]) - tp[k]);
     } else if (score == LEGEND_SCORE_DISTMULT) {
         for (int k = lane; k < d; k += kWave) acc += sp[k] * rp[k] * tp[k];
     } else {

@@ -434,11 +434,13 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "num_nodes, dim, num_partitions must be positive and num_partitions <= num_nodes");
     if (!dim_supported(cfg->dim))
         return fail(LEGEND_E_INVAL, "dim %d is not supported (1..%d)", cfg->dim, max_dim_supported());
-    if (cfg->score < 0 || cfg->score > 2 || cfg->loss < 0 || cfg->loss > 2 || cfg->corrupt < 0 || cfg->corrupt > 2)
+    if (cfg->score < 0 || cfg->score > 3 || cfg->loss < 0 || cfg->loss > 2 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
     if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)
         return fail(LEGEND_E_INVAL, "unknown update_mode %d", cfg->update_mode);
     if (cfg->score == LEGEND_SCORE_COMPLEX && (cfg->dim & 1)) return fail(LEGEND_E_INVAL, "ComplEx needs an even dim");
+    if (cfg->score == LEGEND_SCORE_TRANSE_L1 && cfg->dim > 128)
+        return fail(LEGEND_E_INVAL, "the translational score is implemented for dim <= 128");
     if (cfg->score != LEGEND_SCORE_DOT && cfg->num_relations < 1)
         return fail(LEGEND_E_INVAL, "this score function needs num_relations >= 1");
     if (cfg->score != LEGEND_SCORE_DOT && !init_rel_emb) return fail(LEGEND_E_INVAL, "init_rel_emb must not be NULL for this score");
@@ -980,6 +982,8 @@ int legend_rank_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, con
     if (side != LEGEND_CORRUPT_DST && side != LEGEND_CORRUPT_SRC)
         return fail(LEGEND_E_INVAL, "side must be LEGEND_CORRUPT_DST or LEGEND_CORRUPT_SRC");
     if (c->V > 0x7fffffffll) return fail(LEGEND_E_INVAL, "ranking needs num_nodes < 2^31");
+    if (c->cfg.score == LEGEND_SCORE_TRANSE_L1)
+        return fail(LEGEND_E_INVAL, "ranking is implemented for the product scores (Dot, DistMult, ComplEx)");
     if (metrics) *metrics = legend_rank_metrics{};
     if (m == 0) return LEGEND_OK;
     if (!src || !dst) return fail(LEGEND_E_INVAL, "NULL argument");

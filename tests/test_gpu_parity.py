@@ -9,7 +9,7 @@ from tests.parity_util import EMB_RTOL, STATE_RTOL, OracleRun, check_scores, com
 
 pytestmark = pytest.mark.gpu
 
-DOT, DISTMULT, COMPLEX = 0, 1, 2
+DOT, DISTMULT, COMPLEX, TRANSE = 0, 1, 2, 3
 SOFTMAX, LOGISTIC, SOFTMAX_POS = 0, 1, 2
 DST, SRC, BOTH = 0, 1, 2
 
@@ -43,6 +43,10 @@ CASES = [
     _case("distmult_d256_softmax_pos", DISTMULT, SOFTMAX_POS, SRC, 2_000, 5, 256, 1, 0, 0, 200, 40, 70, 0, 450, 0.2),
     # a wide dimension that is not a multiple of four (rows only 8-byte aligned); chunks of 120 rows take two row tiles
     _case("complex_d150_both", COMPLEX, SOFTMAX, BOTH, 2_500, 6, 150, 2, 1, 0, 300, 120, 90, 20, 700, 0.2),
+    # translational score (vector-ALU kernel): both sides, a dimension that is no multiple of four, two row tiles per chunk
+    _case("transe_d100_both", TRANSE, SOFTMAX, BOTH, 5_000, 9, 100, 2, 0, 1, 600, 50, 200, 40, 1_300, 0.1),
+    _case("transe_d30_logistic_src", TRANSE, LOGISTIC, SRC, 2_000, 5, 30, 2, 1, 1, 200, 33, 65, 10, 450, 0.2),
+    _case("transe_d128_softmax_pos", TRANSE, SOFTMAX_POS, DST, 3_000, 4, 128, 1, 0, 0, 360, 120, 130, 0, 800, 0.1),
 ]
 
 # One node row in 64 is four times larger than the rest, so that some chunks hold a score far
@@ -55,7 +59,7 @@ def _inputs(c):
     rng = np.random.default_rng(c["seed"])
     rp = -(-c["V"] // c["n"])
     node = (c["std"] * rng.standard_normal((c["V"], c["d"]))).astype(np.float32)
-    rel = (c["std"] * rng.standard_normal((max(c["nrel"], 1), c["d"]))).astype(np.float32) + np.float32(0.5 if c["score"] else 0)
+    rel = (c["std"] * rng.standard_normal((max(c["nrel"], 1), c["d"]))).astype(np.float32) + np.float32(0.5 if c["score"] in (DISTMULT, COMPLEX) else 0)
     if c.get("hot_every"):
         node[17::c["hot_every"]] *= np.float32(c["hot_scale"])
 
@@ -205,7 +209,7 @@ def _check_every_batch(c):
         L.legend_destroy(ctx)
 
 
-_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11]
+_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11] + [c for c in CASES if c["name"] == "transe_d100_both"]
 
 
 @pytest.mark.parametrize("c", _ATOMIC_CASES, ids=[c["name"] for c in _ATOMIC_CASES])
@@ -245,7 +249,12 @@ def test_atomic_mode_every_batch_matches_oracle(c):
 def test_free_running_bucket_stays_close_to_oracle(c):
     """Whole bucket without resynchronisation.  Differences of earlier batches feed later
     ones (a gradient can be a copy of another row: g_d = -theta_s for Dot), so the strict
-    per-element bound is asked of 99.5 % of the elements and a bound 100 times wider of all."""
+    per-element bound is asked of 99.5 % of the elements and a bound 100 times wider of all.
+    The translational score has a discontinuous gradient (signs): once two runs differ by a
+    rounding error, a sign of a later batch can differ and move an element by a whole step, so
+    for it only the loss (to 2 %) and the structural facts are asked here; the per-batch
+    lockstep test above holds it to the full bar."""
+    discrete = c["score"] == TRANSE
     node, rel, edges = _inputs(c)
     L, ctx = _gpu_ctx(c, node, rel)
     try:
@@ -256,13 +265,16 @@ def test_free_running_bucket_stays_close_to_oracle(c):
         run = OracleRun(_ocfg(c), node, rel if c["score"] else None)
         want_loss = run.train_bucket(i, j, edges, epoch=1)
         assert stats["batches"] == -(-c["m"] // c["B"]) and stats["edges"] == c["m"]
-        assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss), (stats["loss_sum"], want_loss)
+        assert abs(stats["loss_sum"] - want_loss) <= (2e-2 if discrete else 1e-5) * abs(want_loss), (stats["loss_sum"], want_loss)
         got = _read_all(L, ctx, c)
         want_E = run.tab.node_table(0).astype(np.float64)
         err = np.abs(got[0].astype(np.float64) - want_E)
         strict = EMB_RTOL * np.maximum(np.abs(want_E), 0.1) + run.node_allowance(0)
-        assert (err <= strict).mean() >= 0.995, (err <= strict).mean()
-        assert (err <= 100 * strict).all(), float((err / strict).max())
+        if not discrete:
+            assert (err <= strict).mean() >= 0.995, (err <= strict).mean()
+            assert (err <= 100 * strict).all(), float((err / strict).max())
+        else:
+            assert (err <= strict).mean() >= 0.9, (err <= strict).mean()
         touched = np.concatenate(run.touched_node, 0)[: c["V"]]
         assert np.array_equal(got[0][~touched], node[~touched])
         assert not got[1][~touched].any()
@@ -282,7 +294,7 @@ def test_free_running_bucket_stays_close_to_oracle(c):
         L.legend_destroy(ctx)
 
 
-@pytest.mark.parametrize("score", [DOT, DISTMULT, COMPLEX])
+@pytest.mark.parametrize("score", [DOT, DISTMULT, COMPLEX, TRANSE])
 def test_score_edges_matches_oracle_on_initial_tables(score):
     c = _case("s", score, SOFTMAX, DST, 5_003, 11, 100, 4, 0, 0, 100, 10, 10, 0, 10, 0.5, seed=3)
     node, rel, _ = _inputs(c)

@@ -26,7 +26,7 @@ from typing import Dict, Optional, Tuple
 
 import numpy as np
 
-SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX = 0, 1, 2
+SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX, SCORE_TRANSE_L1 = 0, 1, 2, 3
 LOSS_SOFTMAX, LOSS_LOGISTIC, LOSS_SOFTMAX_POS = 0, 1, 2
 CORRUPT_DST, CORRUPT_SRC, CORRUPT_BOTH = 0, 1, 2
 
