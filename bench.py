@@ -21,7 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
-VALU_F32_PEAK_TFLOPS = 157.3      # fp32 vector peak with every operation a fused multiply-add (256 CUs x 128 lanes x 2 x 2.4 GHz)
+VALU_F32_PEAK_TFLOPS = 157.3      # fp32 vector peak: 256 CUs x 64 lanes x 2 (packed) x 2 (fused multiply-add) x 2.4 GHz
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 # HBM bytes per k_chunk_fast launch from the rocprofv3 counter runs summarised in
 # profiles/c2_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB, calibrated on a copy)
