@@ -89,14 +89,23 @@ __device__ inline void apply_row(const UpdateTables& tb, uint32_t key, const dou
     }
 }
 
-// LPR lanes (a float4 each) own one table row.  Rows with many gradient rows are only
-// recorded here (counters[2] = how many, long_list = which) and handled by the kernels below.
+// Table rows with many gradient rows (counters[2] = how many, long_list = which, in no particular
+// order: every such row is handled on its own).  Part of the index side of a batch: it depends
+// on the segment bounds only.
+__global__ void __launch_bounds__(256)
+k_long_list(uint32_t* __restrict__ counters, const uint32_t* __restrict__ seg_start, uint32_t* __restrict__ long_list) {
+    const uint32_t n_unique = counters[0];
+    for (uint32_t u = blockIdx.x * 256 + threadIdx.x; u < n_unique; u += gridDim.x * 256)
+        if (seg_start[u + 1] - seg_start[u] > (uint32_t)kLongLen) long_list[atomicAdd(&counters[2], 1u)] = u;
+}
+
+// LPR lanes (a float4 each) own one table row.  Rows with many gradient rows are left to the
+// kernels below.
 template <int LPR>
 __global__ void __launch_bounds__(256)
-k_update(uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
+k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
          const uint32_t* __restrict__ seg_start, const uint32_t* __restrict__ sorted_vals,
-         const float* __restrict__ grad, UpdateTables tb, int d, float lr, float eps,
-         uint32_t* __restrict__ long_list) {
+         const float* __restrict__ grad, UpdateTables tb, int d, float lr, float eps) {
     const int groups_per_block = 256 / LPR;
     const int gl = threadIdx.x / LPR;
     const int col4 = threadIdx.x % LPR;
@@ -105,10 +114,7 @@ k_update(uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys
     const uint32_t n_unique = counters[0];
     for (uint32_t u = blockIdx.x * groups_per_block + gl; u < n_unique; u += gridDim.x * groups_per_block) {
         const uint32_t lo = seg_start[u], hi = seg_start[u + 1];
-        if (hi - lo > (uint32_t)kLongLen) {
-            if (col4 == 0) long_list[atomicAdd(&counters[2], 1u)] = u;
-            continue;
-        }
+        if (hi - lo > (uint32_t)kLongLen) continue;
         for (int cc = c0; cc < d; cc += 4 * LPR) {     // rows wider than 4*LPR floats take several passes
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
             sum_rows(grad, sorted_vals, lo, hi, d, cc, vec4, acc);
@@ -226,14 +232,16 @@ k_long_final(const uint32_t* __restrict__ counters, const uint32_t* __restrict__
 
 template <int LPR>
 static hipError_t launch_update_lpr(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
-                                    const uint32_t* sorted_vals, const UpdateTables& tb) {
+                                    const uint32_t* sorted_vals, const UpdateTables& tb, bool long_rows) {
     const int d = bp.dim;
     const int groups = 256 / LPR;
-    int64_t blocks = (g.n_occ + groups - 1) / groups;
-    if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_update<LPR>, dim3((unsigned)blocks), dim3(256), 0, st, ws.counters, ws.uniq_keys, ws.seg_start,
-                       sorted_vals, ws.grad, tb, d, bp.lr, bp.eps, ws.long_list);
-    hipLaunchKernelGGL(k_long_plan, dim3(1), dim3(256), 0, st, ws.counters, ws.long_list, ws.seg_start, ws.unit_start);
+    if (!long_rows) {
+        int64_t blocks = (g.n_occ + groups - 1) / groups;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(k_update<LPR>, dim3((unsigned)blocks), dim3(256), 0, st, ws.counters, ws.uniq_keys, ws.seg_start,
+                           sorted_vals, ws.grad, tb, d, bp.lr, bp.eps);
+        return hipGetLastError();
+    }
     int64_t max_units = g.n_occ / kUnit + g.n_occ / (kLongLen + 1) + 1;
     int64_t ublocks = max_units < 2048 ? max_units : 2048;
     hipLaunchKernelGGL(k_long_partial<LPR>, dim3((unsigned)ublocks), dim3(256), sizeof(double) * 4 * 256, st, ws.counters,
@@ -248,9 +256,20 @@ static hipError_t launch_update_lpr(hipStream_t st, const BatchGeom& g, const Bu
 int64_t update_long_rows_capacity(int64_t n_occ) { return n_occ / (kLongLen + 1) + 2; }
 int64_t update_long_units_capacity(int64_t n_occ) { return n_occ / kUnit + n_occ / (kLongLen + 1) + 2; }
 
+// Index side: which table rows of the batch take the two-level path, and their units.
+hipError_t launch_long_plan(hipStream_t st, int64_t n_occ, const Workspace& ws) {
+    if (n_occ <= 0) return hipSuccess;
+    int64_t blocks = (n_occ + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_long_list, dim3((unsigned)blocks), dim3(256), 0, st, ws.counters, ws.seg_start, ws.long_list);
+    hipLaunchKernelGGL(k_long_plan, dim3(1), dim3(256), 0, st, ws.counters, ws.long_list, ws.seg_start, ws.unit_start);
+    return hipGetLastError();
+}
+
+// long_rows = false: the table rows with few gradient rows; true: the others (two-level sums).
+// The two touch disjoint table rows and may run at the same time on different streams.
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
-                         const uint32_t* sorted_vals, int32_t rows_per_partition) {
-    (void)rows_per_partition;
+                         const uint32_t* sorted_vals, bool long_rows) {
     if (g.n_occ <= 0) return hipSuccess;
     UpdateTables tb;
     tb.E[0] = bp.E_src; tb.S[0] = bp.S_src;
@@ -258,10 +277,10 @@ hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams&
     tb.E[2] = bp.E_rel; tb.S[2] = bp.S_rel;
     tb.key_base[0] = 0; tb.key_base[1] = bp.key_base_dst; tb.key_base[2] = bp.key_base_rel;
     const int d = bp.dim;
-    if (d <= 32) return launch_update_lpr<8>(st, g, bp, ws, sorted_vals, tb);
-    if (d <= 64) return launch_update_lpr<16>(st, g, bp, ws, sorted_vals, tb);
-    if (d <= 128) return launch_update_lpr<32>(st, g, bp, ws, sorted_vals, tb);
-    return launch_update_lpr<64>(st, g, bp, ws, sorted_vals, tb);
+    if (d <= 32) return launch_update_lpr<8>(st, g, bp, ws, sorted_vals, tb, long_rows);
+    if (d <= 64) return launch_update_lpr<16>(st, g, bp, ws, sorted_vals, tb, long_rows);
+    if (d <= 128) return launch_update_lpr<32>(st, g, bp, ws, sorted_vals, tb, long_rows);
+    return launch_update_lpr<64>(st, g, bp, ws, sorted_vals, tb, long_rows);
 }
 
 // Atomic mode: the batch gradient of every table row already sits in a dense fp32 accumulator

@@ -13,9 +13,10 @@ enum KernelClass : int {
     KC_PREPARE = 0,   // negative ids + sort keys of a batch
     KC_SORT,          // radix sort passes (histogram, scan, scatter) + segment heads
     KC_CHUNK,         // fused gather + scores + loss + backward per chunk (MFMA)
-    KC_UPDATE,        // segmented gradient reduce + Adagrad
+    KC_UPDATE,        // segmented gradient reduce + Adagrad (table rows with few gradient rows)
     KC_CHUNK_REDO,    // two-sweep kernel over the chunks the single-sweep kernel handed back
     KC_MISC,          // loss reduction, validation, scoring
+    KC_UPDATE_LONG,   // the same for table rows with many gradient rows (two-level sums), on a stream of its own
     KC_COUNT
 };
 
@@ -108,8 +109,9 @@ hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, con
 // redo = false: the batch computation; redo = true: second launch over the workgroups the single-sweep kernel flagged
 bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws, bool redo);
+hipError_t launch_long_plan(hipStream_t st, int64_t n_occ, const Workspace& ws);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
-                         const uint32_t* sorted_vals, int32_t rows_per_partition);
+                         const uint32_t* sorted_vals, bool long_rows);
 hipError_t launch_update_atomic(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_loss_reduce(hipStream_t st, int64_t nwg, const Workspace& ws);
 hipError_t launch_score(hipStream_t st, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m,

@@ -32,7 +32,7 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
-const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "chunk_redo", "misc"};
+const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "chunk_redo", "misc", "update_long"};
 
 struct ProfSpan {
     int cls;
@@ -71,6 +71,8 @@ struct legend_ctx {
     bool own_compute = false, own_copy = false;
     hipEvent_t ev_fence = nullptr, ev_t0 = nullptr, ev_t1 = nullptr;
     hipStream_t aux = nullptr;              // index side (negatives, keys, sort) of the next batch, one batch ahead
+    hipStream_t aux2 = nullptr;             // update of the table rows with many gradient rows, next to the other rows' update
+    hipEvent_t ev_chunk_done = nullptr, ev_long_done = nullptr;
     hipEvent_t ev_start = nullptr;          // compute stream has reached the start of a bucket call
     hipEvent_t ev_index[2] = {nullptr, nullptr};    // index side of a batch complete (per workspace)
     hipEvent_t ev_updated[2] = {nullptr, nullptr};  // update of a batch complete: its index buffers are free
@@ -286,11 +288,14 @@ void free_ctx(legend_ctx* c) {
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
                      c->ws.counters, c->ws_odd.neg_ids, c->ws_odd.keys[0], c->ws_odd.keys[1], c->ws_odd.vals[0], c->ws_odd.vals[1],
-                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->ws.gemm_Q, c->ws.gemm_G, c->ws.gemm_f,
+                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws_odd.long_list, c->ws_odd.unit_start, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->ws.gemm_Q, c->ws.gemm_G, c->ws.gemm_f,
                      c->ws.gemm_a, c->ws.gemm_S, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
     if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
+    if (c->aux2) { (void)hipStreamSynchronize(c->aux2); (void)hipStreamDestroy(c->aux2); }
+    if (c->ev_chunk_done) (void)hipEventDestroy(c->ev_chunk_done);
+    if (c->ev_long_done) (void)hipEventDestroy(c->ev_long_done);
     if (c->ev_start) (void)hipEventDestroy(c->ev_start);
     for (int k = 0; k < 2; ++k) {
         if (c->ev_index[k]) (void)hipEventDestroy(c->ev_index[k]);
@@ -412,6 +417,7 @@ int enqueue_index_side(legend_ctx* c, hipStream_t st, const BatchGeom& g, const 
     {
         ProfScope ps(c, KC_SORT, st);
         HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, ws, sorted_buf));
+        if (c->cfg.update_mode != LEGEND_UPDATE_ATOMIC) HIP_TRY(c, launch_long_plan(st, g.n_occ, ws));
     }
     return LEGEND_OK;
 }
@@ -510,6 +516,9 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     else { INIT_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)); c->own_copy = true; }
     INIT_TRY(hipEventCreateWithFlags(&c->ev_fence, hipEventDisableTiming));
     INIT_TRY(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
+    INIT_TRY(hipStreamCreateWithFlags(&c->aux2, hipStreamNonBlocking));
+    INIT_TRY(hipEventCreateWithFlags(&c->ev_chunk_done, hipEventDisableTiming));
+    INIT_TRY(hipEventCreateWithFlags(&c->ev_long_done, hipEventDisableTiming));
     INIT_TRY(hipEventCreateWithFlags(&c->ev_start, hipEventDisableTiming));
     for (int k = 0; k < 2; ++k) {
         INIT_TRY(hipEventCreateWithFlags(&c->ev_index[k], hipEventDisableTiming));
@@ -615,6 +624,9 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         o = w;
         o.neg_ids = nullptr; o.keys[0] = o.keys[1] = nullptr; o.vals[0] = o.vals[1] = nullptr;
         o.ghist = nullptr; o.scan_tmp = nullptr; o.uniq_keys = nullptr; o.seg_start = nullptr; o.counters = nullptr;
+        o.long_list = nullptr; o.unit_start = nullptr;
+        INIT_RC(dev_alloc(c, &o.long_list, (size_t)update_long_rows_capacity(occ)));
+        INIT_RC(dev_alloc(c, &o.unit_start, (size_t)update_long_rows_capacity(occ) + 1));
         INIT_RC(dev_alloc(c, &o.neg_ids, (size_t)c->gmax.sides * c->gmax.nchunks * c->gmax.N));
         for (int k = 0; k < 2; ++k) {
             INIT_RC(dev_alloc(c, &o.keys[k], (size_t)occ));
@@ -646,6 +658,7 @@ int legend_sync(legend_ctx* c) {
     int rc = check_ctx(c);
     if (rc) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->compute));
+    HIP_TRY(c, hipStreamSynchronize(c->aux2));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
     HIP_TRY(c, hipStreamSynchronize(c->copy_out));
     return LEGEND_OK;
@@ -770,10 +783,27 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             HIP_TRY(c, hipEventRecord(c->ev_index[nxt], c->aux));
             bp = keep;
         }
-        {
+        if (bp.atomic_mode) {
             ProfScope ps(c, KC_UPDATE);
-            if (bp.atomic_mode) HIP_TRY(c, launch_update_atomic(c->compute, g, bp, ws));
-            else HIP_TRY(c, launch_update(c->compute, g, bp, ws, ws.vals[sorted_of[cur]], (int32_t)c->Rp));
+            HIP_TRY(c, launch_update_atomic(c->compute, g, bp, ws));
+        } else {
+            // the table rows with many gradient rows are disjoint from the others: their two-level
+            // sums run on a stream of their own next to the main update kernel
+            hipStream_t ls = ahead ? c->aux2 : c->compute;
+            if (ahead) {
+                HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
+                HIP_TRY(c, hipStreamWaitEvent(c->aux2, c->ev_chunk_done, 0));
+            }
+            {
+                ProfScope ps(c, KC_UPDATE_LONG, ls);
+                HIP_TRY(c, launch_update(ls, g, bp, ws, ws.vals[sorted_of[cur]], true));
+            }
+            if (ahead) HIP_TRY(c, hipEventRecord(c->ev_long_done, c->aux2));
+            {
+                ProfScope ps(c, KC_UPDATE);
+                HIP_TRY(c, launch_update(c->compute, g, bp, ws, ws.vals[sorted_of[cur]], false));
+            }
+            if (ahead) HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_long_done, 0));
         }
         if (ahead) HIP_TRY(c, hipEventRecord(c->ev_updated[cur], c->compute));
         c->batches_done += 1;

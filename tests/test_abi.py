@@ -78,4 +78,4 @@ def test_profile_names():
     while L.legend_profile_name(k) is not None:
         names.append(L.legend_profile_name(k))
         k += 1
-    assert names == ["prepare", "sort", "chunk", "update", "chunk_redo", "misc"]
+    assert names == ["prepare", "sort", "chunk", "update", "chunk_redo", "misc", "update_long"]
