@@ -767,7 +767,9 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             ProfScope ps(c, KC_CHUNK_REDO);
             HIP_TRY(c, launch_chunks(c->compute, g, bp, ws, true));
         }
-        {
+        // the sum of the workgroups' loss terms is off the critical path when the second stream is in use
+        const bool loss_aside = ahead && !bp.atomic_mode;
+        if (!loss_aside) {
             ProfScope ps(c, KC_MISC);
             HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, ws));
         }
@@ -793,6 +795,8 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             if (ahead) {
                 HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
                 HIP_TRY(c, hipStreamWaitEvent(c->aux2, c->ev_chunk_done, 0));
+                ProfScope ps(c, KC_MISC, c->aux2);
+                HIP_TRY(c, launch_loss_reduce(c->aux2, (int64_t)g.sides * g.nchunks * g.T, ws));
             }
             {
                 ProfScope ps(c, KC_UPDATE_LONG, ls);
