@@ -165,10 +165,15 @@ def run_rank(args, w, L, graphs, torch, np) -> int:
                                f"inside the timed region"},
         "candidate_scores_per_s": round(m * n_cand * len(sides) * K / wall, 1),
         "roofline": {"kernel": "k_rank (gather + scores + compare-and-count, fp32 MFMA)", "bound": "mfma",
-                     "achieved": round(flops / (launch_ms * 1e-3) / 1e12, 3), "peak": 157.3, "unit": "TFLOP/s",
-                     "frac": round(flops / (launch_ms * 1e-3) / 1e12 / 157.3, 4), "traffic": None,
+                     "achieved": round(flops / (launch_ms * 1e-3) / 1e12, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(flops / (launch_ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
                      "flops_per_launch": int(flops), "avg_launch_ms": round(launch_ms, 4)},
     }
+    if w.score == graphs.SCORE_TRANSE_L1:
+        # a subtraction and a |.|-add per component and pair: vector operations that are not fused multiply-adds
+        out["roofline"].update({"kernel": "k_rank_trans (gather + L1 scores + compare-and-count, vector ALU)", "bound": "alu",
+                                "peak": VALU_F32_PEAK_TFLOPS / 2,
+                                "frac": round(flops / (launch_ms * 1e-3) / 1e12 / (VALU_F32_PEAK_TFLOPS / 2), 4)})
     if not args.no_cpu_baseline:
         from oracle import rank as orank
         t1 = time.perf_counter()

@@ -48,8 +48,7 @@ typedef enum legend_status {
  * LEGEND_SCORE_TRANSE_L1 is the translational score -|theta_s + theta_r - theta_d|_1
  * (one of the other models Sec. 8 says fit the same frame): (x) is an addition, its
  * result u = theta_s + theta_r (v = theta_d - theta_r on the source side) is the
- * fp32 sum, and the derivative of |.| at 0 is taken as 0.  dim <= 128; not
- * available in legend_rank_edges. */
+ * fp32 sum, and the derivative of |.| at 0 is taken as 0.  dim <= 128. */
 enum { LEGEND_SCORE_DOT = 0, LEGEND_SCORE_DISTMULT = 1, LEGEND_SCORE_COMPLEX = 2, LEGEND_SCORE_TRANSE_L1 = 3 };
 /* Eq. 1 as printed (log-sum-exp over the sampled negatives only), logistic, or
  * the variant of Eq. 1 whose log-sum-exp also holds the positive score (sampled

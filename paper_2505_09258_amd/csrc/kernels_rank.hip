@@ -83,6 +83,12 @@ k_rank_compose(const int64_t* __restrict__ src, const int32_t* __restrict__ rel,
             q[k] = qr; q[k + h] = qi;
             acc += qr * b[k] + qi * b[k + h];
         }
+    } else if (score == LEGEND_SCORE_TRANSE_L1) {
+        for (int k = lane; k < d; k += kWave) {       // s + r meets d; d - r meets s
+            const float v = side == LEGEND_CORRUPT_SRC ? a[k] - rp[k] : a[k] + rp[k];
+            q[k] = v;
+            acc -= fabsf(v - b[k]);
+        }
     } else {
         for (int k = lane; k < d; k += kWave) {
             const float v = score == LEGEND_SCORE_DISTMULT ? a[k] * rp[k] : a[k];
@@ -234,6 +240,89 @@ k_rank(const float* __restrict__ Q, const float* __restrict__ f, const int32_t* 
     }
 }
 
+// The same counts for the translational score -|q - c|_1: no matrix product.  A lane keeps one
+// candidate row in registers (dim <= 128) and meets the 64 q rows of the tile one after the other
+// (LDS broadcast reads); the comparisons of a row against 64 candidates are counted by ballot.
+constexpr int kRankTransWaves = 4;
+constexpr int kRankTransMaxD4 = 32;
+
+template <bool ALIGNED>
+__global__ void __launch_bounds__(kRankTransWaves* kWave)
+k_rank_trans(const float* __restrict__ Q, const float* __restrict__ f, const int32_t* __restrict__ true_id, int64_t m,
+             const int64_t* __restrict__ cand, int64_t n_cand, int64_t cand_per_wg, float* const* __restrict__ part_emb,
+             int32_t rows_pp, int64_t num_nodes, int32_t d, int32_t* __restrict__ greater, int32_t* __restrict__ equal,
+             uint32_t* __restrict__ err_flag) {
+    extern __shared__ __align__(16) float lds[];
+    const int dp = rank_dpad(d);
+    const int stride = rank_stride(d);
+    float* q_s = lds;
+    float* f_s = q_s + kRankRows * stride;
+    int32_t* t_s = reinterpret_cast<int32_t*>(f_s + kRankRows);
+    int32_t* cnt_s = t_s + kRankRows;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * kRankRows;
+    for (int idx = tid; idx < kRankRows * (dp / 4); idx += kRankTransWaves * kWave) {
+        const int r = idx / (dp / 4), k4 = idx % (dp / 4);
+        *reinterpret_cast<float4*>(q_s + r * stride + 4 * k4) =
+            *reinterpret_cast<const float4*>(Q + (row0 + r) * dp + 4 * k4);
+    }
+    if (tid < kRankRows) {
+        f_s[tid] = f[row0 + tid];
+        t_s[tid] = true_id[row0 + tid];
+        cnt_s[2 * tid] = 0;
+        cnt_s[2 * tid + 1] = 0;
+    }
+    __syncthreads();
+    const int64_t c_lo = (int64_t)blockIdx.y * cand_per_wg;
+    const int64_t c_hi = c_lo + cand_per_wg < n_cand ? c_lo + cand_per_wg : n_cand;
+    const int d4 = (d + 3) >> 2;
+    const int nrows = (int)(m - row0 < kRankRows ? m - row0 : kRankRows);
+    for (int64_t cb = c_lo + kWave * w; cb < c_hi; cb += kWave * kRankTransWaves) {
+        const int64_t j = cb + lane;
+        int64_t cid = -1;
+        const float* row = nullptr;
+        if (j < c_hi) {
+            cid = cand ? cand[j] : j;
+            if (cid < 0 || cid >= num_nodes) {
+                atomicOr(err_flag, 1u);
+                cid = -1;
+            } else {
+                const float* base = part_emb[cid / rows_pp];
+                if (!base) { atomicOr(err_flag, 2u); cid = -1; }
+                else row = base + (cid % rows_pp) * d;
+            }
+        }
+        float4 cr[kRankTransMaxD4];
+#pragma unroll
+        for (int j4 = 0; j4 < kRankTransMaxD4; ++j4)
+            cr[j4] = j4 < d4 ? cand_load4<ALIGNED>(row, 4 * j4, d) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int32_t cid32 = (int32_t)cid;
+        for (int r = 0; r < nrows; ++r) {
+            const float* qr = q_s + r * stride;
+            float s = 0.f;
+#pragma unroll
+            for (int j4 = 0; j4 < kRankTransMaxD4; ++j4) {
+                if (j4 < d4) {
+                    const float4 q4 = *reinterpret_cast<const float4*>(qr + 4 * j4);
+                    s += (fabsf(q4.x - cr[j4].x) + fabsf(q4.y - cr[j4].y)) + (fabsf(q4.z - cr[j4].z) + fabsf(q4.w - cr[j4].w));
+                }
+            }
+            const float S = -s, fv = f_s[r];
+            const bool counted = cid >= 0 && cid32 != t_s[r];
+            const unsigned long long gtm = __ballot(counted && S > fv), eqm = __ballot(counted && S == fv);
+            if (lane == 0) {
+                if (gtm) atomicAdd(&cnt_s[2 * r], __popcll(gtm));
+                if (eqm) atomicAdd(&cnt_s[2 * r + 1], __popcll(eqm));
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < kRankRows && row0 + tid < m) {
+        if (cnt_s[2 * tid]) atomicAdd(&greater[row0 + tid], cnt_s[2 * tid]);
+        if (cnt_s[2 * tid + 1]) atomicAdd(&equal[row0 + tid], cnt_s[2 * tid + 1]);
+    }
+}
+
 // rank = 1 + greater + equal / 2;  sums of 1/rank and of the hit indicators in a fixed order
 __global__ void __launch_bounds__(256)
 k_rank_metrics(const int32_t* __restrict__ greater, const int32_t* __restrict__ equal, int64_t m,
@@ -275,6 +364,34 @@ hipError_t launch_rank(hipStream_t st, const int64_t* src, const int32_t* rel, c
     if (e != hipSuccess) return e;
     if (n_cand > 0) {
         const int64_t tiles = m_pad / kRankRows;
+        const bool aligned = dim % 4 == 0;
+        const size_t lds = sizeof(float) * ((size_t)kRankRows * rank_stride(dim) + kRankRows) + sizeof(int32_t) * 3 * kRankRows;
+        if (score == LEGEND_SCORE_TRANSE_L1) {
+            if (dim > 4 * kRankTransMaxD4) return hipErrorInvalidValue;
+            const int64_t step = kWave * kRankTransWaves;
+            int64_t shares = (4096 + tiles - 1) / tiles;
+            const int64_t max_shares = (n_cand + step - 1) / step;
+            if (shares > max_shares) shares = max_shares;
+            if (shares < 1) shares = 1;
+            if (shares > 65535) shares = 65535;
+            int64_t per = (n_cand + shares - 1) / shares;
+            per = (per + step - 1) / step * step;
+            shares = (n_cand + per - 1) / per;
+            const void* fn = aligned ? reinterpret_cast<const void*>(&k_rank_trans<true>) : reinterpret_cast<const void*>(&k_rank_trans<false>);
+            e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            dim3 grid((unsigned)tiles, (unsigned)shares), block(kRankTransWaves * kWave);
+            if (aligned)
+                hipLaunchKernelGGL(k_rank_trans<true>, grid, block, lds, st, Q, f, true_id, m, cand, n_cand, per, part_emb,
+                                   rows_per_partition, num_nodes, dim, greater, equal, err_flag);
+            else
+                hipLaunchKernelGGL(k_rank_trans<false>, grid, block, lds, st, Q, f, true_id, m, cand, n_cand, per, part_emb,
+                                   rows_per_partition, num_nodes, dim, greater, equal, err_flag);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(k_rank_metrics, dim3(1), dim3(256), 0, st, greater, equal, m, metrics);
+            return hipGetLastError();
+        }
         // enough workgroups to fill the chip a few times over, each with at least four blocks per wave
         const int64_t min_share = 16 * kRankWaves * 4;
         int64_t shares = (4096 + tiles - 1) / tiles;
@@ -285,8 +402,6 @@ hipError_t launch_rank(hipStream_t st, const int64_t* src, const int32_t* rel, c
         int64_t per = (n_cand + shares - 1) / shares;
         per = (per + 16 * kRankWaves - 1) / (16 * kRankWaves) * (16 * kRankWaves);
         shares = (n_cand + per - 1) / per;
-        const size_t lds = sizeof(float) * ((size_t)kRankRows * rank_stride(dim) + kRankRows) + sizeof(int32_t) * 3 * kRankRows;
-        const bool aligned = dim % 4 == 0;
         const void* fn = aligned ? reinterpret_cast<const void*>(&k_rank<true>) : reinterpret_cast<const void*>(&k_rank<false>);
         e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;

@@ -1016,8 +1016,6 @@ int legend_rank_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, con
     if (side != LEGEND_CORRUPT_DST && side != LEGEND_CORRUPT_SRC)
         return fail(LEGEND_E_INVAL, "side must be LEGEND_CORRUPT_DST or LEGEND_CORRUPT_SRC");
     if (c->V > 0x7fffffffll) return fail(LEGEND_E_INVAL, "ranking needs num_nodes < 2^31");
-    if (c->cfg.score == LEGEND_SCORE_TRANSE_L1)
-        return fail(LEGEND_E_INVAL, "ranking is implemented for the product scores (Dot, DistMult, ComplEx)");
     if (metrics) *metrics = legend_rank_metrics{};
     if (m == 0) return LEGEND_OK;
     if (!src || !dst) return fail(LEGEND_E_INVAL, "NULL argument");

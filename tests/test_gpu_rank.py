@@ -43,7 +43,8 @@ def _check_metrics(greater, equal, mt):
 
 @pytest.mark.parametrize("score,d,side", [
     (model.DOT, 20, DST), (model.DOT, 100, SRC), (model.DISTMULT, 36, DST), (model.DISTMULT, 30, SRC),
-    (model.COMPLEX, 100, DST), (model.COMPLEX, 34, SRC), (model.DISTMULT, 400, DST), (model.COMPLEX, 150, SRC)])
+    (model.COMPLEX, 100, DST), (model.COMPLEX, 34, SRC), (model.DISTMULT, 400, DST), (model.COMPLEX, 150, SRC),
+    (model.TRANSE, 100, DST), (model.TRANSE, 30, SRC), (model.TRANSE, 128, SRC)])
 def test_exact_counts_on_integer_embeddings(score, d, side):
     rng = np.random.default_rng(100 * score + d + side)
     V, n, nrel, m = 3_001, 2, 7, 150
@@ -78,12 +79,15 @@ def _band(score, node, rel, src, r, dst, side):
     E = node.astype(np.float64)
     R = rel.astype(np.float64)
     stay = E[src] if side == DST else E[dst]
+    if score == model.TRANSE:       # a sum of dim distances: 1e-5 of the sizes of its operands
+        return 1e-5 * (np.abs(stay).sum(axis=1) + np.abs(R[r]).sum(axis=1) + np.abs(E).sum(axis=1).max())
     q = np.abs(stay) if score == model.DOT else model.abs_compose(score, stay, R[r])
     return 1e-5 * np.linalg.norm(q, axis=1) * np.linalg.norm(E, axis=1).max()
 
 
 @pytest.mark.parametrize("score,d,side,m", [(model.DOT, 100, DST, 130), (model.COMPLEX, 100, SRC, 64),
-                                             (model.DISTMULT, 400, DST, 70), (model.COMPLEX, 50, DST, 1)])
+                                             (model.DISTMULT, 400, DST, 70), (model.COMPLEX, 50, DST, 1),
+                                             (model.TRANSE, 64, DST, 70), (model.TRANSE, 100, SRC, 130)])
 def test_counts_within_the_fp32_band_on_real_embeddings(score, d, side, m):
     rng = np.random.default_rng(7 * score + d + side)
     V, n, nrel = 5_003, 4, 11
