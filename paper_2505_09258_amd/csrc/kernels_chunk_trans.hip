@@ -21,8 +21,21 @@ constexpr int kTNeg = 64;           // negatives per tile
 constexpr int kTWS = 68;            // row stride of the transposed W tile
 constexpr int kTThreads = 256;
 
+// w * sign(diff) for w >= 0, sign(0) = 0
 __device__ inline float sign_times(float diff, float w) {
-    return diff > 0.f ? w : (diff < 0.f ? -w : 0.f);
+    const float t = __builtin_copysignf(w, diff);
+    return diff == 0.f ? 0.f : t;
+}
+// Sum over the eight lanes 8j..8j+7 of a wave, valid in lane 8j (and 8j+7): data-parallel
+// primitives within a row of 16 lanes (two quad permutations, then the mirror of each half row).
+__device__ inline float sum8(float v) {
+    int x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    x = __float_as_int(v);
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    return v;
 }
 __device__ inline float l1_of(float4 a, float4 b) {
     return (fabsf(a.x - b.x) + fabsf(a.y - b.y)) + (fabsf(a.z - b.z) + fabsf(a.w - b.w));
@@ -181,9 +194,11 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
     }
 
     // ---- sweep 2: W, G_q and G_neg --------------------------------------------------------------
-    // gradient pass: 8 lanes (rb = 0..7, eight rows each) share the four columns 4jg..4jg+3
+    // gradient pass: 8 lanes (rb = 0..7) share the four columns 4jg..4jg+3; lane rb owns rows
+    // rb, rb + 8, ..., so that the row groups past the chunk's last row drop out for all lanes at once
     const int rb = tid & 7, jg = tid >> 3;
     const bool gactive = jg < d4;
+    const int imax = (nrows + 7) >> 3;
     float4 accq[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) accq[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -216,14 +231,19 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
                     }
                     w4[a] = w;
                 }
-                *reinterpret_cast<float4*>(Wt + (tx + 16 * b) * kTWS + 4 * ty) = make_float4(w4[0], w4[1], w4[2], w4[3]);
+                // row r sits at position (r % 8) * 8 + r / 8: the eight rows of a lane of the gradient pass are adjacent
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const int r = 4 * ty + a;
+                    Wt[(tx + 16 * b) * kTWS + (r & 7) * 8 + (r >> 3)] = w4[a];
+                }
             }
         }
         __syncthreads();
         if (gactive) {
             float4 q[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) q[i] = lds4(Qs + (8 * rb + i) * QS + 4 * jg);
+            for (int i = 0; i < 8; ++i) q[i] = lds4(Qs + (rb + 8 * i) * QS + 4 * jg);
             for (int k = 0; k < kTNeg; ++k) {
                 const float4 n4 = lds4(Ns + k * QS + 4 * jg);
                 const float4 wa = lds4(Wt + k * kTWS + 8 * rb), wb = lds4(Wt + k * kTWS + 8 * rb + 4);
@@ -231,20 +251,19 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
                 float4 pn = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    float tv;
-                    tv = sign_times(q[i].x - n4.x, w8[i]); accq[i].x -= tv; pn.x += tv;
-                    tv = sign_times(q[i].y - n4.y, w8[i]); accq[i].y -= tv; pn.y += tv;
-                    tv = sign_times(q[i].z - n4.z, w8[i]); accq[i].z -= tv; pn.z += tv;
-                    tv = sign_times(q[i].w - n4.w, w8[i]); accq[i].w -= tv; pn.w += tv;
+                    if (i < imax) {
+                        float tv;
+                        tv = sign_times(q[i].x - n4.x, w8[i]); accq[i].x -= tv; pn.x += tv;
+                        tv = sign_times(q[i].y - n4.y, w8[i]); accq[i].y -= tv; pn.y += tv;
+                        tv = sign_times(q[i].z - n4.z, w8[i]); accq[i].z -= tv; pn.z += tv;
+                        tv = sign_times(q[i].w - n4.w, w8[i]); accq[i].w -= tv; pn.w += tv;
+                    }
                 }
-                // rows 8rb..8rb+7 of every lane of the group: eight lanes, fixed order
-#pragma unroll
-                for (int mask = 1; mask < 8; mask <<= 1) {
-                    pn.x += wave_shfl_xor(pn.x, mask);
-                    pn.y += wave_shfl_xor(pn.y, mask);
-                    pn.z += wave_shfl_xor(pn.z, mask);
-                    pn.w += wave_shfl_xor(pn.w, mask);
-                }
+                // the rows of the eight lanes of the group, in a fixed order
+                pn.x = sum8(pn.x);
+                pn.y = sum8(pn.y);
+                pn.z = sum8(pn.z);
+                pn.w = sum8(pn.w);
                 if (rb == 0 && n0 + k < N) {
                     const int col = 4 * jg;
                     if (atomic) {
@@ -274,7 +293,7 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
     float* Gs = Ns;
     if (gactive) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(Gs + (8 * rb + i) * QS + 4 * jg) = accq[i];
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<float4*>(Gs + (rb + 8 * i) * QS + 4 * jg) = accq[i];
     }
     if (LOSS == LEGEND_LOSS_LOGISTIC) {
         for (int off = kWave / 2; off > 0; off >>= 1) neg_loss += __shfl_down(neg_loss, off, kWave);
@@ -308,7 +327,7 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
                 gr = bp.G_rel + (int64_t)eb[prow * 3 + 1] * d;
             }
             for (int k = ppart; k < d; k += 4) {
-                const float sp = sign_times(Qs[prow * QS + k] - y[k], a);       // a * sign(q - y)
+                const float sp = a * sign_times(Qs[prow * QS + k] - y[k], 1.f);  // a * sign(q - y)
                 const float gq = Gs[prow * QS + k] - sp;
                 emit(gy + k, sp);
                 emit(gx + k, gq);
