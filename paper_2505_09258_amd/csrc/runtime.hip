@@ -768,8 +768,10 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             HIP_TRY(c, launch_chunks(c->compute, g, bp, ws, true));
         }
         // the sum of the workgroups' loss terms is off the critical path when the second stream is in use
-        const bool loss_aside = ahead && !bp.atomic_mode;
-        if (!loss_aside) {
+        // (a batch of a few thousand gradient rows is bound by launch latency: it stays on one stream,
+        // where a kernel follows the other without a hop between streams)
+        const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536;
+        if (!aside) {
             ProfScope ps(c, KC_MISC);
             HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, ws));
         }
@@ -791,8 +793,8 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         } else {
             // the table rows with many gradient rows are disjoint from the others: their two-level
             // sums run on a stream of their own next to the main update kernel
-            hipStream_t ls = ahead ? c->aux2 : c->compute;
-            if (ahead) {
+            hipStream_t ls = aside ? c->aux2 : c->compute;
+            if (aside) {
                 HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
                 HIP_TRY(c, hipStreamWaitEvent(c->aux2, c->ev_chunk_done, 0));
                 ProfScope ps(c, KC_MISC, c->aux2);
@@ -802,12 +804,12 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
                 ProfScope ps(c, KC_UPDATE_LONG, ls);
                 HIP_TRY(c, launch_update(ls, g, bp, ws, ws.vals[sorted_of[cur]], true));
             }
-            if (ahead) HIP_TRY(c, hipEventRecord(c->ev_long_done, c->aux2));
+            if (aside) HIP_TRY(c, hipEventRecord(c->ev_long_done, c->aux2));
             {
                 ProfScope ps(c, KC_UPDATE);
                 HIP_TRY(c, launch_update(c->compute, g, bp, ws, ws.vals[sorted_of[cur]], false));
             }
-            if (ahead) HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_long_done, 0));
+            if (aside) HIP_TRY(c, hipStreamWaitEvent(c->compute, c->ev_long_done, 0));
         }
         if (ahead) HIP_TRY(c, hipEventRecord(c->ev_updated[cur], c->compute));
         c->batches_done += 1;
