@@ -54,6 +54,16 @@ __device__ inline void sum_rows(const float* __restrict__ grad, const uint32_t* 
             acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
         }
     } else {
+                const uint32_t o0 = sorted_vals[p], o1 = sorted_vals[p + 1], o2 = sorted_vals[p + 2];
+                const float4 v0 = *reinterpret_cast<const float4*>(grad + (int64_t)o0 * d + c0);
+                const float4 v1 = *reinterpret_cast<const float4*>(grad + (int64_t)o1 * d + c0);
+                const float4 v2 = *reinterpret_cast<const float4*>(grad + (int64_t)o2 * d + c0);
+                acc[0] += (double)v0.x; acc[1] += (double)v0.y; acc[2] += (double)v0.z; acc[3] += (double)v0.w;
+                acc[0] += (double)v1.x; acc[1] += (double)v1.y; acc[2] += (double)v1.z; acc[3] += (double)v1.w;
+                acc[0] += (double)v2.x; acc[1] += (double)v2.y; acc[2] += (double)v2.z; acc[3] += (double)v2.w;
+            }
+        }
+    } else {
         for (; p < hi; ++p) {
             const float* gp = grad + (int64_t)sorted_vals[p] * d + c0;
             acc[0] += (double)gp[0];
@@ -115,6 +125,28 @@ k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uni
     for (uint32_t u = blockIdx.x * groups_per_block + gl; u < n_unique; u += gridDim.x * groups_per_block) {
         const uint32_t lo = seg_start[u], hi = seg_start[u + 1];
         if (hi - lo > (uint32_t)kLongLen) continue;
+        if (vec4 && d <= 4 * LPR) {
+            // one pass over the row: the table row's loads are issued before the gradient rows are
+            // summed, so that the two round trips to memory overlap
+            if (c0 < d) {
+                const uint32_t key = uniq_keys[u];
+                const int t = table_of_key(tb, key);
+                const int64_t row = (int64_t)(key - tb.key_base[t]);
+                float* ep = tb.E[t] + row * d + c0;
+                float* sp = tb.S[t] + row * d + c0;
+                float4 th = *reinterpret_cast<const float4*>(ep);
+                float4 st = *reinterpret_cast<const float4*>(sp);
+                double acc[4] = {0.0, 0.0, 0.0, 0.0};
+                sum_rows(grad, sorted_vals, lo, hi, d, c0, true, acc);
+                adagrad_elem((float)acc[0], th.x, st.x, lr, eps);
+                adagrad_elem((float)acc[1], th.y, st.y, lr, eps);
+                adagrad_elem((float)acc[2], th.z, st.z, lr, eps);
+                adagrad_elem((float)acc[3], th.w, st.w, lr, eps);
+                *reinterpret_cast<float4*>(ep) = th;
+                *reinterpret_cast<float4*>(sp) = st;
+            }
+            continue;
+        }
         for (int cc = c0; cc < d; cc += 4 * LPR) {     // rows wider than 4*LPR floats take several passes
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
             sum_rows(grad, sorted_vals, lo, hi, d, cc, vec4, acc);
