@@ -49,9 +49,26 @@ __device__ inline void sum_rows(const float* __restrict__ grad, const uint32_t* 
             acc[0] += (double)v2.x; acc[1] += (double)v2.y; acc[2] += (double)v2.z; acc[3] += (double)v2.w;
             acc[0] += (double)v3.x; acc[1] += (double)v3.y; acc[2] += (double)v3.z; acc[3] += (double)v3.w;
         }
-        for (; p < hi; ++p) {
-            const float4 v = *reinterpret_cast<const float4*>(grad + (int64_t)sorted_vals[p] * d + c0);
-            acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
+        // one to three rows left (the common case: most table rows get one or two gradient rows):
+        // their loads go out together as well, the sums stay in order
+        const uint32_t n = hi - p;
+        if (n == 1) {
+            const float4 v0 = *reinterpret_cast<const float4*>(grad + (int64_t)sorted_vals[p] * d + c0);
+            acc[0] += (double)v0.x; acc[1] += (double)v0.y; acc[2] += (double)v0.z; acc[3] += (double)v0.w;
+        } else if (n == 2) {
+            const uint32_t o0 = sorted_vals[p], o1 = sorted_vals[p + 1];
+            const float4 v0 = *reinterpret_cast<const float4*>(grad + (int64_t)o0 * d + c0);
+            const float4 v1 = *reinterpret_cast<const float4*>(grad + (int64_t)o1 * d + c0);
+            acc[0] += (double)v0.x; acc[1] += (double)v0.y; acc[2] += (double)v0.z; acc[3] += (double)v0.w;
+            acc[0] += (double)v1.x; acc[1] += (double)v1.y; acc[2] += (double)v1.z; acc[3] += (double)v1.w;
+        } else if (n == 3) {
+            const uint32_t o0 = sorted_vals[p], o1 = sorted_vals[p + 1], o2 = sorted_vals[p + 2];
+            const float4 v0 = *reinterpret_cast<const float4*>(grad + (int64_t)o0 * d + c0);
+            const float4 v1 = *reinterpret_cast<const float4*>(grad + (int64_t)o1 * d + c0);
+            const float4 v2 = *reinterpret_cast<const float4*>(grad + (int64_t)o2 * d + c0);
+            acc[0] += (double)v0.x; acc[1] += (double)v0.y; acc[2] += (double)v0.z; acc[3] += (double)v0.w;
+            acc[0] += (double)v1.x; acc[1] += (double)v1.y; acc[2] += (double)v1.z; acc[3] += (double)v1.w;
+            acc[0] += (double)v2.x; acc[1] += (double)v2.y; acc[2] += (double)v2.z; acc[3] += (double)v2.w;
         }
     } else {
         for (; p < hi; ++p) {
