@@ -273,9 +273,14 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     float* Ng = Ns + grp * (kFTile * QS);
     float* Wg = Ws + grp * (kFRow * kFWS);
     float4 pf[STEPS];
-    const int grow_lane = lane >> 5;
-    const int gc0 = (lane & 31) * 4;
-    const int gcol_ld = gc0 < d ? gc0 : 0;
+    // The lane's share of a gathered row is recomputed from the lane number wherever it is needed (two
+    // instructions the compiler may not hoist): kept live across the kernel it ends up in scratch
+    // memory, and its reload then sits in front of every tile's gather.
+    auto lane_now = [&]() __attribute__((always_inline)) {
+        int x;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(x));
+        return x;
+    };
     typedef __attribute__((address_space(3))) const int32_t* lds_ids_t;
     // Column k of tile t is negative k * ntiles + t: every tile is an even sample of the chunk's
     // negatives (uniform and degree-weighted ones alike), so the row maxima of the first tile
@@ -283,6 +288,9 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     const int ntiles = (N + kFTile - 1) / kFTile;
     auto neg_of = [&](int t, int k) { return k * ntiles + t; };
     auto gather_issue = [&](int t) __attribute__((always_inline)) {
+        const int ln = lane_now();
+        const int grow_lane = ln >> 5;
+        const int gcol_ld = (ln & 31) * 4 < d ? (ln & 31) * 4 : 0;
         int32_t idv[STEPS];
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) idv[s] = ((lds_ids_t)ids_s)[min(neg_of(t, wl * 16 + s * 2 + grow_lane), N - 1)];
@@ -290,6 +298,9 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         for (int s = 0; s < STEPS; ++s) pf[s] = *reinterpret_cast<const float4*>(En + (int64_t)idv[s] * d + gcol_ld);
     };
     auto gather_commit = [&](int t) __attribute__((always_inline)) {
+        const int ln = lane_now();
+        const int grow_lane = ln >> 5;
+        const int gc0 = (ln & 31) * 4;
         if (neg_of(t, kFTile - 1) >= N) {     // columns past the last negative are zero rows
 #pragma unroll
             for (int s = 0; s < STEPS; ++s)
