@@ -541,7 +541,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     for (int ww = 0; ww < kFWaves; ++ww) bad |= flag_s[ww] != 0u;
     };
     sweep_and_sums(std::false_type{});
-    if (bad && retry_in_place) {
+    if (__builtin_expect(bad && retry_in_place, 0)) {
     // ---- exact row maxima: scores only, every wave on its own gathered rows, no workgroup barrier
         if (tid == 0) atomicAdd(redo_total, 1ull);
         f32x4 mxv[4];
