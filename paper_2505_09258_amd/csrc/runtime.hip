@@ -516,7 +516,6 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     else { INIT_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking)); c->own_copy = true; }
     INIT_TRY(hipEventCreateWithFlags(&c->ev_fence, hipEventDisableTiming));
     INIT_TRY(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
-    INIT_TRY(hipStreamCreateWithFlags(&c->aux2, hipStreamNonBlocking));
     INIT_TRY(hipEventCreateWithFlags(&c->ev_chunk_done, hipEventDisableTiming));
     INIT_TRY(hipEventCreateWithFlags(&c->ev_long_done, hipEventDisableTiming));
     INIT_TRY(hipEventCreateWithFlags(&c->ev_start, hipEventDisableTiming));
@@ -541,6 +540,10 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         (void)half;
     }
     INIT_TRY(hipStreamCreateWithFlags(&c->copy_out, hipStreamNonBlocking));
+    // A process has four hardware queues; a fifth stream shares one with another, and a kernel that
+    // shares a queue with a multi-gigabyte partition transfer waits for it.  With a staged buffer the
+    // two copy streams are busy and the third compute-side stream stays unused (and is not created).
+    if (c->nslots == c->cap) INIT_TRY(hipStreamCreateWithFlags(&c->aux2, hipStreamNonBlocking));
     for (int s = 0; s < c->nslots; ++s) {
         INIT_RC(dev_alloc(c, &c->slot_mem[s], c->part_floats));
         INIT_TRY(hipEventCreateWithFlags(&c->slot_ready[s], hipEventDisableTiming));
@@ -658,7 +661,7 @@ int legend_sync(legend_ctx* c) {
     int rc = check_ctx(c);
     if (rc) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->compute));
-    HIP_TRY(c, hipStreamSynchronize(c->aux2));
+    if (c->aux2) HIP_TRY(c, hipStreamSynchronize(c->aux2));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
     HIP_TRY(c, hipStreamSynchronize(c->copy_out));
     return LEGEND_OK;
@@ -770,7 +773,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         // the sum of the workgroups' loss terms is off the critical path when the second stream is in use
         // (a batch of a few thousand gradient rows is bound by launch latency: it stays on one stream,
         // where a kernel follows the other without a hop between streams)
-        const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536;
+        const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536 && c->aux2 != nullptr;
         if (!aside) {
             ProfScope ps(c, KC_MISC);
             HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, ws));
