@@ -408,6 +408,21 @@ def test_native_epoch_driver_matches_manual_order_and_oracle():
     # prefetching changes when copies run, not what is computed
     assert results[1][0]["loss_sum"] == st["loss_sum"]
     assert np.array_equal(results[1][1], E) and np.array_equal(results[1][2], S)
+    # neither does keeping every partition resident, nor handing over the edge lists in device memory
+    import torch
+    dev = {k: torch.from_numpy(v).cuda() for k, v in buckets.items()}
+    cfg = L.make_config(num_nodes=w.num_nodes, dim=w.dim, num_partitions=7, buffer_capacity=7,
+                        batch_size=w.batch_size, chunk_size=w.chunk_size, num_negs=w.num_negs,
+                        num_degree_negs=w.num_degree_negs, seed=2)
+    ctx = L.legend_init_partitions(cfg, node, None)
+    try:
+        st7 = L.legend_train_epoch(ctx, 7, {k: (t.data_ptr(), t.shape[0]) for k, t in dev.items()},
+                                   edges_mem=L.MEM_DEVICE, epoch=4)
+        assert st7["swaps"] == 7 and st7["buffer_states"] == 1 and st7["loss_sum"] == st["loss_sum"]
+        assert np.array_equal(L.legend_read_embeddings(ctx, L.TABLE_NODE_EMB, None, w.num_nodes, w.dim), E)
+        assert np.array_equal(L.legend_read_embeddings(ctx, L.TABLE_NODE_STATE, None, w.num_nodes, w.dim), S)
+    finally:
+        L.legend_destroy(ctx)
     run = OracleRun(OracleConfig.from_workload(w, seed=2), node, None)
     for (ev, ld, before, during) in oorder.iteration_order(states, 7):
         for (i, j) in before + during:
