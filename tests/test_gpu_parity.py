@@ -492,3 +492,24 @@ def test_device_resident_edges_give_the_same_result():
             L.legend_destroy(ctx)
     assert out[0][0] == out[1][0]
     assert np.array_equal(out[0][1], out[1][1])          # deterministic mode: bit-identical reruns
+
+
+def test_stream_layout_does_not_change_results(monkeypatch):
+    """Batches large enough for the three-stream layout (index side one batch ahead, long rows beside the
+    main update kernel) against the same batches with every kernel on one stream: bit-identical tables."""
+    c = _case("streams", DOT, SOFTMAX, DST, 30_000, 0, 100, 2, 0, 1, 5_000, 50, 1_000, 500, 22_000, 0.1)
+    node, rel, edges = _inputs(c)
+    outs = []
+    for serial in ("0", "1"):
+        monkeypatch.setenv("LEGEND_SERIAL_SORT", serial)
+        L, ctx = _gpu_ctx(c, node, rel)
+        try:
+            for p in (0, 1):
+                L.legend_swap_partition(ctx, -1, p)
+            st = L.legend_train_bucket(ctx, 0, 1, edges, epoch=2)
+            outs.append((st["loss_sum"], _read_all(L, ctx, c)))
+        finally:
+            L.legend_destroy(ctx)
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert np.array_equal(a, b)
