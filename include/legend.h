@@ -262,13 +262,17 @@ int legend_debug_batch_indices(legend_ctx* ctx, int32_t src_part, int32_t dst_pa
 int legend_plan_order(int32_t n, int32_t* states, int32_t state_capacity, int32_t* num_states,
                       int32_t* buckets, int32_t* state_begin, int32_t* state_overlap);
 
-/* Wait until everything enqueued on both streams has finished. */
+/* Wait until everything enqueued on the context's streams has finished. */
 int legend_sync(legend_ctx* ctx);
 
 /*
- * Per-kernel device timing with HIP events on the compute stream.
+ * Per-kernel-class device timing with HIP events on the stream each class runs
+ * on (the index side of a batch is built one batch ahead on a stream of its own,
+ * the update of rows with many gradient rows next to the main update kernel on
+ * another: spans of different classes overlap in time, and a span contains the
+ * wait for compute units that other streams hold).
  * legend_profile_enable: mask bit k switches timing of kernel class k on
- * (0 switches all off).  legend_profile_read waits for the stream, returns the
+ * (0 switches all off).  legend_profile_read waits for the work, returns the
  * accumulated milliseconds and launch counts per class since the last read and
  * clears them; names of the classes come from legend_profile_name (NULL past the
  * last class).
