@@ -43,6 +43,8 @@ CASES = [
     _case("distmult_d256_softmax_pos", DISTMULT, SOFTMAX_POS, SRC, 2_000, 5, 256, 1, 0, 0, 200, 40, 70, 0, 450, 0.2),
     # a wide dimension that is not a multiple of four (rows only 8-byte aligned); chunks of 120 rows take two row tiles
     _case("complex_d150_both", COMPLEX, SOFTMAX, BOTH, 2_500, 6, 150, 2, 1, 0, 300, 120, 90, 20, 700, 0.2),
+    # d = 100 with chunks of 100 edges: the single-sweep kernel with two 50-row tiles per chunk (the dimension sweep's shape)
+    _case("distmult_d100_two_row_tiles", DISTMULT, SOFTMAX, BOTH, 6_000, 7, 100, 2, 0, 1, 700, 100, 300, 30, 1_500, 0.3),
     # translational score (vector-ALU kernel): both sides, a dimension that is no multiple of four, two row tiles per chunk
     _case("transe_d100_both", TRANSE, SOFTMAX, BOTH, 5_000, 9, 100, 2, 0, 1, 600, 50, 200, 40, 1_300, 0.1),
     _case("transe_d30_logistic_src", TRANSE, LOGISTIC, SRC, 2_000, 5, 30, 2, 1, 1, 200, 33, 65, 10, 450, 0.2),
