@@ -111,7 +111,7 @@ def side_loss(loss, f, S, neg_weight):
         return -f + lse, -1.0 + (ef / z)[:, 0], ex / z
     # logistic: softplus(-f) + w * sum_k softplus(S_k)
     sp = lambda x: np.logaddexp(0.0, x)
-    sig = lambda x: 0.5 * (1.0 + np.tanh(0.5 * x))
+    sig = lambda x: np.exp(-np.logaddexp(0.0, -x))       # 1 / (1 + e^-x), accurate for any x (e^x for x << 0)
     l = sp(-f) + neg_weight * sp(S).sum(axis=1)
     return l, -sig(-f), neg_weight * sig(S)
 

@@ -101,6 +101,19 @@ def test_logistic_closed_forms():
     assert abs(l[0] - (np.log(2) + np.log(2))) < 1e-14
 
 
+def test_logistic_coefficients_keep_their_precision_for_very_negative_scores():
+    # sigmoid(x) = e^x (1 - e^x + ...) for x << 0: a distance-based score of -50 must not turn into weight 0
+    f = np.array([-60.0])
+    S = np.array([[-50.0, -37.0, -20.0, 0.0]])
+    l, a, W = model.side_loss(model.LOGISTIC, f, S, 0.5)
+    want = 0.5 * np.exp(S) / (1.0 + np.exp(S))
+    np.testing.assert_allclose(W, want, rtol=1e-14)
+    assert W[0, 0] > 0 and abs(W[0, 0] / (0.5 * np.exp(-50.0)) - 1.0) < 1e-15
+    np.testing.assert_allclose(a, -1.0 / (1.0 + np.exp(-60.0)), rtol=1e-15)
+    # softplus(60) + 0.5 * sum softplus(S)
+    np.testing.assert_allclose(l, 60.0 + np.log1p(np.exp(-60.0)) + 0.5 * np.log1p(np.exp(S)).sum(), rtol=1e-15)
+
+
 def test_softmax_with_positive_closed_forms_and_library_cross_entropy():
     # one negative scoring exactly like the positive: two equal logits
     l, a, W = model.side_loss(model.SOFTMAX_POS, np.array([0.3]), np.array([[0.3]]), 1.0)
