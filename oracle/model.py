@@ -209,11 +209,12 @@ def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, wit
     else:                                                      # q = d - r
         out = dict(loss=l, f=f, S=S, W=W, g_s=g_other, g_r=-g_q, g_d=g_q, g_neg=g_neg)
     if with_magnitudes:
-        # every term is +-W_ek; W_ek = exp(S_ek - lse_e) carries the rounding error of S, a sum of dim
-        # distances of total size |S| (a few roundoffs times |S| in fp32, where the callers' unit
-        # of error is a few dozen roundoffs): a term's error scale is W_ek (1 + max_k |S_ek| / 8)
+        # every term is +-W_ek; W_ek = exp(S_ek - lse_e) carries the absolute rounding error of S, a sum
+        # of dim same-sign distances of total size |S|: up to dim/4 sequential fp32 additions of
+        # partial sums of that size (where the callers' unit of error is 32 roundoffs): a term's
+        # error scale is W_ek (1 + max_k |S_ek| dim / 128)
         nz = np.abs(sg)
-        Wm = np.abs(W) * (1.0 + np.abs(S).max(axis=1, keepdims=True) / 8.0)
+        Wm = np.abs(W) * (1.0 + np.abs(S).max(axis=1, keepdims=True) * (q.shape[1] / 128.0))
         m_q = np.abs(a)[:, None] * np.abs(sg_pos) + np.einsum("ck,ckj->cj", Wm, nz)
         m_other = np.abs(a)[:, None] * np.abs(sg_pos)
         out.update(m_neg=np.einsum("ck,ckj->kj", Wm, nz), m_r=m_q,

@@ -314,6 +314,9 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                 float lse = mx + logf(sum);
                 if (bp.softmax_with_pos) {    // the positive score joins the log-sum-exp
                     const float f = pos_s[srow];
+                    // x = lse over the negatives - f is kept: the loss term is softplus(x) and dL/df is
+                    // -sigmoid(x), both accurate where the positive dominates (lse' - f itself cancels there)
+                    rowloss_s[srow] = lse - f;
                     const float hi = fmaxf(lse, f), lo = fminf(lse, f);
                     lse = hi + log1pf(expf(lo - hi));
                 }
@@ -496,8 +499,14 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             const float f = pos_s[prow];
             float a;
             if (LOSS == LEGEND_LOSS_SOFTMAX) {
-                row_loss = lse_s[prow] - f;
-                a = bp.softmax_with_pos ? expf(-row_loss) - 1.f : -1.f;
+                if (bp.softmax_with_pos) {
+                    const float x = rowloss_s[prow];          // read by the row's four lanes before one of them reuses the slot
+                    row_loss = softplusf(x);
+                    a = -sigmoidf(x);
+                } else {
+                    row_loss = lse_s[prow] - f;
+                    a = -1.f;
+                }
             }
             else { a = -sigmoidf(-f); row_loss = softplusf(-f); }
             const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;

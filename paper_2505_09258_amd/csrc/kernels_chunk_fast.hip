@@ -521,6 +521,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 #pragma unroll
         for (int ww = 0; ww < kFWaves; ++ww) sum += Lw[ww * kFRow + tid];
         const bool live = tid < nrows;
+        const float neg_sum = sum;
         float pos_term = 0.f;
         if (bp.softmax_with_pos && live) {    // Eq. 1 variant: the positive score is one more term of the sum
             const float dpos = f_s[tid] - ref_s[tid];
@@ -533,7 +534,9 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         if (live && !(sum > 1e-30f && sum < 1e36f)) flag_s[8] = 1u;
         scale_s[tid] = live ? 1.f / sum : 0.f;
         logl_s[tid] = live ? logf(sum) : 0.f;
-        mx_s[tid] = live ? pos_term / sum - 1.f : 0.f;      // dL/df (the maxima kept here are no longer needed)
+        // dL/df = minus the negatives' share of the sum (-1 as printed; no cancellation where the positive
+        // dominates in the variant that counts it); the maxima kept here are no longer needed
+        mx_s[tid] = live ? -neg_sum / sum : 0.f;
     }
     __syncthreads();
     bad = flag_s[8] != 0u;

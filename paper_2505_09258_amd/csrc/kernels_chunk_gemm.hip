@@ -290,8 +290,8 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
             float a = -1.f;
             if (bp.softmax_with_pos) {
                 const float pf = expf(f - m);
+                a = -l / (l + pf);            // minus the negatives' share of the sum: no cancellation where the positive dominates
                 l += pf;
-                a = pf / l - 1.f;
             }
             const float il = 1.f / l;
             for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? fast_exp(at(n) - m) * il : 0.f;

@@ -184,6 +184,8 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
                 float mm = m[a], ll = l[a];
                 if (bp.softmax_with_pos) {     // Eq. 1 variant: the positive score is one more term
                     const float f = pos_s[4 * ty + a];
+                    // lse over the negatives - f: the loss term is its softplus and dL/df minus its sigmoid
+                    rowloss_s[4 * ty + a] = mm + logf(ll) - f;
                     const float mn = fmaxf(mm, f);
                     ll = (mm > -INFINITY ? ll * expf(mm - mn) : 0.f) + expf(f - mn);
                     mm = mn;
@@ -310,8 +312,14 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
             const float f = pos_s[prow];
             float a;
             if (LOSS == LEGEND_LOSS_SOFTMAX) {
-                row_loss = lse_s[prow] - f;
-                a = bp.softmax_with_pos ? expf(-row_loss) - 1.f : -1.f;
+                if (bp.softmax_with_pos) {
+                    const float x = rowloss_s[prow];          // read by the row's four lanes before one of them reuses the slot
+                    row_loss = softplusf(x);
+                    a = -sigmoidf(x);
+                } else {
+                    row_loss = lse_s[prow] - f;
+                    a = -1.f;
+                }
             } else {
                 a = -sigmoidf(-f);
                 row_loss = softplusf(-f);
