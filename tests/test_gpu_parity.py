@@ -515,3 +515,36 @@ def test_stream_layout_does_not_change_results(monkeypatch):
     assert outs[0][0] == outs[1][0]
     for a, b in zip(outs[0][1], outs[1][1]):
         assert np.array_equal(a, b)
+
+
+def _random_cases(seed, count):
+    """Seeded random shapes: every score, loss and corruption mode over dimensions on both sides of the
+    kernels' boundaries (multiples of 4 and not, 100, 128 | 132, 400), chunk sizes from 1 to two row tiles,
+    negative counts around the tile size, diagonal and off-diagonal buckets."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for it in range(count):
+        score = int(rng.integers(0, 4))
+        loss = int(rng.integers(0, 3))
+        corrupt = int(rng.integers(0, 3))
+        d = int(rng.choice([6, 20, 32, 50, 64, 100, 100, 100, 128] + ([132, 200, 400] if score != TRANSE else [])))
+        d += d % 2 if score == COMPLEX else 0
+        n = int(rng.integers(1, 4))
+        i, j = int(rng.integers(0, n)), int(rng.integers(0, n))
+        C = int(rng.choice([1, 7, 33, 50, 64, 100, 120]))
+        N = int(rng.choice([1, 5, 63, 64, 65, 130, 300, 1000]))
+        B = int(rng.choice([64, 200, 500, 700]))
+        ndeg = int(rng.integers(0, N + 1)) if rng.random() < 0.5 else 0
+        nrel = 0 if score == DOT else int(rng.integers(1, 12))
+        cases.append(_case(f"random{seed}_{it}", score, loss, corrupt, int(rng.integers(800, 6000)), nrel, d, n, i, j, B, C, N,
+                           ndeg, int(B * rng.uniform(1.1, 2.7)), float(rng.choice([0.1, 0.3]))))
+    return cases
+
+
+_RANDOM_CASES = _random_cases(7, 24)
+
+
+@pytest.mark.parametrize("c", _RANDOM_CASES, ids=[c["name"] for c in _RANDOM_CASES])
+def test_random_shapes_every_batch_matches_oracle(c):
+    test_negative_ids_and_touched_rows_bit_exact(c)
+    test_every_batch_matches_oracle(c)
