@@ -3,10 +3,11 @@
 One batch step from identical tables, compared element by element on every row the batch touches
 (the oracle finishes a full-size batch in seconds), plus bit-exact negative ids / touched-row sets
 and bit-identical untouched rows.  c1: the whole epoch; c2 (the benchmark workload): first batches
-of an off-diagonal and a diagonal bucket; c3: first, second and the partial last batch.  c4 and c5
-share c2's per-batch shape (d = 100, B = 50 000, C = 50, N = 1 000) and differ in table size only;
-their tables do not fit the test's time budget, their scores and corruption modes are covered by
-the scaled cases of test_gpu_parity.py.
+of an off-diagonal and a diagonal bucket; c3: first, second and the partial last batch.  c4 shares
+c2's per-batch shape (d = 100, B = 50 000, C = 50, N = 1 000) and differs in table size only.  c5
+adds ComplEx, 14 824 relations and corruption of both sides to that shape: its full batch runs
+here on a graph with 1/64 of the nodes (the tables of the full one do not fit the test's time
+budget); smaller ComplEx cases are in test_gpu_parity.py.
 """
 
 import numpy as np
@@ -24,7 +25,7 @@ class _Setup:
     def __init__(self, name, seed=5):
         from paper_2505_09258_amd import binding as L
         self.L = L
-        self.w = w = graphs.WORKLOADS[name]
+        self.w = w = graphs.WORKLOADS[name] if isinstance(name, str) else name
         src, rel_ids, dst = graphs.generate_edges(w, seed)
         self.buckets = graphs.bucket_edges(w, src, rel_ids, dst)
         del src, rel_ids, dst
@@ -135,5 +136,18 @@ def test_c3_full_size_batches():
         nb = -(-s.buckets[(0, 0)].shape[0] // s.w.batch_size)
         for b in (0, 1, nb - 1):
             s.check_batch(0, 0, b, check_indices=b != 1)
+    finally:
+        s.close()
+
+
+def test_c5_shape_full_batch():
+    """c5's batch (ComplEx, d = 100, 50 000 edges, both sides corrupted, 2 000 chunk launches of
+    50 x 1 000) on 1/64 of its nodes in 4 partitions."""
+    w = graphs.scaled(graphs.WORKLOADS["c5"], 64, 32, num_partitions=4)
+    s = _Setup(w)
+    try:
+        assert s.buckets[(1, 2)].shape[0] >= 2 * w.batch_size
+        s.check_batch(1, 2, 0)
+        s.check_batch(3, 3, 0, check_indices=False)
     finally:
         s.close()
