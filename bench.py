@@ -25,7 +25,7 @@ VALU_F32_PEAK_TFLOPS = 157.3      # fp32 vector peak: 256 CUs x 64 lanes x 2 (pa
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 # HBM bytes per k_chunk_fast launch from the rocprofv3 counter runs summarised in
 # profiles/c2_hbm_traffic.txt (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB, calibrated on a copy)
-CHUNK_TRAFFIC_BYTES = {"c2": int((303157.6 * 2.0 + 488443.8) * 1024)}
+CHUNK_TRAFFIC_BYTES = {"c2": int((281764.5 * 2.0 + 447782.4) * 1024)}
 
 
 def log(*a):
