@@ -131,6 +131,7 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
     node_mags = [[], []]
     rel_keys, rel_grads, rel_mags = [], [], []
     loss = 0.0
+    loss_mag = 0.0
     want_mags = record is not None
 
     # stage 5: batch computation, chunk by chunk, side by side
@@ -147,6 +148,7 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
                                    rounded=cfg.round_composed)
             loss += float(out["loss"].sum())
             if want_mags:
+                loss_mag += float(out["m_loss"].sum())
                 node_mags[ti].append(out["m_s"]); node_mags[tj].append(out["m_d"])
                 node_mags[neg_slot].append(out["m_neg"])
                 if uses_rel:
@@ -173,6 +175,7 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
             mags[2] = _coalesce(rel_keys, rel_mags)[1]
     if record is not None:
         record["grad_magnitudes"] = mags
+        record["loss_magnitude"] = loss_mag
         record["grads"] = (node, rel)
         record["neg_ids"] = neg
         record["touched"] = negatives.touched_rows(cfg, i, j, e, neg)

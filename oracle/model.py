@@ -108,7 +108,8 @@ def side_loss(loss, f, S, neg_weight):
         ef = np.exp(f[:, None] - m)
         z = ex.sum(axis=1, keepdims=True) + ef
         lse = (m + np.log(z))[:, 0]
-        return -f + lse, -1.0 + (ef / z)[:, 0], ex / z
+        # dl/df = -1 + e^f / z = -(sum_k e^S_k) / z: the second form has no cancellation where the positive dominates
+        return -f + lse, -(ex.sum(axis=1, keepdims=True) / z)[:, 0], ex / z
     # logistic: softplus(-f) + w * sum_k softplus(S_k)
     sp = lambda x: np.logaddexp(0.0, x)
     sig = lambda x: np.exp(-np.logaddexp(0.0, -x))       # 1 / (1 + e^-x), accurate for any x (e^x for x << 0)
@@ -159,7 +160,8 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitu
     Returns dict(loss [C], f [C], S [C,N], g_s, g_r (or None), g_d [C,dim], g_neg [N,dim]).
     With with_magnitudes, also m_s, m_r, m_d, m_neg: for every gradient element the sum of
     the absolute values of the elementary products it is made of (a forward error bound of
-    any floating-point evaluation of that element is a small multiple of roundoff times this)."""
+    any floating-point evaluation of that element is a small multiple of roundoff times this),
+    and m_loss [C]: the same scale for the absolute error of each loss term."""
     if side_is_dst:
         q = compose_u(score, s, r, rounded) if score == TRANSE else compose_u(score, s, r)       # meets destination-like rows
         other = d
@@ -184,11 +186,18 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitu
     if with_magnitudes:
         x = s if side_is_dst else d
         aq = abs_compose(score, x, r)
-        m_q = np.abs(a)[:, None] * np.abs(other) + np.abs(W) @ np.abs(negs)
-        m_other = np.abs(a)[:, None] * aq
+        # W_ek and a_e are functions of score differences, so they carry the absolute rounding error of
+        # the scores, which scales with A_ek = sum_j |q_ej| |theta_kj| rather than with |S_ek|: about
+        # 8 roundoffs times the row's largest A (twice a dot product's few-roundoff error, once for S_ek
+        # and once for the row's log-sum), i.e. max A / 4 in the callers' unit of 32 roundoffs
+        spread = np.maximum((aq @ np.abs(negs).T).max(axis=1), np.sum(aq * np.abs(other), axis=1)) / 4.0
+        Wm = np.abs(W) * (1.0 + spread)[:, None]
+        am = np.abs(a) * (1.0 + spread)
+        m_q = am[:, None] * np.abs(other) + Wm @ np.abs(negs)
+        m_other = am[:, None] * aq
         m_x = m_q if score == DOT else abs_compose(score, r, m_q)
         m_r = None if score == DOT else abs_compose(score, x, m_q)
-        out.update(m_neg=np.abs(W).T @ aq, m_r=m_r,
+        out.update(m_neg=Wm.T @ aq, m_r=m_r, m_loss=spread,
                    m_s=m_x if side_is_dst else m_other, m_d=m_other if side_is_dst else m_x)
     return out
 
@@ -214,9 +223,11 @@ def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, wit
         # partial sums of that size (where the callers' unit of error is 32 roundoffs): a term's
         # error scale is W_ek (1 + max_k |S_ek| dim / 128)
         nz = np.abs(sg)
-        Wm = np.abs(W) * (1.0 + np.abs(S).max(axis=1, keepdims=True) * (q.shape[1] / 128.0))
-        m_q = np.abs(a)[:, None] * np.abs(sg_pos) + np.einsum("ck,ckj->cj", Wm, nz)
-        m_other = np.abs(a)[:, None] * np.abs(sg_pos)
-        out.update(m_neg=np.einsum("ck,ckj->kj", Wm, nz), m_r=m_q,
+        spread = np.maximum(np.abs(S).max(axis=1), np.abs(f)) * (q.shape[1] / 128.0)
+        Wm = np.abs(W) * (1.0 + spread)[:, None]
+        am = np.abs(a) * (1.0 + spread)
+        m_q = am[:, None] * np.abs(sg_pos) + np.einsum("ck,ckj->cj", Wm, nz)
+        m_other = am[:, None] * np.abs(sg_pos)
+        out.update(m_neg=np.einsum("ck,ckj->kj", Wm, nz), m_r=m_q, m_loss=spread,
                    m_s=m_q if side_is_dst else m_other, m_d=m_other if side_is_dst else m_q)
     return out

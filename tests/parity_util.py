@@ -25,6 +25,12 @@ from oracle.bucket import OracleConfig, Tables, train_batch
 # it only matters where the gradient terms nearly cancel, which no fp32 order can reproduce.
 # The error of an fp32 dot product grows with the square root of its length: KAPPA is 32 roundoffs
 # up to dim 128 and grows like sqrt(dim / 128) beyond (45 roundoffs at 256, 57 at 400, 64 at 512).
+# Softmax weights and dl/df are functions of score differences and inherit the absolute error of the
+# fp32 scores, which scales with A = sum_j |q_j| |theta_j| and not with the score: the oracle widens
+# their magnitudes by (1 + max A / 4) per row (8 roundoffs times A; 1.25 at the benchmark workloads'
+# initial scale, two orders of magnitude once scores reach the hundreds), and the batch loss is allowed
+# KAPPA * sum_e max A_e / 4 beside its 1e-5 relative bound.  For the translational score the same role
+# is played by max |S| dim / 128.
 # Below the normal range of fp32 (2^-126) results are spaced 2^-149 apart and a relative bound means
 # nothing: every comparison allows two such steps on top.
 EMB_RTOL = 1e-5
@@ -84,9 +90,11 @@ class OracleRun:
         if max_batches is not None:
             nb = min(nb, batch_begin + max_batches)
         loss = 0.0
+        self.last_loss_allowance = 0.0       # of this call's loss sum, absolute
         for b in range(batch_begin, nb):
             rec = {}
             loss += train_batch(self.tab, i, j, edges, b, epoch, record=rec)
+            self.last_loss_allowance += kappa_for(cfg.dim) * rec["loss_magnitude"]
             node, rel = rec["grads"]
             mags = rec["grad_magnitudes"]
             for slot, part in ((0, i), (1, j)):

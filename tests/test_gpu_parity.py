@@ -191,7 +191,7 @@ def _check_every_batch(c):
             stats = L.legend_train_bucket_range(ctx, i, j, edges, epoch=1, batch_begin=b, batch_end=b + 1)
             want_loss = run.train_bucket(i, j, edges, epoch=1, batch_begin=b, max_batches=1)
             assert stats["batches"] == 1 and stats["edges"] == min(c["B"], c["m"] - b * c["B"])
-            assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss), (b, stats["loss_sum"], want_loss)
+            assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss) + run.last_loss_allowance, (b, stats["loss_sum"], want_loss)
             after = _read_all(L, ctx, c)
             touched = np.concatenate(run.touched_node, 0)[: c["V"]]
             compare_table(f"batch {b} node embeddings", after[0], run.tab.node_table(0), run.node_allowance(0), EMB_RTOL, 0.1)
@@ -232,7 +232,7 @@ def test_atomic_mode_every_batch_matches_oracle(c):
             run.set_state(*before)
             stats = L.legend_train_bucket_range(ctx, i, j, edges, epoch=1, batch_begin=b, batch_end=b + 1)
             want_loss = run.train_bucket(i, j, edges, epoch=1, batch_begin=b, max_batches=1)
-            assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss)
+            assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss) + run.last_loss_allowance
             after = _read_all(L, ctx, c)
             touched = np.concatenate(run.touched_node, 0)[: c["V"]]
             compare_table(f"batch {b} node embeddings", after[0], run.tab.node_table(0), 4 * run.node_allowance(0), EMB_RTOL, 0.1)
@@ -267,7 +267,7 @@ def test_free_running_bucket_stays_close_to_oracle(c):
         run = OracleRun(_ocfg(c), node, rel if c["score"] else None)
         want_loss = run.train_bucket(i, j, edges, epoch=1)
         assert stats["batches"] == -(-c["m"] // c["B"]) and stats["edges"] == c["m"]
-        assert abs(stats["loss_sum"] - want_loss) <= (2e-2 if discrete else 1e-5) * abs(want_loss), (stats["loss_sum"], want_loss)
+        assert abs(stats["loss_sum"] - want_loss) <= (2e-2 if discrete else 1e-5) * abs(want_loss) + run.last_loss_allowance, (stats["loss_sum"], want_loss)
         got = _read_all(L, ctx, c)
         want_E = run.tab.node_table(0).astype(np.float64)
         err = np.abs(got[0].astype(np.float64) - want_E)

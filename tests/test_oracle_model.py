@@ -121,6 +121,11 @@ def test_softmax_with_positive_closed_forms_and_library_cross_entropy():
     # a hopeless negative: loss -> 0, nothing to learn
     l, a, W = model.side_loss(model.SOFTMAX_POS, np.array([50.0]), np.array([[-50.0]]), 1.0)
     assert l[0] < 1e-40 + np.exp(-100.0) * 1.01 and abs(a[0]) < 1e-40 and W[0, 0] < 1e-40
+    # a dominating positive: dl/df = -r / (1 + r) with r = sum_k e^(S_k - f) tiny; evaluated as -1 + e^f / z
+    # it would keep two digits of r = 2e-14
+    l, a, W = model.side_loss(model.SOFTMAX_POS, np.array([30.0]), np.array([[-2.0, -5.0]]), 1.0)
+    r = np.exp(-32.0) + np.exp(-35.0)
+    assert abs(a[0] / (-r / (1.0 + r)) - 1.0) < 1e-14 and abs(a[0] + W.sum()) < 1e-28
     # torch's cross entropy over the logits [f, S_1..S_N] with class 0 as the target
     rng = np.random.default_rng(3)
     f, S = rng.standard_normal(5) * 3, rng.standard_normal((5, 9)) * 3
