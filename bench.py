@@ -43,6 +43,7 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
                         num_degree_negs=w.num_degree_negs, lr=w.lr, eps=w.eps, seed=args.seed,
                         update_mode=L.UPDATE_ATOMIC if args.update_mode == "atomic" else L.UPDATE_DETERMINISTIC)
     ctx = L.legend_init_partitions(cfg, node, rel if uses_rel else None)
+    log("[bench] context ready")
     K, W = max(args.steps, 1), args.warmup
     stats = None
     # where the caller keeps the edge list: device (default: a 288 GB card holds it next to the
@@ -72,12 +73,14 @@ def run_epochs(args, w, buckets, node, rel, L, graphs, torch) -> int:
             log(f"[bench] pinned {len(keep)} of {len(buckets)} bucket edge arrays, the rest stays pageable ({str(err).splitlines()[0]})")
     for ep in range(W):
         L.legend_train_epoch(ctx, n, buckets, edges_mem=edges_mem, epoch=ep, overlap=not args.no_overlap)
+        log(f"[bench] warm-up epoch {ep + 1}/{W} done")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     edges = 0
     for ep in range(W, W + K):
         stats = L.legend_train_epoch(ctx, n, buckets, edges_mem=edges_mem, epoch=ep, overlap=not args.no_overlap)
         edges += stats["edges"]
+        log(f"[bench] epoch {ep - W + 1}/{K} done after {time.perf_counter() - t0:.1f}s")
     L.legend_sync(ctx)
     wall = time.perf_counter() - t0
     log(f"[bench] {K} epoch(s), prefetch {'off' if args.no_overlap else 'on'}: {wall:.2f} s, {edges / wall:.3e} edges/s")
@@ -200,8 +203,8 @@ def run_rank(args, w, L, graphs, torch, np) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 200 batches; with --epoch a step is an epoch: 1)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default 20 batches; with --epoch 0)")
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--scale", type=int, default=1, help="divide nodes and edges of the workload (for quick checks)")
     ap.add_argument("--seed", type=int, default=1)
@@ -226,6 +229,10 @@ def main() -> int:
     ap.add_argument("--score", choices=["dot", "distmult", "complex", "transe"], default=None, help="override the score function")
     ap.add_argument("--batch-size", type=int, default=0, help="override the batch size")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 1 if args.epoch else 200
+    if args.warmup is None:
+        args.warmup = 0 if args.epoch else 20
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
         return 2
