@@ -244,16 +244,17 @@ hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_key
 }
 
 // ------------------------------------------------------------------------------------------
-// Small batches (n <= kSmallSortMax): one workgroup sorts the pairs in LDS and emits the segment
-// heads, so a latency-bound tiny batch pays one launch instead of some twenty.
+// Small batches (n <= kSmallSortMax): one workgroup sorts the pairs in LDS, emits the segment
+// heads and (deterministic mode) lists the rows with many gradient rows and their units, so a
+// latency-bound tiny batch pays one launch instead of some twenty.
 // Same stable ranking as the multi-block scatter: wave w owns a contiguous quarter of the keys.
 // ------------------------------------------------------------------------------------------
-constexpr int kSmallSortMax = 4096;
 
 __global__ void __launch_bounds__(kSortThreads)
 k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, uint32_t* __restrict__ vals_out,
                       uint32_t* __restrict__ uniq_keys, uint32_t* __restrict__ seg_start,
-                      uint32_t* __restrict__ counters, unsigned long long* __restrict__ uniq_total) {
+                      uint32_t* __restrict__ counters, unsigned long long* __restrict__ uniq_total,
+                      uint32_t* __restrict__ long_list, uint32_t* __restrict__ unit_start, int plan_long) {
     constexpr int kWaves = kSortThreads / kWave;
     extern __shared__ uint32_t sm[];
     auto kb = [&](int b) { return sm + b * kSmallSortMax; };                     // key buffers 0 / 1
@@ -357,17 +358,58 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
         if (tid == kSortThreads - 1) wsum[kWaves] = run + flag;
         __syncthreads();
     }
+    const uint32_t total = wsum[kWaves];
     if (tid == 0) {
-        const uint32_t total = wsum[kWaves];
         seg_start[total] = (uint32_t)n;
         counters[0] = total;
-        counters[2] = 0;
-        counters[3] = 0;
         *uniq_total += total;
+        wsum[kWaves + 1] = 0;                 // long rows
+        wsum[kWaves + 2] = 0;                 // their units
+    }
+    __threadfence_block();                    // segment bounds written above are read by other lanes below
+    __syncthreads();
+    uint32_t n_long = 0, units = 0;
+    if (plan_long) {
+        // table rows with many gradient rows, in no particular order, then the exclusive prefix of
+        // their unit counts
+        for (uint32_t u = tid; u < total; u += kSortThreads)
+            if (seg_start[u + 1] - seg_start[u] > (uint32_t)kLongLen) long_list[atomicAdd(&wsum[kWaves + 1], 1u)] = u;
+        __threadfence_block();
+        __syncthreads();
+        n_long = wsum[kWaves + 1];
+        for (uint32_t base = 0; base < n_long; base += kSortThreads) {
+            const uint32_t r = base + tid;
+            uint32_t v = 0;
+            if (r < n_long) {
+                const uint32_t u = long_list[r];
+                v = (seg_start[u + 1] - seg_start[u] + kUnit - 1) / kUnit;
+            }
+            uint32_t incl = v;
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t t = __shfl_up(incl, off, kWave);
+                if (lane >= off) incl += t;
+            }
+            if (lane == kWave - 1) wsum[w] = incl;
+            __syncthreads();
+            uint32_t woff = 0;
+            for (int ww = 0; ww < w; ++ww) woff += wsum[ww];
+            const uint32_t carry = wsum[kWaves + 2];
+            if (r < n_long) unit_start[r] = carry + woff + incl - v;
+            __syncthreads();
+            if (tid == kSortThreads - 1) wsum[kWaves + 2] = carry + woff + incl;
+            __syncthreads();
+        }
+        units = wsum[kWaves + 2];
+    }
+    if (tid == 0) {
+        if (plan_long) unit_start[n_long] = units;
+        counters[2] = n_long;
+        counters[3] = units;
     }
 }
 
-hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf) {
+hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf,
+                                    bool plan_long) {
     *out_buf = 0;
     if (n <= 0) return hipSuccess;
     if (n <= kSmallSortMax) {
@@ -382,7 +424,8 @@ hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, con
             attr_set = true;
         }
         hipLaunchKernelGGL(k_small_sort_segments, dim3(1), dim3(kSortThreads), lds, st, ws.keys[0], (int)n, passes,
-                           ws.vals[1], ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total);
+                           ws.vals[1], ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total, ws.long_list,
+                           ws.unit_start, plan_long ? 1 : 0);
         *out_buf = 1;
         return hipGetLastError();
     }

@@ -26,9 +26,6 @@ __device__ inline void adagrad_elem(float g, float& theta, float& state, float l
     theta = theta - step;
 }
 
-constexpr int kLongLen = 32;    // table rows with more gradient rows than this take the two-level path
-constexpr int kUnit = 256;      // gradient rows per unit of the two-level path (8 groups x 32)
-
 __device__ inline int table_of_key(const UpdateTables& tb, uint32_t key) {
     return key >= tb.key_base[2] ? 2 : (key >= tb.key_base[1] && tb.key_base[1] > 0 ? 1 : 0);
 }
@@ -297,7 +294,7 @@ int64_t update_long_units_capacity(int64_t n_occ) { return n_occ / kUnit + n_occ
 
 // Index side: which table rows of the batch take the two-level path, and their units.
 hipError_t launch_long_plan(hipStream_t st, int64_t n_occ, const Workspace& ws) {
-    if (n_occ <= 0) return hipSuccess;
+    if (n_occ <= kSmallSortMax) return hipSuccess;      // the single-workgroup sort kernel has done it
     int64_t blocks = (n_occ + 255) / 256;
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(k_long_list, dim3((unsigned)blocks), dim3(256), 0, st, ws.counters, ws.seg_start, ws.long_list);

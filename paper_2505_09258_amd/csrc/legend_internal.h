@@ -8,6 +8,13 @@
 
 namespace legend {
 
+// Coalescing of gradient rows: table rows with more than kLongLen gradient rows are summed in units of
+// kUnit rows (two levels, fixed order); batches of at most kSmallSortMax gradient rows are sorted, cut
+// into segments and planned by one workgroup.
+constexpr int kLongLen = 32;
+constexpr int kUnit = 256;      // 8 groups x 32 rows
+constexpr int kSmallSortMax = 4096;
+
 // ---- kernel classes for per-kernel event timing --------------------------------------------
 enum KernelClass : int {
     KC_PREPARE = 0,   // negative ids + sort keys of a batch
@@ -104,11 +111,14 @@ hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams
 // sorts ws.keys[0]/vals[0] (n_occ entries); result buffer index returned in *out_buf
 hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
 hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws);
-// sort + segment heads; small inputs take a single-workgroup kernel
-hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
+// sort + segment heads; small inputs take a single-workgroup kernel, which with plan_long also lists
+// the long rows and their units (what launch_long_plan does for larger inputs)
+hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf,
+                                    bool plan_long);
 // redo = false: the batch computation; redo = true: second launch over the workgroups the single-sweep kernel flagged
 bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws, bool redo);
+// long rows and their units from the segment bounds; nothing to do for n_occ <= kSmallSortMax
 hipError_t launch_long_plan(hipStream_t st, int64_t n_occ, const Workspace& ws);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, bool long_rows);

@@ -416,8 +416,9 @@ int enqueue_index_side(legend_ctx* c, hipStream_t st, const BatchGeom& g, const 
     }
     {
         ProfScope ps(c, KC_SORT, st);
-        HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, ws, sorted_buf));
-        if (c->cfg.update_mode != LEGEND_UPDATE_ATOMIC) HIP_TRY(c, launch_long_plan(st, g.n_occ, ws));
+        const bool plan_long = c->cfg.update_mode != LEGEND_UPDATE_ATOMIC;
+        HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, ws, sorted_buf, plan_long));
+        if (plan_long) HIP_TRY(c, launch_long_plan(st, g.n_occ, ws));
     }
     return LEGEND_OK;
 }
