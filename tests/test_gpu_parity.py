@@ -49,6 +49,12 @@ CASES = [
     _case("transe_d100_both", TRANSE, SOFTMAX, BOTH, 5_000, 9, 100, 2, 0, 1, 600, 50, 200, 40, 1_300, 0.1),
     _case("transe_d30_logistic_src", TRANSE, LOGISTIC, SRC, 2_000, 5, 30, 2, 1, 1, 200, 33, 65, 10, 450, 0.2),
     _case("transe_d128_softmax_pos", TRANSE, SOFTMAX_POS, DST, 3_000, 4, 128, 1, 0, 0, 360, 120, 130, 0, 800, 0.1),
+    # 2 * 1024 + 32 chunks * 64 negatives = 4096 gradient rows: the largest batch that one workgroup sorts, cuts into
+    # segments and plans (hub rows included); one edge more and the multi-kernel sort takes over
+    _case("dot_d32_small_sort_limit", DOT, SOFTMAX, DST, 2_500, 0, 32, 1, 0, 0, 1_024, 32, 64, 20, 2_300, 0.2),
+    _case("dot_d32_above_small_sort", DOT, SOFTMAX, DST, 2_500, 0, 32, 1, 0, 0, 1_025, 32, 64, 20, 2_300, 0.2),
+    # one negative more than the single-sweep kernel holds (1024): d = 100 through the two-sweep kernel
+    _case("dot_d100_n1025", DOT, SOFTMAX, DST, 6_000, 0, 100, 2, 0, 1, 300, 50, 1_025, 300, 700, 0.2),
 ]
 
 # One node row in 64 is four times larger than the rest, so that some chunks hold a score far
