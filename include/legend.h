@@ -86,7 +86,8 @@ typedef struct legend_config {
     float    eps;              /* Adagrad epsilon (added to sqrt of the state)      */
     float    neg_weight;       /* logistic loss: weight of each negative term;
                                   < 0 selects 1 / num_negs                          */
-    float    init_std;         /* reserved                                          */
+    float    init_std;         /* standard deviation of the seeded initial embeddings
+                                  (used only for a table whose init pointer is NULL) */
     uint64_t seed;             /* seed of the negative-sampling counter hash        */
     void*    compute_stream;   /* borrowed hipStream_t, or NULL: library creates    */
     void*    copy_stream;      /* borrowed hipStream_t, or NULL: library creates    */
@@ -112,10 +113,18 @@ typedef struct legend_bucket_stats {
  *   cfg            configuration; validated, copied.
  *   init_node_emb  [num_nodes][dim] fp32, row-major, global node order.  Node g
  *                  lives in partition g / R_p at local row g % R_p; the last
- *                  partition is zero-padded to R_p rows.  Must not be NULL.
- *   init_rel_emb   [max(num_relations,1)][dim] fp32, or NULL for zeros (allowed
- *                  only for LEGEND_SCORE_DOT, which ignores relations).
+ *                  partition is zero-padded to R_p rows.  NULL: seeded fill (below).
+ *   init_rel_emb   [max(num_relations,1)][dim] fp32, or NULL: seeded fill (zeros for
+ *                  LEGEND_SCORE_DOT, which ignores relations).
  *   out            receives the context.
+ * Seeded fill ("randomly initialized", Sec. 3 step 1; the paper prints no distribution):
+ * element (row g, column k) of a table is an integer function of cfg->seed,
+ *     h = fold(fold(fold(seed, tag), g), k),  fold(h, x) = mix64(h + 0x9E3779B97F4A7C15 + x),
+ *     mix64 = the splitmix64 output function, tag = 0x6E6F6465 (nodes) / 0x72656C73 (relations),
+ *     u = sum of the four 16-bit fields of h,
+ *     value = (float)(u - 131070) * (float)((double)init_std * sqrt(3) / 65536)
+ * (a sum of four uniform integers: mean 0, standard deviation init_std, the same on every
+ * machine).  init_std must be > 0 when a fill is asked for (LEGEND_E_INVAL otherwise).
  * Optimiser state starts at zero.  Allocates n pinned host blocks of
  * 2*R_p*dim floats, buffer_capacity device slots of the same size (one more when
  * buffer_capacity < num_partitions: the slot a partition is loaded into while the

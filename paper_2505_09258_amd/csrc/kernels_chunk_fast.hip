@@ -744,12 +744,12 @@ template <int SC, int D>
 static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     dim3 grid((unsigned)(g.sides * g.nchunks * g.T)), block(kFThreads);
     constexpr size_t lds = FastShape<D>::lds_bytes;
-    static bool configured = false;
-    if (!configured) {
+    static PerDeviceFlag configured;
+    if (configured.pending()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chunk_fast<SC, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.set();
     }
     hipLaunchKernelGGL((k_chunk_fast<SC, D>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,
                        ws.loss_partial, ws.redo, ws.redo_total, ws.fast_limit, ws.fast_no_retry ? 0 : 1);

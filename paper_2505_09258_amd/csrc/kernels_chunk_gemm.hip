@@ -546,12 +546,12 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
     const int negtiles = (bp.dim + kGNegColTile - 1) / kGNegColTile;
     const size_t gneg_lds = sizeof(float) * (kGRows * kGWS + kGRows * (kGNegColTile + 4));
     const size_t gq_lds = sizeof(float) * (kGRows * kGWS + kGNeg * (kGColTile + 4));
-    static bool configured = false;
-    if (!configured) {
+    static PerDeviceFlag configured;
+    if (configured.pending()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gneg<kGNegColTile>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)gneg_lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured.set();
     }
     switch (bp.score) {
         case LEGEND_SCORE_DOT:

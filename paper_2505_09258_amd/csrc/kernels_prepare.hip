@@ -29,6 +29,35 @@ hipError_t launch_validate_edges(hipStream_t st, const int32_t* edges, int64_t m
     return hipGetLastError();
 }
 
+// Seeded initial embeddings ("randomly initialized", Sec. 3 step 1; the distribution is not printed):
+// element (row g, column k) of a table is a pure integer function of (seed, table tag, g, k),
+//     h = fold(fold(fold(seed, tag), g), k),   u = sum of the four 16-bit fields of h  (0 .. 262140),
+//     value = float(int(u) - 131070) * scale,  scale = float(init_std * sqrt(3) / 65536),
+// a sum of four uniform integers: mean 0, standard deviation init_std, no transcendental function.
+__global__ void __launch_bounds__(256)
+k_init_fill(float* __restrict__ out, int64_t rows, int32_t dim, int64_t row0, uint64_t table_hash, float scale) {
+    const int64_t total = rows * dim;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const int64_t r = idx / dim;
+        const int k = (int)(idx - r * dim);
+        const uint64_t h = hash_fold(hash_fold(table_hash, (uint64_t)(row0 + r)), (uint64_t)k);
+        const int32_t u = (int32_t)((h & 0xFFFFu) + ((h >> 16) & 0xFFFFu) + ((h >> 32) & 0xFFFFu) + (h >> 48));
+        out[idx] = (float)(u - 131070) * scale;
+    }
+}
+
+hipError_t launch_init_fill(hipStream_t st, float* out, int64_t rows, int32_t dim, int64_t row0, uint64_t seed,
+                            uint64_t table_tag, float init_std) {
+    if (rows <= 0) return hipSuccess;
+    const float scale = (float)((double)init_std * 1.7320508075688772 / 65536.0);
+    int64_t blocks = (rows * dim + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_init_fill, dim3((unsigned)blocks), dim3(256), 0, st, out, rows, dim, row0,
+                       hash_fold(seed, table_tag), scale);
+    return hipGetLastError();
+}
+
 // One thread per occurrence (gradient row) of the batch: its sort key, and for
 // negative rows the sampled id.  Index arithmetic only; no floating point.
 __global__ void __launch_bounds__(256)

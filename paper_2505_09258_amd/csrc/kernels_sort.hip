@@ -416,12 +416,12 @@ hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, con
         int passes = (key_bits + 7) / 8;
         if (passes < 1) passes = 1;
         const size_t lds = (4 * (size_t)kSmallSortMax + 2 * 4 * kRadix + 8) * sizeof(uint32_t);
-        static bool attr_set = false;
-        if (!attr_set) {
+        static PerDeviceFlag attr_set;
+        if (attr_set.pending()) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_small_sort_segments),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
-            attr_set = true;
+            attr_set.set();
         }
         hipLaunchKernelGGL(k_small_sort_segments, dim3(1), dim3(kSortThreads), lds, st, ws.keys[0], (int)n, passes,
                            ws.vals[1], ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total, ws.long_list,

@@ -104,9 +104,25 @@ struct Workspace {
     int64_t   cap_wg;
 };
 
+// A kernel attribute (hipFuncSetAttribute) belongs to the device that is current when it is set:
+// "already set" is remembered per device, not per process.
+struct PerDeviceFlag {
+    bool done[64] = {};
+    int dev = 0;
+    bool pending() {
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { dev = -1; return true; }
+        return !done[dev];
+    }
+    void set() { if (dev >= 0) done[dev] = true; }
+};
+
 // ---- launch wrappers (defined in the kernel translation units) --------------------------------
 hipError_t launch_validate_edges(hipStream_t st, const int32_t* edges, int64_t m, int32_t rows_src,
                                  int32_t rows_dst, int32_t num_rel, int check_rel, uint32_t* err_flag);
+// seeded fill of `rows` table rows starting at global row `row0` (table_tag: kInitTagNode / kInitTagRel)
+constexpr uint64_t kInitTagNode = 0x6E6F6465ull, kInitTagRel = 0x72656C73ull;
+hipError_t launch_init_fill(hipStream_t st, float* out, int64_t rows, int32_t dim, int64_t row0, uint64_t seed,
+                            uint64_t table_tag, float init_std);
 hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 // sorts ws.keys[0]/vals[0] (n_occ entries); result buffer index returned in *out_buf
 hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);

@@ -4,6 +4,7 @@
 // so each swap can overlap the buckets that do not involve the partition being evicted.
 #include <cstdint>
 #include <cstring>
+#include <new>
 #include <vector>
 
 #include "legend.h"
@@ -113,8 +114,8 @@ std::vector<int> build_states(int n) {
 
 }  // namespace
 
-extern "C" int legend_plan_order(int32_t n, int32_t* states, int32_t state_capacity, int32_t* num_states,
-                                 int32_t* buckets, int32_t* state_begin, int32_t* state_overlap) {
+static int plan_order(int32_t n, int32_t* states, int32_t state_capacity, int32_t* num_states,
+                      int32_t* buckets, int32_t* state_begin, int32_t* state_overlap) {
     if (n < 1 || !states || !num_states || !buckets || !state_begin || !state_overlap) return LEGEND_E_INVAL;
     const std::vector<int> st = build_states(n);
     const int ns = (int)(st.size() / 3);
@@ -166,4 +167,16 @@ extern "C" int legend_plan_order(int32_t n, int32_t* states, int32_t state_capac
     }
     state_begin[ns] = nbk;
     return nbk == n * n ? LEGEND_OK : LEGEND_E_STATE;
+}
+
+// no C++ exception (the planner's containers can throw std::bad_alloc) crosses the C ABI
+extern "C" int legend_plan_order(int32_t n, int32_t* states, int32_t state_capacity, int32_t* num_states,
+                                 int32_t* buckets, int32_t* state_begin, int32_t* state_overlap) {
+    try {
+        return plan_order(n, states, state_capacity, num_states, buckets, state_begin, state_overlap);
+    } catch (const std::bad_alloc&) {
+        return LEGEND_E_NOMEM;
+    } catch (...) {
+        return LEGEND_E_STATE;
+    }
 }

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <new>
 #include <string>
 #include <vector>
@@ -20,16 +21,30 @@ using namespace legend;
 
 namespace {
 
-thread_local std::string g_last_error;
+// message of the calling thread's last failure: a fixed buffer, so that reporting an error never allocates
+thread_local char g_last_error[512] = "";
 
-int fail(int code, const char* fmt, ...) {
-    char buf[512];
+int fail(int code, const char* fmt, ...) noexcept {
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(buf, sizeof buf, fmt, ap);
+    vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
     va_end(ap);
-    g_last_error = buf;
     return code;
+}
+
+// Every entry point runs its body through this: no C++ exception (the containers of the host runtime
+// can throw std::bad_alloc) leaves the library through the C ABI.
+template <class F>
+int guarded(const char* what, F&& body) noexcept {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(LEGEND_E_NOMEM, "%s: out of host memory", what);
+    } catch (const std::exception& e) {
+        return fail(LEGEND_E_STATE, "%s: unexpected failure in the host runtime: %s", what, e.what());
+    } catch (...) {
+        return fail(LEGEND_E_STATE, "%s: unexpected failure in the host runtime", what);
+    }
 }
 
 const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "chunk_redo", "misc", "update_long"};
@@ -427,12 +442,13 @@ int enqueue_index_side(legend_ctx* c, hipStream_t st, const BatchGeom& g, const 
 
 extern "C" {
 
-const char* legend_last_error(void) { return g_last_error.c_str(); }
+const char* legend_last_error(void) { return g_last_error; }
 
 const char* legend_profile_name(int32_t k) { return (k >= 0 && k < KC_COUNT) ? kClassNames[k] : nullptr; }
 
 int legend_init_partitions(const legend_config* cfg, const float* init_node_emb, const float* init_rel_emb,
                            legend_ctx** out) {
+    return guarded("legend_init_partitions", [&]() -> int {
     if (!cfg || !out) return fail(LEGEND_E_INVAL, "cfg and out must not be NULL");
     *out = nullptr;
     if (cfg->struct_size != sizeof(legend_config))
@@ -450,8 +466,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "the translational score is implemented for dim <= 128");
     if (cfg->score != LEGEND_SCORE_DOT && cfg->num_relations < 1)
         return fail(LEGEND_E_INVAL, "this score function needs num_relations >= 1");
-    if (cfg->score != LEGEND_SCORE_DOT && !init_rel_emb) return fail(LEGEND_E_INVAL, "init_rel_emb must not be NULL for this score");
-    if (!init_node_emb) return fail(LEGEND_E_INVAL, "init_node_emb must not be NULL");
+    if ((!init_node_emb || (cfg->score != LEGEND_SCORE_DOT && !init_rel_emb)) && !(cfg->init_std > 0.f))
+        return fail(LEGEND_E_INVAL, "a NULL initial table asks for the seeded fill, which needs init_std > 0");
     if (cfg->batch_size < 1 || cfg->chunk_size < 1 || cfg->num_negs < 1 || cfg->num_degree_negs < 0 ||
         cfg->num_degree_negs > cfg->num_negs)
         return fail(LEGEND_E_INVAL, "batch_size, chunk_size, num_negs must be >= 1 and 0 <= num_degree_negs <= num_negs");
@@ -466,6 +482,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     if (hipSetDevice(cfg->device) != hipSuccess) return fail(LEGEND_E_HIP, "hipSetDevice(%d) failed", cfg->device);
     legend_ctx* c = new (std::nothrow) legend_ctx();
     if (!c) return fail(LEGEND_E_NOMEM, "context allocation failed");
+    try {
     c->cfg = *cfg;
     c->V = cfg->num_nodes;
     c->n = cfg->num_partitions;
@@ -536,8 +553,9 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         c->host_part[p] = static_cast<float*>(q);
         const int64_t lo = (int64_t)p * Rp;
         const int64_t rows = std::max<int64_t>(0, std::min<int64_t>(Rp, c->V - lo));
-        std::memcpy(c->host_part[p], init_node_emb + lo * c->d, (size_t)rows * c->d * sizeof(float));
-        std::memset(c->host_part[p] + (size_t)rows * c->d, 0, (c->part_floats - (size_t)rows * c->d) * sizeof(float));
+        if (init_node_emb) std::memcpy(c->host_part[p], init_node_emb + lo * c->d, (size_t)rows * c->d * sizeof(float));
+        std::memset(c->host_part[p] + (size_t)(init_node_emb ? rows : 0) * c->d, 0,
+                    (c->part_floats - (size_t)(init_node_emb ? rows : 0) * c->d) * sizeof(float));
         (void)half;
     }
     INIT_TRY(hipStreamCreateWithFlags(&c->copy_out, hipStreamNonBlocking));
@@ -554,6 +572,16 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
             INIT_TRY(hipMemset(c->slot_grad[s], 0, (size_t)Rp * c->d * sizeof(float)));
         }
     }
+    if (!init_node_emb) {
+        // seeded fill: generated on the device into the first slot, one partition at a time, and copied to the host tier
+        for (int p = 0; p < c->n; ++p) {
+            const int64_t lo = (int64_t)p * Rp;
+            const int64_t rows = std::max<int64_t>(0, std::min<int64_t>(Rp, c->V - lo));
+            INIT_TRY(launch_init_fill(c->compute, c->slot_mem[0], rows, c->d, lo, cfg->seed, kInitTagNode, cfg->init_std));
+            INIT_TRY(hipMemcpyAsync(c->host_part[p], c->slot_mem[0], (size_t)rows * c->d * sizeof(float), hipMemcpyDeviceToHost, c->compute));
+        }
+        INIT_TRY(hipStreamSynchronize(c->compute));
+    }
     const size_t rel_floats = (size_t)c->nrel_rows * c->d;
     INIT_RC(dev_alloc(c, &c->E_rel, rel_floats));
     INIT_RC(dev_alloc(c, &c->S_rel, rel_floats));
@@ -563,6 +591,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         INIT_TRY(hipMemset(c->G_rel, 0, rel_floats * sizeof(float)));
     }
     if (init_rel_emb) INIT_TRY(hipMemcpy(c->E_rel, init_rel_emb, rel_floats * sizeof(float), hipMemcpyHostToDevice));
+    else if (c->uses_rel) INIT_TRY(launch_init_fill(c->compute, c->E_rel, c->nrel_rows, c->d, 0, cfg->seed, kInitTagRel, cfg->init_std));
     else INIT_TRY(hipMemset(c->E_rel, 0, rel_floats * sizeof(float)));
     INIT_RC(dev_alloc(c, &c->d_part_emb, (size_t)c->n));
     INIT_RC(dev_alloc(c, &c->d_part_state, (size_t)c->n));
@@ -649,16 +678,24 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     INIT_TRY(hipDeviceSynchronize());
 #undef INIT_TRY
 #undef INIT_RC
+    } catch (...) {
+        free_ctx(c);
+        throw;
+    }
     *out = c;
     return LEGEND_OK;
+    });
 }
 
 int legend_destroy(legend_ctx* ctx) {
+    return guarded("legend_destroy", [&]() -> int {
     free_ctx(ctx);
     return LEGEND_OK;
+    });
 }
 
 int legend_sync(legend_ctx* c) {
+    return guarded("legend_sync", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->compute));
@@ -666,30 +703,38 @@ int legend_sync(legend_ctx* c) {
     HIP_TRY(c, hipStreamSynchronize(c->copy));
     HIP_TRY(c, hipStreamSynchronize(c->copy_out));
     return LEGEND_OK;
+    });
 }
 
 int legend_swap_partition(legend_ctx* c, int32_t evict, int32_t load) {
+    return guarded("legend_swap_partition", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     return do_swap(c, evict, load, true);
+    });
 }
 
 int legend_partition_slot(legend_ctx* c, int32_t part, int32_t* slot) {
+    return guarded("legend_partition_slot", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!slot || part < 0 || part >= c->n) return fail(LEGEND_E_INVAL, "bad partition id or NULL output");
     *slot = c->part_slot[part];
     return LEGEND_OK;
+    });
 }
 
 int legend_train_bucket(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
                         int32_t epoch, const legend_prefetch* hint, legend_bucket_stats* stats) {
+    return guarded("legend_train_bucket", [&]() -> int {
     return legend_train_bucket_range(c, i, j, edges, m, edges_mem, epoch, 0, -1, hint, stats);
+    });
 }
 
 int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
                               int32_t epoch, int64_t batch_begin, int64_t batch_end, const legend_prefetch* hint,
                               legend_bucket_stats* stats) {
+    return guarded("legend_train_bucket_range", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (i < 0 || j < 0 || i >= c->n || j >= c->n) return fail(LEGEND_E_INVAL, "bucket (%d,%d) out of range", i, j);
@@ -835,10 +880,12 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         stats->ms = ms;
     }
     return LEGEND_OK;
+    });
 }
 
 int legend_train_epoch(legend_ctx* c, const int32_t* const* bucket_edges, const int64_t* bucket_sizes, int32_t edges_mem,
                        int32_t epoch, int32_t overlap, legend_epoch_stats* stats) {
+    return guarded("legend_train_epoch", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!bucket_edges || !bucket_sizes) return fail(LEGEND_E_INVAL, "NULL bucket table");
@@ -919,11 +966,13 @@ int legend_train_epoch(legend_ctx* c, const int32_t* const* bucket_edges, const 
         stats->ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     }
     return LEGEND_OK;
+    });
 }
 
 int legend_debug_batch_indices(legend_ctx* c, int32_t i, int32_t j, const int32_t* edges, int64_t m, int32_t edges_mem,
                                int32_t epoch, int64_t batch, int32_t* neg_ids, int64_t neg_capacity, int64_t* touched,
                                int64_t touched_capacity, int64_t* touched_count) {
+    return guarded("legend_debug_batch_indices", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (i < 0 || j < 0 || i >= c->n || j >= c->n) return fail(LEGEND_E_INVAL, "bucket (%d,%d) out of range", i, j);
@@ -969,9 +1018,11 @@ int legend_debug_batch_indices(legend_ctx* c, int32_t i, int32_t j, const int32_
         touched[k] = (t << 32) + row;
     }
     return LEGEND_OK;
+    });
 }
 
 int legend_score_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m, float* out) {
+    return guarded("legend_score_edges", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (m < 0) return fail(LEGEND_E_INVAL, "m < 0");
@@ -1011,11 +1062,13 @@ int legend_score_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, co
     if (h & 1u) return fail(LEGEND_E_RANGE, "a node or relation id is out of range");
     if (h & 2u) return fail(LEGEND_E_NOT_RESIDENT, "an edge refers to a partition that is not resident");
     return LEGEND_OK;
+    });
 }
 
 int legend_rank_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m, int32_t side,
                       const int64_t* candidates, int64_t num_candidates, int32_t* greater, int32_t* equal,
                       legend_rank_metrics* metrics) {
+    return guarded("legend_rank_edges", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (m < 0 || num_candidates < 0) return fail(LEGEND_E_INVAL, "m < 0 or num_candidates < 0");
@@ -1087,9 +1140,11 @@ int legend_rank_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, con
         metrics->ms = ms;
     }
     return LEGEND_OK;
+    });
 }
 
 int legend_read_embeddings(legend_ctx* c, int32_t table, const int64_t* ids, int64_t m, float* out) {
+    return guarded("legend_read_embeddings", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (table < 0 || table > 3) return fail(LEGEND_E_INVAL, "unknown table %d", table);
@@ -1153,16 +1208,20 @@ int legend_read_embeddings(legend_ctx* c, int32_t table, const int64_t* ids, int
         if (c->part_slot[p] < 0) std::memcpy(out + k * d, c->host_part[p] + off + (ids[k] % c->Rp) * d, rowb);
     }
     return LEGEND_OK;
+    });
 }
 
 int legend_profile_enable(legend_ctx* c, uint32_t mask) {
+    return guarded("legend_profile_enable", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     c->prof_mask = mask & ((1u << KC_COUNT) - 1u);
     return LEGEND_OK;
+    });
 }
 
 int legend_profile_read(legend_ctx* c, double* ms, int64_t* launches, int32_t capacity) {
+    return guarded("legend_profile_read", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!ms || !launches || capacity < KC_COUNT) return fail(LEGEND_E_INVAL, "need capacity >= %d", (int)KC_COUNT);
@@ -1176,9 +1235,11 @@ int legend_profile_read(legend_ctx* c, double* ms, int64_t* launches, int32_t ca
         c->prof_launches[k] = 0;
     }
     return LEGEND_OK;
+    });
 }
 
 int legend_batch_shape_of(legend_ctx* c, legend_batch_shape* out) {
+    return guarded("legend_batch_shape_of", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!out) return fail(LEGEND_E_INVAL, "NULL output");
@@ -1188,9 +1249,11 @@ int legend_batch_shape_of(legend_ctx* c, legend_batch_shape* out) {
     out->key_bits = c->key_bits;
     out->row_tiles = c->gmax.T;
     return LEGEND_OK;
+    });
 }
 
 int legend_unique_rows_read(legend_ctx* c, int64_t* unique_rows, int64_t* batches) {
+    return guarded("legend_unique_rows_read", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!unique_rows || !batches) return fail(LEGEND_E_INVAL, "NULL output");
@@ -1202,9 +1265,11 @@ int legend_unique_rows_read(legend_ctx* c, int64_t* unique_rows, int64_t* batche
     *batches = c->batches_done;
     c->batches_done = 0;
     return LEGEND_OK;
+    });
 }
 
 int legend_fallback_chunks_read(legend_ctx* c, int64_t* chunks) {
+    return guarded("legend_fallback_chunks_read", [&]() -> int {
     int rc = check_ctx(c);
     if (rc) return rc;
     if (!chunks) return fail(LEGEND_E_INVAL, "NULL output");
@@ -1214,6 +1279,7 @@ int legend_fallback_chunks_read(legend_ctx* c, int64_t* chunks) {
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     *chunks = (int64_t)u;
     return LEGEND_OK;
+    });
 }
 
 }  // extern "C"
