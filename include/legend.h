@@ -335,6 +335,34 @@ int legend_rank_edges(legend_ctx* ctx, const int64_t* src, const int32_t* rel, c
                       int64_t m, int32_t side, const int64_t* candidates, int64_t num_candidates,
                       int32_t* greater, int32_t* equal, legend_rank_metrics* metrics);
 
+/*
+ * legend_rank_edges for callers that cannot allocate: code under HIP graph capture, tight
+ * evaluation loops inside a serving process, harnesses that forbid hipMalloc.  The same kernels
+ * as legend_rank_edges, but
+ *   - every pointer is a DEVICE pointer (src, rel, dst [m]; candidates [num_candidates] or NULL
+ *     for every node; outputs greater, equal [m] int32, metrics [4] double = MRR, Hits@1,
+ *     Hits@3, Hits@10, status [1] uint32), all owned by the caller and all required except rel
+ *     (Dot) and candidates;
+ *   - the intermediate results (composed rows q_e, own scores, true endpoints) live in a static
+ *     device buffer of 8 MiB inside the library instead of an allocation: one copy per GPU, held
+ *     until the process ends.  The call is refused with LEGEND_E_INVAL when m exceeds
+ *     legend_rank_edges_static_max_triples(dim) (18 368 triples at dim 100, 5 184 at dim 400);
+ *   - it calls no hipMalloc / hipFree and no allocating routine, clears what must start at zero
+ *     with a fill kernel, enqueues everything on the context's compute stream and returns without
+ *     waiting: results are final after legend_sync (or a wait on the borrowed compute stream).
+ *     Exception: if the buffer contents changed since the last scoring or ranking call, the
+ *     partition table is re-sent first (one small copy and a stream synchronisation).
+ * status: 0 = fine; bit 0: a node, relation or candidate id out of range; bit 1: a partition
+ * that is not resident (the counts of the triples concerned are then meaningless).
+ * Every call on a GPU shares that GPU's buffer, whatever the context or stream: calls that
+ * overlap in time on one GPU race; serialise them.  Per-kernel profiling does not cover this call.
+ */
+int legend_rank_edges_static(legend_ctx* ctx, const int64_t* src, const int32_t* rel, const int64_t* dst,
+                             int64_t m, int32_t side, const int64_t* candidates, int64_t num_candidates,
+                             int32_t* greater, int32_t* equal, double* metrics, uint32_t* status);
+/* Largest m legend_rank_edges_static accepts at embedding dimension dim (0: unsupported dim). */
+int64_t legend_rank_edges_static_max_triples(int32_t dim);
+
 /* Message of the last error on this thread ("" if none). */
 const char* legend_last_error(void);
 

@@ -28,7 +28,8 @@ TABLE_NODE_EMB, TABLE_NODE_STATE, TABLE_REL_EMB, TABLE_REL_STATE = 0, 1, 2, 3
 
 EXPORTS = [
     "legend_init_partitions", "legend_destroy", "legend_swap_partition", "legend_partition_slot",
-    "legend_train_bucket", "legend_train_bucket_range", "legend_train_epoch", "legend_score_edges", "legend_rank_edges", "legend_read_embeddings", "legend_debug_batch_indices",
+    "legend_train_bucket", "legend_train_bucket_range", "legend_train_epoch", "legend_score_edges", "legend_rank_edges", "legend_rank_edges_static",
+    "legend_rank_edges_static_max_triples", "legend_read_embeddings", "legend_debug_batch_indices",
     "legend_plan_order", "legend_sync", "legend_profile_enable", "legend_profile_read",
     "legend_profile_name", "legend_batch_shape_of", "legend_unique_rows_read", "legend_fallback_chunks_read",
     "legend_last_error",
@@ -92,6 +93,8 @@ def _load() -> C.CDLL:
     lib.legend_train_epoch.argtypes = [vp, vp, vp, i32, i32, i32, C.POINTER(legend_epoch_stats)]
     lib.legend_score_edges.argtypes = [vp, vp, vp, vp, i64, vp]
     lib.legend_rank_edges.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, vp, vp, C.POINTER(legend_rank_metrics)]
+    lib.legend_rank_edges_static.argtypes = [vp, vp, vp, vp, i64, i32, vp, i64, vp, vp, vp, vp]
+    lib.legend_rank_edges_static_max_triples.argtypes = [i32]
     lib.legend_read_embeddings.argtypes = [vp, i32, vp, i64, vp]
     lib.legend_debug_batch_indices.argtypes = [vp, i32, i32, vp, i64, i32, i32, i64, vp, i64, vp, i64,
                                                C.POINTER(i64)]
@@ -106,8 +109,9 @@ def _load() -> C.CDLL:
     lib.legend_fallback_chunks_read.argtypes = [vp, C.POINTER(i64)]
     lib.legend_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("legend_profile_name", "legend_last_error"):
+        if name not in ("legend_profile_name", "legend_last_error", "legend_rank_edges_static_max_triples"):
             getattr(lib, name).restype = C.c_int
+    lib.legend_rank_edges_static_max_triples.restype = C.c_int64
     return lib
 
 
@@ -255,6 +259,19 @@ def legend_rank_edges(ctx, src, rel, dst, side: int = CORRUPT_DST, candidates=No
     _check(_lib.legend_rank_edges(ctx, _ptr(s), _ptr(r), _ptr(d), m, side, _ptr(cand),
                                   0 if cand is None else cand.shape[0], _ptr(greater), _ptr(equal), C.byref(mt)))
     return greater, equal, {k: getattr(mt, k) for k, _ in legend_rank_metrics._fields_}
+
+
+def legend_rank_edges_static(ctx, src: int, rel: Optional[int], dst: int, m: int, side: int, candidates: Optional[int],
+                             num_candidates: int, greater: int, equal: int, metrics: int, status: int) -> None:
+    """Every array argument is a device address (an integer); None for rel / candidates passes NULL."""
+    def dp(a):
+        return None if a is None else C.c_void_p(int(a))
+    _check(_lib.legend_rank_edges_static(ctx, dp(src), dp(rel), dp(dst), m, side, dp(candidates), num_candidates,
+                                         dp(greater), dp(equal), dp(metrics), dp(status)))
+
+
+def legend_rank_edges_static_max_triples(dim: int) -> int:
+    return int(_lib.legend_rank_edges_static_max_triples(dim))
 
 
 def legend_read_embeddings(ctx, table: int, ids, m: int, dim: int) -> np.ndarray:

@@ -29,6 +29,20 @@ hipError_t launch_validate_edges(hipStream_t st, const int32_t* edges, int64_t m
     return hipGetLastError();
 }
 
+// Plain fill of 32-bit words: clears counters and flags where a memset node must not be recorded.
+__global__ void __launch_bounds__(256) k_fill_u32(uint32_t* __restrict__ p, uint32_t v, int64_t n) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t n) {
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, st, p, v, n);
+    return hipGetLastError();
+}
+
 // Seeded initial embeddings ("randomly initialized", Sec. 3 step 1; the distribution is not printed):
 // element (row g, column k) of a table is a pure integer function of (seed, table tag, g, k),
 //     h = fold(fold(fold(seed, tag), g), k),   u = sum of the four 16-bit fields of h  (0 .. 262140),

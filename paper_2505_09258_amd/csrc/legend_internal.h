@@ -123,6 +123,7 @@ hipError_t launch_validate_edges(hipStream_t st, const int32_t* edges, int64_t m
 constexpr uint64_t kInitTagNode = 0x6E6F6465ull, kInitTagRel = 0x72656C73ull;
 hipError_t launch_init_fill(hipStream_t st, float* out, int64_t rows, int32_t dim, int64_t row0, uint64_t seed,
                             uint64_t table_tag, float init_std);
+hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t n);
 hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 // sorts ws.keys[0]/vals[0] (n_occ entries); result buffer index returned in *out_buf
 hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);

@@ -19,6 +19,8 @@
 
 using namespace legend;
 
+static __device__ __align__(256) unsigned char scratch[(size_t)8 << 20];
+
 namespace {
 
 // message of the calling thread's last failure: a fixed buffer, so that reporting an error never allocates
@@ -47,6 +49,13 @@ int guarded(const char* what, F&& body) noexcept {
     }
 }
 
+// Scratch memory of legend_rank_edges_static: lives in the code object, one copy per device, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the device
+// address is resolved once per device (resolve_static_scratch) and kernels and fills take that pointer.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+unsigned char* g_static_scratch[kMaxDevices] = {};
+
 const char* kClassNames[KC_COUNT] = {"prepare", "sort", "chunk", "update", "chunk_redo", "misc", "update_long"};
 
 struct ProfSpan {
@@ -55,6 +64,20 @@ struct ProfSpan {
 };
 
 }  // namespace
+
+// device address of `scratch` on the current device `dev`; resolved on first use per device
+static int resolve_static_scratch(int dev) {
+    if (dev < 0 || dev >= kMaxDevices) return fail(LEGEND_E_INVAL, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    if (g_static_scratch[dev]) return LEGEND_OK;
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return fail(LEGEND_E_HIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    }
+    g_static_scratch[dev] = static_cast<unsigned char*>(p);
+    return LEGEND_OK;
+}
 
 struct legend_ctx {
     legend_config cfg{};
@@ -80,6 +103,7 @@ struct legend_ctx {
     std::vector<int> slot_drain_part;       // the partition whose write-back slot_drained marks
     float* E_rel = nullptr;
     float* S_rel = nullptr;
+    std::vector<float*> h_part_emb, h_part_state;   // host images of the two tables below (sized at init)
     float** d_part_emb = nullptr;           // device: embedding base per partition or null
     float** d_part_state = nullptr;
     hipStream_t compute = nullptr, copy = nullptr;
@@ -205,13 +229,12 @@ int ensure_io(legend_ctx* c, size_t bytes) {
 }
 
 int upload_part_tables(legend_ctx* c) {
-    std::vector<float*> e(c->n, nullptr), s(c->n, nullptr);
+    std::vector<float*>& e = c->h_part_emb;
+    std::vector<float*>& s = c->h_part_state;
     for (int p = 0; p < c->n; ++p) {
         int sl = c->part_slot[p];
-        if (sl >= 0) {
-            e[p] = c->slot_mem[sl];
-            s[p] = c->slot_mem[sl] + c->Rp * c->d;
-        }
+        e[p] = sl >= 0 ? c->slot_mem[sl] : nullptr;
+        s[p] = sl >= 0 ? c->slot_mem[sl] + c->Rp * c->d : nullptr;
     }
     HIP_TRY(c, hipMemcpyAsync(c->d_part_emb, e.data(), sizeof(float*) * c->n, hipMemcpyHostToDevice, c->compute));
     HIP_TRY(c, hipMemcpyAsync(c->d_part_state, s.data(), sizeof(float*) * c->n, hipMemcpyHostToDevice, c->compute));
@@ -480,6 +503,10 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     if (2 * Rp + std::max(cfg->num_relations, 1) >= (int64_t)1 << 31) return fail(LEGEND_E_INVAL, "partition too large for 32-bit row keys");
 
     if (hipSetDevice(cfg->device) != hipSuccess) return fail(LEGEND_E_HIP, "hipSetDevice(%d) failed", cfg->device);
+    {
+        int rc_scratch = resolve_static_scratch(cfg->device);
+        if (rc_scratch) return rc_scratch;
+    }
     legend_ctx* c = new (std::nothrow) legend_ctx();
     if (!c) return fail(LEGEND_E_NOMEM, "context allocation failed");
     try {
@@ -502,6 +529,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     c->slot_grad.assign(c->nslots, nullptr);
     c->slot_part.assign(c->nslots, -1);
     c->part_slot.assign(c->n, -1);
+    c->h_part_emb.assign(c->n, nullptr);
+    c->h_part_state.assign(c->n, nullptr);
     c->slot_ready.assign(c->nslots, nullptr);
     c->slot_pending.assign(c->nslots, 0);
     c->slot_drained.assign(c->nslots, nullptr);
@@ -1141,6 +1170,65 @@ int legend_rank_edges(legend_ctx* c, const int64_t* src, const int32_t* rel, con
     }
     return LEGEND_OK;
     });
+}
+
+int legend_rank_edges_static(legend_ctx* c, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m,
+                             int32_t side, const int64_t* candidates, int64_t num_candidates, int32_t* greater,
+                             int32_t* equal, double* metrics, uint32_t* status) {
+    return guarded("legend_rank_edges_static", [&]() -> int {
+    int rc = check_ctx(c);
+    if (rc) return rc;
+    if (m < 0 || num_candidates < 0) return fail(LEGEND_E_INVAL, "m < 0 or num_candidates < 0");
+    if (side != LEGEND_CORRUPT_DST && side != LEGEND_CORRUPT_SRC)
+        return fail(LEGEND_E_INVAL, "side must be LEGEND_CORRUPT_DST or LEGEND_CORRUPT_SRC");
+    if (c->V > 0x7fffffffll) return fail(LEGEND_E_INVAL, "ranking needs num_nodes < 2^31");
+    if (!metrics || !status) return fail(LEGEND_E_INVAL, "metrics and status must not be NULL");
+    if (m > 0 && (!src || !dst || !greater || !equal)) return fail(LEGEND_E_INVAL, "NULL argument");
+    if (m > 0 && c->uses_rel && !rel) return fail(LEGEND_E_INVAL, "rel must not be NULL for this score");
+    const int64_t n_cand = candidates ? num_candidates : c->V;
+    if (n_cand > 0x7fffffffll) return fail(LEGEND_E_INVAL, "too many candidates");
+    // scratch layout: q rows [m_pad][dp] | own scores [m_pad] | true endpoints [m_pad]
+    const int64_t m_pad = rank_rows_padded(std::max<int64_t>(m, 1));
+    const int dp = rank_dim_padded(c->d);
+    auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
+    const size_t b_q = up((size_t)m_pad * dp * sizeof(float)), b_row = up((size_t)m_pad * sizeof(int32_t));
+    if (b_q + 2 * b_row > kStaticScratchBytes)
+        return fail(LEGEND_E_INVAL, "%lld triples of dimension %d need %zu bytes of scratch, the static buffer holds %zu "
+                    "(at most %lld triples at this dimension)", (long long)m, c->d, b_q + 2 * b_row, kStaticScratchBytes,
+                    (long long)legend_rank_edges_static_max_triples(c->d));
+    unsigned char* base = g_static_scratch[c->cfg.device];
+    if (!base) return fail(LEGEND_E_STATE, "static scratch of device %d was never resolved", c->cfg.device);
+    for (int s = 0; s < c->nslots; ++s) {
+        rc = wait_slot(c, s);
+        if (rc) return rc;
+    }
+    if (c->part_tables_dirty) {
+        rc = upload_part_tables(c);
+        if (rc) return rc;
+    }
+    float* d_q = reinterpret_cast<float*>(base);
+    float* d_f = reinterpret_cast<float*>(base + b_q);
+    int32_t* d_true = reinterpret_cast<int32_t*>(base + b_q + b_row);
+    // counts and the status word start at zero; a fill kernel, not a memset node, so that the call can be
+    // recorded into a graph
+    HIP_TRY(c, launch_fill_u32(c->compute, reinterpret_cast<uint32_t*>(greater), 0u, m));
+    HIP_TRY(c, launch_fill_u32(c->compute, reinterpret_cast<uint32_t*>(equal), 0u, m));
+    HIP_TRY(c, launch_fill_u32(c->compute, status, 0u, 1));
+    HIP_TRY(c, launch_fill_u32(c->compute, reinterpret_cast<uint32_t*>(metrics), 0u, 8));
+    if (m == 0) return LEGEND_OK;
+    // no event-timed profiling span here: creating its events would allocate
+    HIP_TRY(c, launch_rank(c->compute, src, rel, dst, m, side, candidates, n_cand, c->d_part_emb, (int32_t)c->Rp, c->V,
+                           c->E_rel, c->cfg.num_relations, c->d, c->cfg.score, d_q, d_f, d_true, greater, equal,
+                           metrics, status));
+    return LEGEND_OK;
+    });
+}
+
+int64_t legend_rank_edges_static_max_triples(int32_t dim) {
+    if (dim < 1 || dim > max_dim_supported()) return 0;
+    const int64_t per_row = (int64_t)rank_dim_padded(dim) * 4 + 8;
+    int64_t rows = (int64_t)(kStaticScratchBytes - 3 * 256) / per_row;
+    return rows / 64 * 64;
 }
 
 int legend_read_embeddings(legend_ctx* c, int32_t table, const int64_t* ids, int64_t m, float* out) {
