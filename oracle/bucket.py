@@ -111,7 +111,12 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
 
     Returns (loss, node, rel): loss is the float64 batch sum; node maps a table
     slot (0: partition i, 1: partition j when j != i) to (unique rows, summed
-    float64 gradient rows); rel is the same pair for the relation table or None."""
+    float64 gradient rows); rel is the same pair for the relation table or None.
+    record, when given, receives the batch's gradients, negative ids and touched rows; a
+    callable under record["observer"] is shown every chunk's inputs and results
+    (side index, corrupted side is dst, chunk, the chunk's edge rows, negative ids, the
+    gathered float64 rows s, r, d, negs, and chunk_side's result) and takes no part in
+    the computation."""
     cfg = tab.cfg
     lo = b * cfg.batch_size
     e = bucket_edges[lo: lo + cfg.batch_size]
@@ -128,11 +133,9 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
     ti, tj = 0, (0 if i == j else 1)      # node table slot of each role
     node_keys = [[], []]
     node_grads = [[], []]
-    node_mags = [[], []]
-    rel_keys, rel_grads, rel_mags = [], [], []
+    rel_keys, rel_grads = [], []
     loss = 0.0
-    loss_mag = 0.0
-    want_mags = record is not None
+    observer = record.get("observer") if record is not None else None
 
     # stage 5: batch computation, chunk by chunk, side by side
     nchunks = -(-p // cfg.chunk_size)
@@ -142,40 +145,27 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
         for c in range(nchunks):
             sl = slice(c * cfg.chunk_size, min(p, (c + 1) * cfg.chunk_size))
             ids = neg[si, c]
+            neg_rows = neg_table[ids].astype(np.float64)
             out = model.chunk_side(cfg.score, cfg.loss, cfg.w_neg, is_dst,
                                    s_all[sl], r_all[sl] if uses_rel else None, d_all[sl],
-                                   neg_table[ids].astype(np.float64), with_magnitudes=want_mags,
-                                   rounded=cfg.round_composed)
+                                   neg_rows, rounded=cfg.round_composed)
             loss += float(out["loss"].sum())
-            if want_mags:
-                loss_mag += float(out["m_loss"].sum())
-                node_mags[ti].append(out["m_s"]); node_mags[tj].append(out["m_d"])
-                node_mags[neg_slot].append(out["m_neg"])
-                if uses_rel:
-                    rel_mags.append(out["m_r"])
             node_keys[ti].append(e[sl, 0].astype(np.int64)); node_grads[ti].append(out["g_s"])
             node_keys[tj].append(e[sl, 2].astype(np.int64)); node_grads[tj].append(out["g_d"])
             node_keys[neg_slot].append(ids); node_grads[neg_slot].append(out["g_neg"])
             if uses_rel:
                 rel_keys.append(e[sl, 1].astype(np.int64)); rel_grads.append(out["g_r"])
-            if record is not None:
-                record.setdefault("chunks", []).append((si, c, out))
+            if observer is not None:
+                observer(si, is_dst, c, e[sl], ids, s_all[sl], r_all[sl] if uses_rel else None, d_all[sl], neg_rows, out)
 
-    mags = {}
     node = {}
     for slot in (0, 1):
         if node_keys[slot]:
             node[slot] = _coalesce(node_keys[slot], node_grads[slot])
-            if want_mags:
-                mags[slot] = _coalesce(node_keys[slot], node_mags[slot])[1]
     rel = None
     if uses_rel and rel_keys:
         rel = _coalesce(rel_keys, rel_grads)
-        if want_mags:
-            mags[2] = _coalesce(rel_keys, rel_mags)[1]
     if record is not None:
-        record["grad_magnitudes"] = mags
-        record["loss_magnitude"] = loss_mag
         record["grads"] = (node, rel)
         record["neg_ids"] = neg
         record["touched"] = negatives.touched_rows(cfg, i, j, e, neg)

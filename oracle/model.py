@@ -139,29 +139,13 @@ def chain_from_v(score, g_v, r, d):
     return cmul(r, g_v), cmul_conj(g_v, d)
 
 
-def abs_compose(score, a, b):
-    """Sum of the absolute values of the products that form a (x) b (either form):
-    the magnitude against which the rounding error of that product is measured."""
-    if score == DOT:
-        return np.abs(a)
-    a, b = np.abs(a), np.abs(b)
-    if score == DISTMULT:
-        return a * b
-    ar, ai = _halves(a)
-    br, bi = _halves(b)
-    return np.concatenate([ar * br + ai * bi, ar * bi + ai * br], axis=-1)
-
-
-def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitudes=False, rounded=True):
+def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, rounded=True):
     """Loss and gradients of one chunk for one corrupted side.
 
     s, r, d: [C, dim] float64 rows of the chunk's positive edges (r ignored for Dot).
     negs:    [N, dim] float64 rows of the shared negatives of this side.
-    Returns dict(loss [C], f [C], S [C,N], g_s, g_r (or None), g_d [C,dim], g_neg [N,dim]).
-    With with_magnitudes, also m_s, m_r, m_d, m_neg: for every gradient element the sum of
-    the absolute values of the elementary products it is made of (a forward error bound of
-    any floating-point evaluation of that element is a small multiple of roundoff times this),
-    and m_loss [C]: the same scale for the absolute error of each loss term."""
+    Returns dict(loss [C], f [C], S [C,N], W = dl/dS [C,N], a = dl/df [C], q [C,dim] (the composed
+    operand that meets the negatives), g_s, g_r (or None), g_d [C,dim], g_neg [N,dim])."""
     if side_is_dst:
         q = compose_u(score, s, r, rounded) if score == TRANSE else compose_u(score, s, r)       # meets destination-like rows
         other = d
@@ -169,7 +153,7 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitu
         q = compose_v(score, r, d, rounded) if score == TRANSE else compose_v(score, r, d)       # meets source-like rows
         other = s
     if score == TRANSE:
-        return _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, with_magnitudes)
+        return _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs)
     f = np.sum(q * other, axis=1)
     S = q @ negs.T
     l, a, W = side_loss(loss, f, S, neg_weight)
@@ -182,27 +166,10 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, with_magnitu
     else:
         g_d, g_r = chain_from_v(score, g_q, r, d)
         g_s = g_other
-    out = dict(loss=l, f=f, S=S, W=W, g_s=g_s, g_r=g_r, g_d=g_d, g_neg=g_neg)
-    if with_magnitudes:
-        x = s if side_is_dst else d
-        aq = abs_compose(score, x, r)
-        # W_ek and a_e are functions of score differences, so they carry the absolute rounding error of
-        # the scores, which scales with A_ek = sum_j |q_ej| |theta_kj| rather than with |S_ek|: about
-        # 8 roundoffs times the row's largest A (twice a dot product's few-roundoff error, once for S_ek
-        # and once for the row's log-sum), i.e. max A / 4 in the callers' unit of 32 roundoffs
-        spread = np.maximum((aq @ np.abs(negs).T).max(axis=1), np.sum(aq * np.abs(other), axis=1)) / 4.0
-        Wm = np.abs(W) * (1.0 + spread)[:, None]
-        am = np.abs(a) * (1.0 + spread)
-        m_q = am[:, None] * np.abs(other) + Wm @ np.abs(negs)
-        m_other = am[:, None] * aq
-        m_x = m_q if score == DOT else abs_compose(score, r, m_q)
-        m_r = None if score == DOT else abs_compose(score, x, m_q)
-        out.update(m_neg=Wm.T @ aq, m_r=m_r, m_loss=spread,
-                   m_s=m_x if side_is_dst else m_other, m_d=m_other if side_is_dst else m_x)
-    return out
+    return dict(loss=l, f=f, S=S, W=W, a=a, q=q, g_s=g_s, g_r=g_r, g_d=g_d, g_neg=g_neg)
 
 
-def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, with_magnitudes):
+def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs):
     """chunk_side for the translational score: pair score -|q - row|_1,
     d(pair)/dq = -sign(q - row), d(pair)/drow = +sign(q - row)."""
     f = -np.abs(q - other).sum(axis=1)
@@ -214,20 +181,5 @@ def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, wit
     g_other = a[:, None] * sg_pos
     g_neg = np.einsum("ck,ckj->kj", W, sg)
     if side_is_dst:                                            # q = s + r
-        out = dict(loss=l, f=f, S=S, W=W, g_s=g_q, g_r=g_q, g_d=g_other, g_neg=g_neg)
-    else:                                                      # q = d - r
-        out = dict(loss=l, f=f, S=S, W=W, g_s=g_other, g_r=-g_q, g_d=g_q, g_neg=g_neg)
-    if with_magnitudes:
-        # every term is +-W_ek; W_ek = exp(S_ek - lse_e) carries the absolute rounding error of S, a sum
-        # of dim same-sign distances of total size |S|: up to dim/4 sequential fp32 additions of
-        # partial sums of that size (where the callers' unit of error is 32 roundoffs): a term's
-        # error scale is W_ek (1 + max_k |S_ek| dim / 128)
-        nz = np.abs(sg)
-        spread = np.maximum(np.abs(S).max(axis=1), np.abs(f)) * (q.shape[1] / 128.0)
-        Wm = np.abs(W) * (1.0 + spread)[:, None]
-        am = np.abs(a) * (1.0 + spread)
-        m_q = am[:, None] * np.abs(sg_pos) + np.einsum("ck,ckj->cj", Wm, nz)
-        m_other = am[:, None] * np.abs(sg_pos)
-        out.update(m_neg=np.einsum("ck,ckj->kj", Wm, nz), m_r=m_q, m_loss=spread,
-                   m_s=m_q if side_is_dst else m_other, m_d=m_other if side_is_dst else m_q)
-    return out
+        return dict(loss=l, f=f, S=S, W=W, a=a, q=q, g_s=g_q, g_r=g_q, g_d=g_other, g_neg=g_neg)
+    return dict(loss=l, f=f, S=S, W=W, a=a, q=q, g_s=g_other, g_r=-g_q, g_d=g_q, g_neg=g_neg)    # q = d - r

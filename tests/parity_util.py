@@ -4,8 +4,11 @@ from __future__ import annotations
 
 import numpy as np
 
+import os
+
 from oracle import model
 from oracle.bucket import OracleConfig, Tables, train_batch
+from tests.error_model import BatchMagnitudes
 
 # Tolerances (spec: scores 1e-5 relative in fp32, embeddings 1e-5 relative).
 #
@@ -26,8 +29,8 @@ from oracle.bucket import OracleConfig, Tables, train_batch
 # The error of an fp32 dot product grows with the square root of its length: KAPPA is 32 roundoffs
 # up to dim 128 and grows like sqrt(dim / 128) beyond (45 roundoffs at 256, 57 at 400, 64 at 512).
 # Softmax weights and dl/df are functions of score differences and inherit the absolute error of the
-# fp32 scores, which scales with A = sum_j |q_j| |theta_j| and not with the score: the oracle widens
-# their magnitudes by (1 + max A / 4) per row (8 roundoffs times A; 1.25 at the benchmark workloads'
+# fp32 scores, which scales with A = sum_j |q_j| |theta_j| and not with the score: the error model
+# (tests/error_model.py) widens their magnitudes by (1 + max A / 4) per row (8 roundoffs times A; 1.25 at the benchmark workloads'
 # initial scale, two orders of magnitude once scores reach the hundreds), and the batch loss is allowed
 # KAPPA * sum_e max A_e / 4 beside its 1e-5 relative bound.  For the translational score the same role
 # is played by max |S| dim / 128.
@@ -44,27 +47,37 @@ def kappa_for(dim: int) -> float:
 
 
 class OracleRun:
-    """Trains batches with the oracle and accumulates the forward-error allowance per element."""
+    """Trains batches with the oracle and accumulates the forward-error allowance per element
+    (the allowance comes from tests/error_model.py, which watches the oracle's chunks; the oracle
+    itself computes the method only).
 
-    def __init__(self, cfg: OracleConfig, node: np.ndarray, rel):
+    sparse=True keeps no dense per-partition allowance arrays: after each train_bucket call
+    `last` maps a partition (or "rel") to (rows, allowance on embeddings, allowance on state) of
+    the rows the call's LAST batch touched -- for tables too large to shadow three times."""
+
+    def __init__(self, cfg: OracleConfig, node: np.ndarray, rel, sparse: bool = False, tables: Tables = None):
         self.cfg = cfg
-        self.tab = Tables(cfg, node, rel)
+        self.tab = tables if tables is not None else Tables(cfg, node, rel)
+        self.sparse = sparse
         rp, d = cfg.rows_per_partition, cfg.dim
         n = cfg.num_partitions
-        self.fe_node = [np.zeros((rp, d)) for _ in range(n)]      # allowance on embeddings
-        self.fs_node = [np.zeros((rp, d)) for _ in range(n)]      # allowance on optimiser state
+        if not sparse:
+            self.fe_node = [np.zeros((rp, d)) for _ in range(n)]      # allowance on embeddings
+            self.fs_node = [np.zeros((rp, d)) for _ in range(n)]      # allowance on optimiser state
+            self.touched_node = [np.zeros(rp, bool) for _ in range(n)]
         self.fe_rel = np.zeros(self.tab.RE.shape)
         self.fs_rel = np.zeros(self.tab.RE.shape)
-        self.touched_node = [np.zeros(rp, bool) for _ in range(n)]
         self.touched_rel = np.zeros(self.tab.RE.shape[0], bool)
+        self.last = {}
         self.loss = 0.0
 
-    def _allow(self, fe, fs, state, rows, g, mag):
+    def _allowances(self, state, rows, g, mag):
         lr, eps = self.cfg.lr, self.cfg.eps
         s_new = state[rows].astype(np.float64)               # after the update
         kappa = kappa_for(self.cfg.dim)
-        fe[rows] += lr * kappa * mag / (np.sqrt(s_new) + eps)
-        fs[rows] += 2.0 * np.abs(g) * kappa * mag + (kappa * mag) ** 2      # |(G + e)^2 - G^2| <= 2 |G| e + e^2
+        fe = lr * kappa * mag / (np.sqrt(s_new) + eps)
+        fs = 2.0 * np.abs(g) * kappa * mag + (kappa * mag) ** 2      # |(G + e)^2 - G^2| <= 2 |G| e + e^2
+        return fe, fs
 
     def set_state(self, node_E, node_S, rel_E=None, rel_S=None):
         """Restart from given tables (global node order) and clear the allowances."""
@@ -74,9 +87,10 @@ class OracleRun:
             lo, hi = p * rp, min(cfg.num_nodes, (p + 1) * rp)
             self.tab.E[p][: hi - lo] = node_E[lo:hi]
             self.tab.S[p][: hi - lo] = node_S[lo:hi]
-            self.fe_node[p][:] = 0
-            self.fs_node[p][:] = 0
-            self.touched_node[p][:] = False
+            if not self.sparse:
+                self.fe_node[p][:] = 0
+                self.fs_node[p][:] = 0
+                self.touched_node[p][:] = False
         if rel_E is not None:
             self.tab.RE[:] = rel_E
             self.tab.RS[:] = rel_S
@@ -92,19 +106,32 @@ class OracleRun:
         loss = 0.0
         self.last_loss_allowance = 0.0       # of this call's loss sum, absolute
         for b in range(batch_begin, nb):
-            rec = {}
+            watch = BatchMagnitudes(cfg.score, i == j)
+            rec = {"observer": watch}
             loss += train_batch(self.tab, i, j, edges, b, epoch, record=rec)
-            self.last_loss_allowance += kappa_for(cfg.dim) * rec["loss_magnitude"]
+            self.last_loss_allowance += kappa_for(cfg.dim) * watch.loss_magnitude
             node, rel = rec["grads"]
-            mags = rec["grad_magnitudes"]
+            mags = watch.coalesced()
+            self.last = {}
             for slot, part in ((0, i), (1, j)):
                 if slot in node:
                     rows, g = node[slot]
-                    self._allow(self.fe_node[part], self.fs_node[part], self.tab.S[part], rows, g, mags[slot])
-                    self.touched_node[part][rows] = True
+                    mrows, mag = mags[slot]
+                    assert np.array_equal(rows, mrows)
+                    fe, fs = self._allowances(self.tab.S[part], rows, g, mag)
+                    if self.sparse:
+                        self.last[part] = (rows, fe, fs)
+                    else:
+                        self.fe_node[part][rows] += fe
+                        self.fs_node[part][rows] += fs
+                        self.touched_node[part][rows] = True
             if rel is not None:
                 rows, g = rel
-                self._allow(self.fe_rel, self.fs_rel, self.tab.RS, rows, g, mags[2])
+                mrows, mag = mags[2]
+                assert np.array_equal(rows, mrows)
+                fe, fs = self._allowances(self.tab.RS, rows, g, mag)
+                self.fe_rel[rows] += fe
+                self.fs_rel[rows] += fs
                 self.touched_rel[rows] = True
         self.loss += loss
         return loss
@@ -114,11 +141,28 @@ class OracleRun:
         return np.concatenate(src, 0)[: self.cfg.num_nodes]
 
 
-def compare_table(name, got, want, allowance, rtol, floor):
-    """Element-wise comparison: |got - want| <= rtol * max(|want|, floor) + allowance."""
+# Every comparison leaves a record here; tests/conftest.py prints the table at the end of the run
+# (and writes it to gpurun_out/parity_stats.json when that folder exists): how much of each comparison
+# ran at the plain spec bound, and how much of the allowance the rest needed.
+STATS = []
+
+
+def compare_table(name, got, want, allowance, rtol, floor, untested_above=None, kind=None):
+    """Element-wise comparison: |got - want| <= rtol * max(|want|, floor) + allowance.
+
+    Returns the comparison's statistics (also appended to STATS):
+      n                 elements compared
+      share_plain       share of them inside the plain bound rtol * max(|want|, floor) (the spec bar)
+      max_err_over_plain
+      allowance_used    largest (err - plain) / allowance over the elements outside the plain bound:
+                        the share of the allowance (hence of KAPPA) that this comparison needed
+      share_allowance_dominant   share of elements whose allowance exceeds their plain bound
+      share_untested    share of elements whose allowance exceeds `untested_above` (for embeddings: the learning
+                        rate, the size of a whole Adagrad step -- such an element passes whatever its value)"""
     assert got.shape == want.shape, (name, got.shape, want.shape)
     got64, want64 = got.astype(np.float64), want.astype(np.float64)
-    tol = rtol * np.maximum(np.abs(want64), floor) + allowance + 2 * FP32_SUBNORMAL_STEP
+    plain = rtol * np.maximum(np.abs(want64), floor) + 2 * FP32_SUBNORMAL_STEP
+    tol = plain + allowance
     err = np.abs(got64 - want64)
     viol = err > tol
     if viol.any():
@@ -126,8 +170,18 @@ def compare_table(name, got, want, allowance, rtol, floor):
         lines = [f"{tuple(int(x) for x in k)}: gpu={got64[tuple(k)]!r} oracle={want64[tuple(k)]!r} tol={tol[tuple(k)]:.3e}"
                  for k in idx]
         raise AssertionError(f"{name}: {int(viol.sum())} of {viol.size} elements outside tolerance; first: " + "; ".join(lines))
-    # how much of the comparison ran at the plain spec tolerance
-    return float((allowance > rtol * np.maximum(np.abs(want64), floor)).mean())
+    beyond = err > plain
+    allow = np.broadcast_to(np.asarray(allowance, np.float64), err.shape)
+    used = float(((err[beyond] - plain[beyond]) / allow[beyond]).max()) if beyond.any() else 0.0
+    st = dict(name=name, kind=kind or ("state" if floor == 0.0 else "emb"), n=int(err.size),
+              share_plain=float(1.0 - beyond.mean()) if err.size else 1.0,
+              max_err_over_plain=float((err / plain).max()) if err.size else 0.0,
+              allowance_used=used,
+              share_allowance_dominant=float((allow > plain).mean()) if err.size else 0.0,
+              share_untested=float((allow > untested_above).mean()) if (untested_above is not None and err.size) else 0.0,
+              test=os.environ.get("PYTEST_CURRENT_TEST", "").split(" ")[0])
+    STATS.append(st)
+    return st
 
 
 def check_scores(got, want, s64, r64, d64, score):

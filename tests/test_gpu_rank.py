@@ -12,6 +12,7 @@ import numpy as np
 import pytest
 
 from oracle import model, rank
+from tests import error_model
 
 pytestmark = pytest.mark.gpu
 
@@ -81,7 +82,7 @@ def _band(score, node, rel, src, r, dst, side):
     stay = E[src] if side == DST else E[dst]
     if score == model.TRANSE:       # a sum of dim distances: 1e-5 of the sizes of its operands
         return 1e-5 * (np.abs(stay).sum(axis=1) + np.abs(R[r]).sum(axis=1) + np.abs(E).sum(axis=1).max())
-    q = np.abs(stay) if score == model.DOT else model.abs_compose(score, stay, R[r])
+    q = np.abs(stay) if score == model.DOT else error_model.abs_compose(score, stay, R[r])
     return 1e-5 * np.linalg.norm(q, axis=1) * np.linalg.norm(E, axis=1).max()
 
 
