@@ -26,8 +26,8 @@ from tests.error_model import BatchMagnitudes
 # and sum_k W_k = 1).  For an
 # element without cancellation (M ~ |G| ~ sqrt(S)) this adds 2e-7 to a tolerance of 1e-6;
 # it only matters where the gradient terms nearly cancel, which no fp32 order can reproduce.
-# The error of an fp32 dot product grows with the square root of its length: KAPPA is 32 roundoffs
-# up to dim 128 and grows like sqrt(dim / 128) beyond (45 roundoffs at 256, 57 at 400, 64 at 512).
+# The error of an fp32 dot product grows with the square root of its length: KAPPA (below) holds
+# up to dim 128 and grows like sqrt(dim / 128) beyond (x1.41 at 256, x1.77 at 400, x2 at 512).
 # Softmax weights and dl/df are functions of score differences and inherit the absolute error of the
 # fp32 scores, which scales with A = sum_j |q_j| |theta_j| and not with the score: the error model
 # (tests/error_model.py) widens their magnitudes by (1 + max A / 4) per row (8 roundoffs times A; 1.25 at the benchmark workloads'
@@ -38,12 +38,25 @@ from tests.error_model import BatchMagnitudes
 # nothing: every comparison allows two such steps on top.
 EMB_RTOL = 1e-5
 STATE_RTOL = 3e-5
-KAPPA = 32 * 2.0 ** -24        # ~1.9e-6
+# KAPPA, in roundoffs of 2^-24, is set from measurement with a factor of two of headroom: over every GPU parity
+# case of this repository (the table the test run prints: column "allow. used" is the largest share of the
+# allowance that any element outside the plain bound needed) the embedding tables used at most 5.3 roundoffs
+# times M, the optimiser-state tables 15.4 (both in one case: ComplEx, d = 128, scores in the thousands); at the
+# full-size workloads 1.5 and 2.2.  The atomic update mode stays inside the same allowance (0.8 / 9.2 roundoffs
+# measured).  No batch loss of a committed case left its plain 1e-5 bound; its allowance (needed by randomised
+# sweeps with initial standard deviations up to 4, scores of several hundred) is kept at 8 roundoffs.
+KAPPA_EMB = 12 * 2.0 ** -24
+KAPPA_STATE = 32 * 2.0 ** -24
+KAPPA_LOSS = 8 * 2.0 ** -24
 FP32_SUBNORMAL_STEP = 2.0 ** -149
 
 
-def kappa_for(dim: int) -> float:
-    return KAPPA * max(1.0, (dim / 128.0) ** 0.5)
+def _dim_growth(dim: int) -> float:
+    return max(1.0, (dim / 128.0) ** 0.5)
+
+
+def kappa_for(dim: int, what: str = "state") -> float:
+    return {"emb": KAPPA_EMB, "state": KAPPA_STATE, "loss": KAPPA_LOSS}[what] * _dim_growth(dim)
 
 
 class OracleRun:
@@ -74,9 +87,9 @@ class OracleRun:
     def _allowances(self, state, rows, g, mag):
         lr, eps = self.cfg.lr, self.cfg.eps
         s_new = state[rows].astype(np.float64)               # after the update
-        kappa = kappa_for(self.cfg.dim)
-        fe = lr * kappa * mag / (np.sqrt(s_new) + eps)
-        fs = 2.0 * np.abs(g) * kappa * mag + (kappa * mag) ** 2      # |(G + e)^2 - G^2| <= 2 |G| e + e^2
+        ke, ks = kappa_for(self.cfg.dim, "emb"), kappa_for(self.cfg.dim, "state")
+        fe = lr * ke * mag / (np.sqrt(s_new) + eps)
+        fs = 2.0 * np.abs(g) * ks * mag + (ks * mag) ** 2            # |(G + e)^2 - G^2| <= 2 |G| e + e^2
         return fe, fs
 
     def set_state(self, node_E, node_S, rel_E=None, rel_S=None):
@@ -109,7 +122,7 @@ class OracleRun:
             watch = BatchMagnitudes(cfg.score, i == j)
             rec = {"observer": watch}
             loss += train_batch(self.tab, i, j, edges, b, epoch, record=rec)
-            self.last_loss_allowance += kappa_for(cfg.dim) * watch.loss_magnitude
+            self.last_loss_allowance += kappa_for(cfg.dim, "loss") * watch.loss_magnitude
             node, rel = rec["grads"]
             mags = watch.coalesced()
             self.last = {}
@@ -182,6 +195,18 @@ def compare_table(name, got, want, allowance, rtol, floor, untested_above=None, 
               test=os.environ.get("PYTEST_CURRENT_TEST", "").split(" ")[0])
     STATS.append(st)
     return st
+
+
+def check_loss(name, got, want, allowance, rtol=1e-5):
+    """Batch (or bucket) loss: |got - want| <= rtol * |want| + allowance; records how much of the allowance was used."""
+    err = abs(got - want)
+    plain = rtol * abs(want)
+    assert err <= plain + allowance, (name, got, want, allowance)
+    used = (err - plain) / allowance if (err > plain and allowance > 0) else 0.0
+    STATS.append(dict(name=name, kind="loss", n=1, share_plain=1.0 if err <= plain else 0.0,
+                      max_err_over_plain=err / plain if plain > 0 else 0.0, allowance_used=used,
+                      share_allowance_dominant=1.0 if allowance > plain else 0.0, share_untested=0.0,
+                      test=os.environ.get("PYTEST_CURRENT_TEST", "").split(" ")[0]))
 
 
 def check_scores(got, want, s64, r64, d64, score):

@@ -5,7 +5,7 @@ import pytest
 
 from oracle import model, negatives
 from oracle.bucket import OracleConfig, Tables, score_edges
-from tests.parity_util import EMB_RTOL, STATE_RTOL, OracleRun, check_scores, compare_table
+from tests.parity_util import EMB_RTOL, STATE_RTOL, OracleRun, check_loss, check_scores, compare_table
 
 pytestmark = pytest.mark.gpu
 
@@ -181,7 +181,40 @@ def test_single_sweep_kernel_out_of_range_chunks(monkeypatch, in_place):
     _check_every_batch(c)
 
 
-def _check_every_batch(c):
+def _beyond_reference(c, node, rel, edges, b, limit, epoch=1):
+    """Which workgroups (corrupted side x chunk; one row tile per chunk here) of batch b hold a score more than
+    `limit` above their row's reference, the row maximum over the first tile of negatives (every T-th negative
+    of the chunk, T = number of 64-negative tiles) -- or, in the variant that counts it, a positive score that
+    far above it.  float64 scores from the given tables; returns (flags, margins)."""
+    cfg = _ocfg(c)
+    rp = cfg.rows_per_partition
+    e = edges[b * c["B"]:(b + 1) * c["B"]]
+    neg = negatives.batch_negatives(cfg, epoch, c["i"], c["j"], b, e, edges)
+    tiles = -(-c["N"] // 64)
+    s = node[c["i"] * rp + e[:, 0]].astype(np.float64)
+    d = node[c["j"] * rp + e[:, 2]].astype(np.float64)
+    r = rel[e[:, 1]].astype(np.float64)
+    flags, margins = [], []
+    for si, side in enumerate(negatives.sides_of(cfg)):
+        is_dst = side == negatives.SIDE_DST
+        q = model.compose_u(c["score"], s, r) if is_dst else model.compose_v(c["score"], r, d)
+        f = np.sum(q * (d if is_dst else s), axis=1)
+        part = c["j"] if is_dst else c["i"]
+        for ch in range(neg.shape[1]):
+            sl = slice(ch * c["C"], min(e.shape[0], (ch + 1) * c["C"]))
+            S = q[sl] @ node[part * rp + neg[si, ch]].astype(np.float64).T
+            ref = S[:, ::tiles].max(axis=1)
+            m = (S.max(axis=1) - ref).max()
+            if c["loss"] == SOFTMAX_POS:
+                m = max(m, (f[sl] - ref).max())
+            margins.append(m)
+            flags.append(m > limit)
+    return flags, np.array(margins)
+
+
+def _check_every_batch(c, beyond_limit=None):
+    """beyond_limit: also check, batch by batch, the library's count of workgroups that met a score beyond
+    their softmax reference by more than this limit against the prediction from the tables before the batch."""
     node, rel, edges = _inputs(c)
     L, ctx = _gpu_ctx(c, node, rel)
     try:
@@ -192,29 +225,61 @@ def _check_every_batch(c):
         nb = -(-c["m"] // c["B"])
         before = _read_all(L, ctx, c)
         assert np.array_equal(before[0], node)
+        seen = []
         for b in range(nb):
             run.set_state(*before)
+            if beyond_limit is not None:
+                flags, margins = _beyond_reference(c, before[0], before[2], edges, b, beyond_limit)
+                assert (np.abs(margins - beyond_limit) > 1e-2).all()        # no workgroup sits on the limit itself
+                L.legend_fallback_chunks_read(ctx)
             stats = L.legend_train_bucket_range(ctx, i, j, edges, epoch=1, batch_begin=b, batch_end=b + 1)
+            if beyond_limit is not None:
+                assert L.legend_fallback_chunks_read(ctx) == sum(flags), (b, sum(flags), len(flags))
+                seen.append((sum(flags), len(flags)))
             want_loss = run.train_bucket(i, j, edges, epoch=1, batch_begin=b, max_batches=1)
             assert stats["batches"] == 1 and stats["edges"] == min(c["B"], c["m"] - b * c["B"])
-            assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss) + run.last_loss_allowance, (b, stats["loss_sum"], want_loss)
+            check_loss(f"batch {b} loss", stats["loss_sum"], want_loss, run.last_loss_allowance)
             after = _read_all(L, ctx, c)
             touched = np.concatenate(run.touched_node, 0)[: c["V"]]
-            compare_table(f"batch {b} node embeddings", after[0], run.tab.node_table(0), run.node_allowance(0), EMB_RTOL, 0.1)
+            compare_table(f"batch {b} node embeddings", after[0], run.tab.node_table(0), run.node_allowance(0), EMB_RTOL, 0.1, untested_above=0.1)
             compare_table(f"batch {b} node state", after[1], run.tab.node_table(1), run.node_allowance(1), STATE_RTOL, 0.0)
             # rows nothing addressed are bit-identical to what they were before the batch
             assert np.array_equal(after[0][~touched], before[0][~touched])
             assert np.array_equal(after[1][~touched], before[1][~touched])
             assert touched.any() and (after[0][touched] != before[0][touched]).any()
             if c["score"]:
-                compare_table(f"batch {b} relation embeddings", after[2], run.tab.RE, run.fe_rel, EMB_RTOL, 0.1)
+                compare_table(f"batch {b} relation embeddings", after[2], run.tab.RE, run.fe_rel, EMB_RTOL, 0.1, untested_above=0.1)
                 compare_table(f"batch {b} relation state", after[3], run.tab.RS, run.fs_rel, STATE_RTOL, 0.0)
                 assert np.array_equal(after[2][~run.touched_rel], before[2][~run.touched_rel])
             else:
                 assert np.array_equal(after[2], before[2]) and not after[3].any()
             before = after
+        return seen
     finally:
         L.legend_destroy(ctx)
+
+
+# The same recipe (one node row in 64 four times larger) with the tables scaled until the kernel's own
+# limit of 110 is passed in some chunks of every batch and not in others: no knob lowered.
+_BEYOND_CASES = [
+    dict(_case("distmult_d100_both_hot_rows", DISTMULT, SOFTMAX, BOTH, 12_000, 7, 100, 2, 0, 1, 1_000, 50, 300, 0, 2_500, 0.9),
+         hot_every=64, hot_scale=4.0),
+    dict(_case("complex_d100_n1000_hot_rows", COMPLEX, SOFTMAX, DST, 12_000, 9, 100, 2, 1, 0, 1_000, 50, 1_000, 200, 2_500, 0.75),
+         hot_every=64, hot_scale=4.0),
+    dict(_case("dot_d100_softmax_pos_hot_rows", DOT, SOFTMAX_POS, DST, 12_000, 0, 100, 2, 0, 1, 1_000, 50, 300, 0, 2_500, 1.05),
+         hot_every=64, hot_scale=4.0),
+]
+
+
+@pytest.mark.parametrize("c", _BEYOND_CASES, ids=[c["name"] for c in _BEYOND_CASES])
+def test_single_sweep_kernel_scores_beyond_the_reference_at_the_real_limit(c):
+    """DistMult (both sides), ComplEx (all eight steps of negatives) and the Eq. 1 variant with the positive
+    inside the log-sum-exp, with scores in the hundreds: in every batch some workgroups meet a score more than
+    110 above the reference taken from their first tile of negatives and others do not (in the first batch and
+    again later; never all of them); the library's count of them equals the prediction, and every batch matches
+    the oracle element by element."""
+    seen = _check_every_batch(c, beyond_limit=110.0)
+    assert 0 < seen[0][0] < seen[0][1] and all(k < n for k, n in seen) and sum(k for k, _ in seen[1:]) > 0, seen
 
 
 _ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11] + [c for c in CASES if c["name"] == "transe_d100_both"]
@@ -223,8 +288,7 @@ _ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11] + [c for c in CASES if c["n
 @pytest.mark.parametrize("c", _ATOMIC_CASES, ids=[c["name"] for c in _ATOMIC_CASES])
 def test_atomic_mode_every_batch_matches_oracle(c):
     """The atomic update mode computes the same batch step; its gradient sums are fp32 in
-    arrival order instead of fp64 in a fixed order, so the rounding allowance is four times
-    wider (a hub row adds thousands of terms in fp32)."""
+    arrival order instead of fp64 in a fixed order.  Same bar as the deterministic mode."""
     node, rel, edges = _inputs(c)
     L, ctx = _gpu_ctx(c, node, rel, update_mode=1)
     try:
@@ -238,16 +302,16 @@ def test_atomic_mode_every_batch_matches_oracle(c):
             run.set_state(*before)
             stats = L.legend_train_bucket_range(ctx, i, j, edges, epoch=1, batch_begin=b, batch_end=b + 1)
             want_loss = run.train_bucket(i, j, edges, epoch=1, batch_begin=b, max_batches=1)
-            assert abs(stats["loss_sum"] - want_loss) <= 1e-5 * abs(want_loss) + run.last_loss_allowance
+            check_loss(f"batch {b} loss", stats["loss_sum"], want_loss, run.last_loss_allowance)
             after = _read_all(L, ctx, c)
             touched = np.concatenate(run.touched_node, 0)[: c["V"]]
-            compare_table(f"batch {b} node embeddings", after[0], run.tab.node_table(0), 4 * run.node_allowance(0), EMB_RTOL, 0.1)
-            compare_table(f"batch {b} node state", after[1], run.tab.node_table(1), 4 * run.node_allowance(1), STATE_RTOL, 0.0)
+            compare_table(f"batch {b} node embeddings", after[0], run.tab.node_table(0), run.node_allowance(0), EMB_RTOL, 0.1, untested_above=0.1)
+            compare_table(f"batch {b} node state", after[1], run.tab.node_table(1), run.node_allowance(1), STATE_RTOL, 0.0)
             assert np.array_equal(after[0][~touched], before[0][~touched])
             assert np.array_equal(after[1][~touched], before[1][~touched])
             if c["score"]:
-                compare_table(f"batch {b} relation embeddings", after[2], run.tab.RE, 4 * run.fe_rel, EMB_RTOL, 0.1)
-                compare_table(f"batch {b} relation state", after[3], run.tab.RS, 4 * run.fs_rel, STATE_RTOL, 0.0)
+                compare_table(f"batch {b} relation embeddings", after[2], run.tab.RE, run.fe_rel, EMB_RTOL, 0.1, untested_above=0.1)
+                compare_table(f"batch {b} relation state", after[3], run.tab.RS, run.fs_rel, STATE_RTOL, 0.0)
             before = after
     finally:
         L.legend_destroy(ctx)
