@@ -139,6 +139,58 @@ def generate_edges(w: Workload, seed: int, block: int = 1 << 24, progress=None):
     return src, rel, dst
 
 
+def _rank_cdf(x: np.ndarray, size: int, skew: Tuple[float, float]) -> np.ndarray:
+    """CDF of the rank density p(x) ~ (x+q)^(-s) on [0, size) at the points x (float64)."""
+    s, q = skew
+    x = np.asarray(x, np.float64)
+    if s == 0.0:
+        return x / size
+    if abs(s - 1.0) < 1e-12:
+        return np.log((x + q) / q) / np.log((size + q) / q)
+    a = q ** (1.0 - s)
+    b = (size + q) ** (1.0 - s)
+    return (np.power(x + q, 1.0 - s) - a) / (b - a)
+
+
+def generate_bucket_edges(w: Workload, seed: int, wanted):
+    """Edges of the buckets in `wanted` (pairs (i, j)) only, for graphs too large to generate whole.
+
+    The edges of generate_edges are independent draws with independent endpoints, so the edges of
+    bucket (i, j) are independent draws too: their number is Binomial(E, P(src in i) P(dst in j)), and
+    each endpoint follows the rank distribution restricted to its partition (rank -> node through the
+    same seeded permutation).  This samples exactly that law (another random stream than
+    generate_edges: the same distribution, not the same edges).
+    Returns ({(i, j): int32 [m_ij, 3]}, {(i, j): expected share of all edges})."""
+    n, rp = w.num_partitions, w.rows_per_partition
+    perm = np.random.default_rng([seed, 0xF]).permutation(w.num_nodes)
+    part_of_rank = perm // rp
+    cache = {}
+
+    def side(p, skew):
+        key = (p, skew)
+        if key not in cache:
+            ranks = np.flatnonzero(part_of_rank == p)
+            pmf = _rank_cdf(ranks + 1.0, w.num_nodes, skew) - _rank_cdf(ranks, w.num_nodes, skew)
+            cdf = np.cumsum(pmf)
+            mass = float(cdf[-1])
+            cache[key] = (ranks, cdf / mass, mass)
+        return cache[key]
+
+    out, share = {}, {}
+    for (i, j) in wanted:
+        rs, cs, ms = side(i, w.src_skew)
+        rd, cd, md = side(j, w.dst_skew)
+        rng = np.random.default_rng([seed, 0xB0C, i, j])
+        m = int(rng.binomial(w.num_edges, ms * md))
+        e = np.empty((m, 3), np.int32)
+        e[:, 0] = perm[rs[np.minimum(np.searchsorted(cs, rng.random(m), side="right"), rs.size - 1)]] - i * rp
+        e[:, 2] = perm[rd[np.minimum(np.searchsorted(cd, rng.random(m), side="right"), rd.size - 1)]] - j * rp
+        e[:, 1] = _sample_ranks(rng, m, w.num_relations, w.rel_skew) if w.num_relations > 1 else 0
+        out[(i, j)] = e
+        share[(i, j)] = ms * md
+    return out, share
+
+
 def bucket_edges(w: Workload, src: np.ndarray, rel: np.ndarray, dst: np.ndarray, progress=None):
     """Stable partition of the edges into n*n buckets.
 
