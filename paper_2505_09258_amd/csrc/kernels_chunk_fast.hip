@@ -10,10 +10,16 @@
 // blocks (64 x N values, the paper's "Intermediate Result 3") stay in the register file of the
 // workgroup: eight waves, 128 registers per lane each, one workgroup per compute unit.  After
 // the sweep the stored numerators are scaled by 1 / l_e and G_neg = W^T Q is formed straight from
-// the stored blocks.  If some S_en exceeds the first tile's row maximum by more than a limit
-// (110 unless overridden; the numerators stay far from overflow), the workgroup takes the exact
-// row maxima in a scores-only pass and runs the sweep once more; if a row sum is not finite it
-// writes nothing and flags itself, and the general two-sweep kernel redoes the chunk.
+// the stored blocks.  The reference is rescaled by exception (the online form of the softmax, paid
+// for only where it is needed): a wave whose 16 negatives of a tile hold a score more than a limit
+// (110 unless overridden; the numerators stay far from overflow) above the row's current reference
+// takes its own row maxima as the reference for its share of that tile and says so in LDS; the waves
+// that add the tile to G_Q bring every share to a common new reference (factors exp(ref - new) <= 1
+// on the W operands and on their accumulators) and publish it for the group's next tile.  Every
+// wave's reference per tile is kept in LDS, and after the sweep the stored numerators and both
+// groups' accumulators are brought to the final reference, the largest of all.  Nothing is ever
+// computed twice.  Only a row sum that is not finite makes the workgroup write nothing and flag
+// itself; the general two-sweep kernel then redoes the chunk.
 //
 // Work split (16x16x4 fp32 MFMA; g = lane / 16, l15 = lane % 16).  The eight waves form two
 // groups of four; the negatives are dealt into tiles of 64 (negative n sits in tile n mod T),
@@ -94,7 +100,8 @@ struct FastShape {
     static constexpr int q_floats = kFRow * QS;
     static constexpr int n_floats = 2 * kFTile * QS + 16;   // one tile per wave group; + slack: column blocks run past the last row
     static constexpr int w_floats = 2 * kFRow * kFWS > 16 * NJ * kFQT ? 2 * kFRow * kFWS : 16 * NJ * kFQT;
-    static constexpr size_t lds_bytes = sizeof(float) * (q_floats + n_floats + w_floats + 9 * kFRow + 16 + kIdsLds);
+    static constexpr int r_floats = 2 * kFMaxSteps * 4 * kFRow;   // every wave's softmax reference per tile and row
+    static constexpr size_t lds_bytes = sizeof(float) * (q_floats + n_floats + w_floats + 11 * kFRow + 48 + kIdsLds + r_floats);
 };
 
 // Four elements of an embedding row that are handled together: elements 4c..4c+3, or for
@@ -169,7 +176,7 @@ template <int SCORE, int D>
 __global__ void __launch_bounds__(kFThreads, 1)
 k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float* __restrict__ grad,
              double* __restrict__ loss_partial, uint32_t* __restrict__ redo, unsigned long long* __restrict__ redo_total,
-             float limit, int retry_in_place) {
+             float limit, int rescale_allowed) {
     using Sh = FastShape<D>;
     using Item = RowItem<SCORE, D>;
     constexpr int QS = Sh::QS, KG = Sh::KG, KT = Sh::KT, NJ = Sh::NJ, STEPS = Sh::STEPS;
@@ -185,8 +192,11 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     float* rowloss_s = logl_s + kFRow;          // [64]
     float* f_s = rowloss_s + kFRow;             // [64] positive scores
     float* mx_s = f_s + kFRow;                  // [4][64] per-wave row maxima of the first tile
-    uint32_t* flag_s = reinterpret_cast<uint32_t*>(mx_s + 4 * kFRow);    // [16]
-    int32_t* ids_s = reinterpret_cast<int32_t*>(flag_s + 16);            // [kIdsLds]
+    float* Rtab = mx_s + 4 * kFRow;             // [2][64] reference of each wave group's G_Q accumulators
+    uint32_t* flag_s = reinterpret_cast<uint32_t*>(Rtab + 2 * kFRow);    // [16]: 0..7 unused, 8 row sum not finite, 9 some reference was raised
+    uint32_t* bump_s = flag_s + 16;             // [2][16]: a wave of the group raised its reference in this tile
+    int32_t* ids_s = reinterpret_cast<int32_t*>(bump_s + 32);            // [kIdsLds]
+    float* refw_s = reinterpret_cast<float*>(ids_s + kIdsLds);           // [2][kFMaxSteps][4][64]
 
     const int tid = threadIdx.x;
     const int w = tid >> 6;
@@ -215,7 +225,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     const int64_t neg_base = side_base + (int64_t)g.roles * g.P + ((int64_t)c * g.T + t_row) * N;
 
     for (int k = tid; k < N; k += kFThreads) ids_s[k] = my_negs[k];         // N <= 1024 here
-    if (tid < 16) flag_s[tid] = 0;
+    if (tid < 48) flag_s[tid] = 0;              // flags and the per-tile marks behind them
 
     // ---- prologue: Q rows and positive scores ---------------------------------------------------
     // A row is cut into D/4 items of four elements; a thread takes up to ITEMS (row, item) pairs
@@ -321,8 +331,6 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 
     f32x4 P[kFMaxSteps][4];                   // the chunk's softmax numerators owned by this wave
     f32x4 accB[NJ];
-    float top;                                // largest S - reference seen
-    bool bad = false;
 
     // scores of all 64 rows against the wave's own 16 negatives of its group's tile in LDS;
     // columns past the last negative get -1e30
@@ -360,16 +368,12 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     };
 
     __syncthreads();                          // ids, Q and the positive scores are in LDS
-    // One pass in ordinary training.  If the sampled reference turns out too low for some score
-    // (or the positive, in the variant that counts it), the exact row maxima are taken in a
-    // scores-only pass and the sweep runs once more (a second copy of its code, EXACT): the
-    // workgroup pays, the launch does not.
-    auto sweep_and_sums = [&](auto EXACT) __attribute__((always_inline)) {
-    constexpr bool exact_ref = decltype(EXACT)::value;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) accB[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    top = -1e30f;
     if (tile_of(0) < ntiles) gather_issue(tile_of(0));
+    float* Rg = Rtab + grp * kFRow;           // reference of this group's accumulators, per row
+    // this wave's reference of tile i of its group, rows 0..63
+    auto refw_of = [&](int g2, int i, int w2) { return refw_s + ((g2 * kFMaxSteps + i) * 4 + w2) * kFRow; };
 
     // scores and numerators of tile i of this group; P[i] is written
     // With FIRST (tile 0, wave group 0) the reference is made on the way: the row maxima of this
@@ -387,7 +391,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         f32x4 acc[4];
         score_block(t, acc);
         float4 reff[4];
-        if (first && !exact_ref) {
+        if (first) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -416,21 +420,65 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 m.z = row + 2 < nrows ? m.z : 1e30f;
                 m.w = row + 3 < nrows ? m.w : 1e30f;
                 reff[r] = m;
-                if (wl == 0 && l15 == 0) *reinterpret_cast<float4*>(ref_s + row) = m;
+                if (wl == 0 && l15 == 0) {    // both groups' accumulators start at this reference
+                    *reinterpret_cast<float4*>(Rtab + row) = m;
+                    *reinterpret_cast<float4*>(Rtab + kFRow + row) = m;
+                }
+            }
+        }
+        // where this wave's reference of the tile is read from: the group's, or its own once raised
+        const float* refp = Rg;
+        float* own = refw_of(grp, i, wl);
+        if (first) {
+            if (l15 == 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) *reinterpret_cast<float4*>(own + 16 * r + 4 * gq) = reff[r];
             }
         } else {
+            // a score beyond the reference by more than the limit: this wave goes on with its own row
+            // maxima as the reference of its 16 negatives (never below the common one)
+            float over = -1e30f;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) reff[r] = lds4(ref_s + 16 * r + 4 * gq);
+            for (int r = 0; r < 4; ++r) {
+                const float4 rf = lds4(Rg + 16 * r + 4 * gq);
+                over = fmaxf(over, fmaxf(fmaxf(acc[r][0] - rf.x, acc[r][1] - rf.y), fmaxf(acc[r][2] - rf.z, acc[r][3] - rf.w)));
+                if (l15 == 0) *reinterpret_cast<float4*>(own + 16 * r + 4 * gq) = rf;
+            }
+            if (__builtin_expect(__ballot(over > limit) != 0ull, 0)) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float4 rf = lds4(Rg + 16 * r + 4 * gq);
+                    float mm[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float m = acc[r][v];
+                        m = fmaxf(m, wave_shfl_xor(m, 1));
+                        m = fmaxf(m, wave_shfl_xor(m, 2));
+                        m = fmaxf(m, wave_shfl_xor(m, 4));
+                        m = fmaxf(m, wave_shfl_xor(m, 8));
+                        mm[v] = m;
+                    }
+                    rf.x = fmaxf(rf.x, mm[0]); rf.y = fmaxf(rf.y, mm[1]); rf.z = fmaxf(rf.z, mm[2]); rf.w = fmaxf(rf.w, mm[3]);
+                    if (l15 == 0) *reinterpret_cast<float4*>(own + 16 * r + 4 * gq) = rf;
+                }
+                if (lane == 0) {
+                    bump_s[grp * 16 + i] = 1u;
+                    flag_s[9] = 1u;
+                    if (!rescale_allowed) flag_s[8] = 1u;      // test knob: hand the chunk to the two-sweep kernel instead
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                refp = own;
+            }
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float4 rf = reff[r];
+            const float4 rf = first ? reff[r] : lds4(refp + 16 * r + 4 * gq);
             const float refv[4] = {rf.x, rf.y, rf.z, rf.w};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float diff = acc[r][v] - refv[v];
-                top = fmaxf(top, diff);
-                const float p = fast_exp_lifted(diff);
+                const float p = fast_exp_lifted(acc[r][v] - refv[v]);
                 acc[r][v] = p;
                 Wg[(16 * r + 4 * gq + v) * kFWS + 16 * wl + l15] = p;
             }
@@ -438,14 +486,44 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         }
     };
     // G_Q += W tile x negatives tile of this group: wave wl has rows 16wl..16wl+15, all columns
-    auto accumulate_tile = [&](int i) __attribute__((always_inline)) {
+    auto accumulate_tile = [&](auto I) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
         const int t = tile_of(i);
         const float* wa = Wg + (16 * wl + l15) * kFWS + 4 * gq;
         const float* nbB = Ng + (4 * gq) * QS + l15;
+        // the four waves' shares of W are brought to one reference where a wave raised its own in this tile
+        const bool bumped = bump_s[grp * 16 + i] != 0u;      // uniform
+        const int arow = 16 * wl + l15;       // the row of this lane's A operands
+        if (__builtin_expect(bumped, 0)) {
+            float rnew = Rg[arow];
+#pragma unroll
+            for (int G = 0; G < 4; ++G) rnew = fmaxf(rnew, refw_of(grp, i, G)[arow]);
+            // the accumulators (rows 16wl + 4g + v) follow the reference
+            float4 ro = lds4(Rg + 16 * wl + 4 * gq), rn = ro;
+#pragma unroll
+            for (int G = 0; G < 4; ++G) {
+                const float4 o = lds4(refw_of(grp, i, G) + 16 * wl + 4 * gq);
+                rn.x = fmaxf(rn.x, o.x); rn.y = fmaxf(rn.y, o.y); rn.z = fmaxf(rn.z, o.z); rn.w = fmaxf(rn.w, o.w);
+            }
+            const f32x4 down = f32x4{fast_exp(ro.x - rn.x), fast_exp(ro.y - rn.y), fast_exp(ro.z - rn.z), fast_exp(ro.w - rn.w)};
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) accB[j] *= down;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();  // every lane has read the old reference of the wave's rows
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (gq == 0) Rg[arow] = rnew;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
 #pragma unroll
         for (int G = 0; G < 4; ++G) {
             if (neg_of(t, 16 * G) < N) {      // uniform: the group has a live column
-                const float4 a4 = lds4(wa + 16 * G);
+                float4 a4 = lds4(wa + 16 * G);
+                if (__builtin_expect(bumped, 0)) {
+                    const float f = fast_exp(refw_of(grp, i, G)[arow] - Rg[arow]);     // <= 1
+                    a4.x *= f; a4.y *= f; a4.z *= f; a4.w *= f;
+                }
                 const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
@@ -474,16 +552,14 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                             score_tile(std::integral_constant<int, h / 2>{}, std::integral_constant<bool, h == 0>{});
                     }
                 } else {
-                    if constexpr (h == 0) {
-                        if (!exact_ref) __syncthreads();          // the barrier inside group 0's first tile
-                    }
+                    if constexpr (h == 0) __syncthreads();            // the barrier inside group 0's first tile
                     if constexpr (h >= 2) {
-                        if (tile_of(h / 2 - 1) < ntiles) accumulate_tile(h / 2 - 1);
+                        if (tile_of(h / 2 - 1) < ntiles) accumulate_tile(std::integral_constant<int, h / 2 - 1>{});
                     }
                 }
             } else {
                 if (grp == 0) {
-                    if (tile_of(h / 2) < ntiles) accumulate_tile(h / 2);
+                    if (tile_of(h / 2) < ntiles) accumulate_tile(std::integral_constant<int, h / 2>{});
                 } else {
                     if (tile_of(h / 2) < ntiles) score_tile(std::integral_constant<int, h / 2>{}, std::false_type{});
                 }
@@ -491,6 +567,27 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             __syncthreads();
         }
     });
+
+    // ---- final reference: the larger of the two groups' (and, in the variant that counts it, a positive
+    // score beyond it); where a reference was raised on the way, numerators and accumulators follow ------
+    if (tid < kFRow) {
+        float m = fmaxf(Rtab[tid], Rtab[kFRow + tid]);
+        if (bp.softmax_with_pos && tid < nrows && f_s[tid] - m > limit) {
+            m = f_s[tid];
+            flag_s[9] = 1u;
+            if (!rescale_allowed) flag_s[8] = 1u;
+        }
+        ref_s[tid] = m;
+    }
+    __syncthreads();
+    const bool raised = flag_s[9] != 0u;      // uniform
+    // exp(reference of this wave's tile u - final reference) for rows 16r + 4g + v: 1 unless some
+    // reference was raised on the way
+    auto to_final = [&](int u, int r) __attribute__((always_inline)) {
+        const float4 mf = lds4(ref_s + 16 * r + 4 * gq);
+        const float4 rw = lds4(refw_of(grp, u, wl) + 16 * r + 4 * gq);
+        return f32x4{fast_exp(rw.x - mf.x), fast_exp(rw.y - mf.y), fast_exp(rw.z - mf.z), fast_exp(rw.w - mf.w)};
+    };
 
     // ---- row sums: over the sweep steps in registers, over 16 lanes, then over the waves --------
     {
@@ -500,7 +597,11 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
             f32x4 l = f32x4{0.f, 0.f, 0.f, 0.f};
             static_for<0, kFMaxSteps>([&](auto U) {
                 constexpr int u = decltype(U)::value;
-                if (tile_of(u) < ntiles) l += P[u][r];
+                if (tile_of(u) < ntiles) {
+                    f32x4 t = P[u][r];
+                    if (__builtin_expect(raised, 0)) t *= to_final(u, r);
+                    l += t;
+                }
             });
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -512,7 +613,6 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 if (l15 == 0) Lw[w * kFRow + 16 * r + 4 * gq + v] = s;
             }
         }
-        if (__ballot(top > limit) != 0ull && lane == 0) flag_s[w] = 1u;
     }
     __syncthreads();
     if (tid < kFRow) {
@@ -522,15 +622,10 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         for (int ww = 0; ww < kFWaves; ++ww) sum += Lw[ww * kFRow + tid];
         const bool live = tid < nrows;
         const float neg_sum = sum;
-        float pos_term = 0.f;
-        if (bp.softmax_with_pos && live) {    // Eq. 1 variant: the positive score is one more term of the sum
-            const float dpos = f_s[tid] - ref_s[tid];
-            if (dpos > limit) flag_s[8] = 1u;
-            pos_term = fast_exp_lifted(fminf(dpos, 110.f));
-            sum += pos_term;
-        }
-        // the row maximum of the first tile alone contributes 2^-58, so the sum can only leave
-        // this range if a score is not finite
+        if (bp.softmax_with_pos && live)      // Eq. 1 variant: the positive score is one more term of the sum
+            sum += fast_exp_lifted(f_s[tid] - ref_s[tid]);
+        // no reference exceeds its row's largest term, which therefore contributes at least 2^-58: the
+        // sum can only leave this range if a score is not finite
         if (live && !(sum > 1e-30f && sum < 1e36f)) flag_s[8] = 1u;
         scale_s[tid] = live ? 1.f / sum : 0.f;
         logl_s[tid] = live ? logf(sum) : 0.f;
@@ -539,63 +634,10 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         mx_s[tid] = live ? -neg_sum / sum : 0.f;
     }
     __syncthreads();
-    bad = flag_s[8] != 0u;
-#pragma unroll
-    for (int ww = 0; ww < kFWaves; ++ww) bad |= flag_s[ww] != 0u;
-    };
-    sweep_and_sums(std::false_type{});
-    if (__builtin_expect(bad && retry_in_place, 0)) {
-    // ---- exact row maxima: scores only, every wave on its own gathered rows, no workgroup barrier
-        if (tid == 0) atomicAdd(redo_total, 1ull);
-        f32x4 mxv[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) mxv[r] = f32x4{-1e30f, -1e30f, -1e30f, -1e30f};
-        if (tile_of(0) < ntiles) gather_issue(tile_of(0));
-        for (int i = 0; tile_of(i) < ntiles; ++i) {
-            const int t = tile_of(i);
-            gather_commit(t);
-            if (tile_of(i + 1) < ntiles) gather_issue(t + 2);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            f32x4 acc[4];
-            score_block(t, acc);
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) mxv[r][v] = fmaxf(mxv[r][v], acc[r][v]);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
-        float* Mw = Ws;                       // [8 waves][64 rows]
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float m = mxv[r][v];
-                m = fmaxf(m, wave_shfl_xor(m, 1));
-                m = fmaxf(m, wave_shfl_xor(m, 2));
-                m = fmaxf(m, wave_shfl_xor(m, 4));
-                m = fmaxf(m, wave_shfl_xor(m, 8));
-                if (l15 == 0) Mw[w * kFRow + 16 * r + 4 * gq + v] = m;
-            }
-        }
-        __syncthreads();
-        if (tid < kFRow) {
-            float m = Mw[tid];
-#pragma unroll
-            for (int ww = 1; ww < kFWaves; ++ww) m = fmaxf(m, Mw[ww * kFRow + tid]);
-            if (bp.softmax_with_pos) m = fmaxf(m, f_s[tid]);
-            ref_s[tid] = tid < nrows ? m : 1e30f;
-        }
-        if (tid < 16) flag_s[tid] = 0;
-        __syncthreads();
-        sweep_and_sums(std::true_type{});
-    }
+    const bool bad = flag_s[8] != 0u;
     if (tid == 0) {
         redo[blockIdx.x] = bad ? 1u : 0u;
-        if (bad) atomicAdd(redo_total, 1ull);
+        if (bad || raised) atomicAdd(redo_total, 1ull);
     }
     if (bad) return;                          // uniform: nothing has been written yet
 
@@ -611,7 +653,11 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         const f32x4 sc = f32x4{sc4.x, sc4.y, sc4.z, sc4.w};
         static_for<0, kFMaxSteps>([&](auto U) {
             constexpr int u = decltype(U)::value;
-            if (tile_of(u) < ntiles) P[u][r] *= sc;
+            if (tile_of(u) < ntiles) {
+                f32x4 k = sc;
+                if (__builtin_expect(raised, 0)) k *= to_final(u, r);
+                P[u][r] *= k;
+            }
         });
     }
     __syncthreads();
@@ -679,12 +725,17 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
 
     // ---- epilogue: the two halves of G_Q to LDS, chain rule, gradient rows of the positives -----
     float* Gs = Ns + grp * (kFRow * QS);      // [2][64][QS]: one partial sum per wave group
+    f32x4 down = f32x4{1.f, 1.f, 1.f, 1.f};   // this group's accumulators to the final reference
+    if (__builtin_expect(raised, 0)) {
+        const float4 ra = lds4(Rg + 16 * wl + 4 * gq), ma = lds4(ref_s + 16 * wl + 4 * gq);
+        down = f32x4{fast_exp(ra.x - ma.x), fast_exp(ra.y - ma.y), fast_exp(ra.z - ma.z), fast_exp(ra.w - ma.w)};
+    }
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int col = 16 * j + l15;
         if (col < d) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Gs[(16 * wl + 4 * gq + v) * QS + col] = accB[j][v];
+            for (int v = 0; v < 4; ++v) Gs[(16 * wl + 4 * gq + v) * QS + col] = accB[j][v] * down[v];
         }
     }
     __syncthreads();
@@ -752,7 +803,7 @@ static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const Buck
         configured.set();
     }
     hipLaunchKernelGGL((k_chunk_fast<SC, D>), grid, block, lds, st, g, bp, ws.neg_ids, ws.grad,
-                       ws.loss_partial, ws.redo, ws.redo_total, ws.fast_limit, ws.fast_no_retry ? 0 : 1);
+                       ws.loss_partial, ws.redo, ws.redo_total, ws.fast_limit, ws.fast_no_rescale ? 0 : 1);
     return hipGetLastError();
 }
 

@@ -97,8 +97,8 @@ struct Workspace {
     float*    gemm_a;         // [sides][P] dL/df
     float*    gemm_G;         // [sides][P][dim] G_Q
     int32_t   no_fast_path;   // LEGEND_NO_FAST_CHUNK=1: always use the general two-sweep kernel
-    int32_t   fast_no_retry;  // LEGEND_FAST_CHUNK_NO_RETRY=1: no second pass in place, every flagged chunk goes to the two-sweep kernel
-    float     fast_limit;     // largest S - f the single-sweep kernel accepts (LEGEND_FAST_CHUNK_LIMIT, default 110): largest score above the reference row maximum
+    int32_t   fast_no_rescale;  // LEGEND_FAST_CHUNK_NO_RESCALE=1: a chunk that would raise its softmax reference goes to the two-sweep kernel instead
+    float     fast_limit;     // how far above its row's current reference a score may lie before the single-sweep kernel raises the reference (LEGEND_FAST_CHUNK_LIMIT, default 110)
     double*   loss_sum;       // running bucket loss
     int64_t   cap_occ;
     int64_t   cap_wg;

@@ -664,8 +664,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     {
         const char* e = std::getenv("LEGEND_NO_FAST_CHUNK");
         w.no_fast_path = (e && e[0] == '1') ? 1 : 0;
-        const char* nr = std::getenv("LEGEND_FAST_CHUNK_NO_RETRY");
-        w.fast_no_retry = (nr && nr[0] == '1') ? 1 : 0;
+        const char* nr = std::getenv("LEGEND_FAST_CHUNK_NO_RESCALE");
+        w.fast_no_rescale = (nr && nr[0] == '1') ? 1 : 0;
         const char* lim = std::getenv("LEGEND_FAST_CHUNK_LIMIT");
         w.fast_limit = lim ? (float)std::atof(lim) : 110.f;
         if (!(w.fast_limit <= 110.f)) w.fast_limit = 110.f;   // a test knob: it can only tighten the limit

@@ -141,17 +141,17 @@ def test_every_batch_matches_oracle(c):
     _check_every_batch(c)
 
 
-@pytest.mark.parametrize("in_place", [True, False], ids=["second_pass_in_place", "handed_to_two_sweep_kernel"])
+@pytest.mark.parametrize("in_place", [True, False], ids=["reference_raised_in_place", "handed_to_two_sweep_kernel"])
 def test_single_sweep_kernel_out_of_range_chunks(monkeypatch, in_place):
     """The single-sweep kernel takes the row maxima over its first tile of negatives (every T-th
-    negative of the chunk, T = number of 64-negative tiles) as the softmax reference.  A chunk in
-    which some score lies more than a limit above its row's reference is computed again: in place
-    with the exact row maxima, or (LEGEND_FAST_CHUNK_NO_RETRY=1, and always for scores that are
-    not finite) by the two-sweep kernel.  With the limit lowered to 1.25 the hot rows put some
-    chunks of every batch on either path."""
+    negative of the chunk, T = number of 64-negative tiles) as the softmax reference.  Where a
+    score lies more than a limit above its row's reference, the reference is raised on the way
+    (numerators and accumulators rescaled), or (LEGEND_FAST_CHUNK_NO_RESCALE=1, and always for
+    scores that are not finite) the chunk is handed to the two-sweep kernel.  With the limit
+    lowered to 1.25 the hot rows put some chunks of every batch on either path."""
     c, limit = _HOT_CASE, 1.25
     if not in_place:
-        monkeypatch.setenv("LEGEND_FAST_CHUNK_NO_RETRY", "1")
+        monkeypatch.setenv("LEGEND_FAST_CHUNK_NO_RESCALE", "1")
     node, rel, edges = _inputs(c)
     rp = -(-c["V"] // c["n"])
     tiles = -(-c["N"] // 64)
