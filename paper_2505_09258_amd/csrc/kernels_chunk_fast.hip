@@ -95,6 +95,15 @@ struct FastShape {
     static constexpr int KG = D / 16;                       // full groups of 16 along the dimension
     static constexpr int KT = (D % 16) / 4;                 // single steps of 4 after them
     static constexpr int NJ = (D + 15) / 16;                // 16-column blocks of a gradient row
+    // Columns of the G_Q accumulator blocks (B operand and result column of lane l15 in block j), chosen so
+    // that a lane's B operands of several blocks are adjacent in a row of the negatives tile:
+    //   N4 groups of four blocks, block 4q + t holds column 64q + 4 l15 + t (one 128-bit LDS read per group),
+    //   then N2 (0 or 1) pair of blocks, block t of it holds column 64 N4 + 2 l15 + t (one 64-bit read),
+    //   then N1 single blocks holding column 64 N4 + 32 N2 + 16 q + l15.
+    static constexpr int N4 = D / 64;
+    static constexpr int N2 = (D - 64 * N4) / 32;
+    static constexpr int N1 = (D - 64 * N4 - 32 * N2 + 15) / 16;
+    static_assert(4 * N4 + 2 * N2 + N1 == NJ, "column blocks");
     static constexpr int LPR = 32;                          // lanes per gathered row (float4 each)
     static constexpr int STEPS = 16 / (kWave / LPR);        // a wave gathers 16 rows, two at a time
     static constexpr int q_floats = kFRow * QS;
@@ -180,6 +189,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     using Sh = FastShape<D>;
     using Item = RowItem<SCORE, D>;
     constexpr int QS = Sh::QS, KG = Sh::KG, KT = Sh::KT, NJ = Sh::NJ, STEPS = Sh::STEPS;
+    constexpr int N4 = Sh::N4, N2 = Sh::N2, N1 = Sh::N1;
     constexpr int d = D;
 
     extern __shared__ __align__(16) float smem[];
@@ -490,7 +500,6 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         constexpr int i = decltype(I)::value;
         const int t = tile_of(i);
         const float* wa = Wg + (16 * wl + l15) * kFWS + 4 * gq;
-        const float* nbB = Ng + (4 * gq) * QS + l15;
         // the four waves' shares of W are brought to one reference where a wave raised its own in this tile
         const bool bumped = bump_s[grp * 16 + i] != 0u;      // uniform
         const int arow = 16 * wl + l15;       // the row of this lane's A operands
@@ -527,10 +536,20 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
                 const float av[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const float* nrow = nbB + (16 * G + s) * QS;
+                    // row k = 16G + 4g + s of the negatives tile; this lane's columns of it (gq_col)
+                    const float* nrow = Ng + (16 * G + 4 * gq + s) * QS;
                     float b[NJ];
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) b[j] = nrow[16 * j];
+                    for (int q4 = 0; q4 < N4; ++q4) {
+                        const float4 x = lds4(nrow + 64 * q4 + 4 * l15);
+                        b[4 * q4] = x.x; b[4 * q4 + 1] = x.y; b[4 * q4 + 2] = x.z; b[4 * q4 + 3] = x.w;
+                    }
+                    if constexpr (N2 == 1) {
+                        const float2 x = *reinterpret_cast<const float2*>(nrow + 64 * N4 + 2 * l15);
+                        b[4 * N4] = x.x; b[4 * N4 + 1] = x.y;
+                    }
+#pragma unroll
+                    for (int q1 = 0; q1 < N1; ++q1) b[4 * N4 + 2 * N2 + q1] = nrow[64 * N4 + 32 * N2 + 16 * q1 + l15];
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) accB[j] = mfma16(av[s], b[j], accB[j]);
                 }
@@ -731,11 +750,18 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
         down = f32x4{fast_exp(ra.x - ma.x), fast_exp(ra.y - ma.y), fast_exp(ra.z - ma.z), fast_exp(ra.w - ma.w)};
     }
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        const int col = 16 * j + l15;
-        if (col < d) {
+    for (int v = 0; v < 4; ++v) {
+        float* grow = Gs + (16 * wl + 4 * gq + v) * QS;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Gs[(16 * wl + 4 * gq + v) * QS + col] = accB[j][v] * down[v];
+        for (int q4 = 0; q4 < N4; ++q4)       // columns 64q + 4 l15 .. + 3 (all below d: d >= 64 N4)
+            *reinterpret_cast<float4*>(grow + 64 * q4 + 4 * l15) =
+                make_float4(accB[4 * q4][v] * down[v], accB[4 * q4 + 1][v] * down[v], accB[4 * q4 + 2][v] * down[v], accB[4 * q4 + 3][v] * down[v]);
+        if constexpr (N2 == 1)
+            *reinterpret_cast<float2*>(grow + 64 * N4 + 2 * l15) = make_float2(accB[4 * N4][v] * down[v], accB[4 * N4 + 1][v] * down[v]);
+#pragma unroll
+        for (int q1 = 0; q1 < N1; ++q1) {
+            const int col = 64 * N4 + 32 * N2 + 16 * q1 + l15;
+            if (col < d) grow[col] = accB[4 * N4 + 2 * N2 + q1][v] * down[v];
         }
     }
     __syncthreads();
