@@ -1,5 +1,5 @@
-// Batch construction on the GPU (paper Sec. 2.1 stages 1-2, Sec. 3 step 3):
-// negative ids from a counter hash and the sort key of every gradient row.
+// Small helpers around a bucket call: validation of a bucket's edge ids, plain fills, and the seeded
+// initial embeddings (paper Sec. 3 steps 1-3).
 #include "legend_internal.h"
 #include "device_utils.h"
 
@@ -69,51 +69,6 @@ hipError_t launch_init_fill(hipStream_t st, float* out, int64_t rows, int32_t di
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(k_init_fill, dim3((unsigned)blocks), dim3(256), 0, st, out, rows, dim, row0,
                        hash_fold(seed, table_tag), scale);
-    return hipGetLastError();
-}
-
-// One thread per occurrence (gradient row) of the batch: its sort key, and for
-// negative rows the sampled id.  Index arithmetic only; no floating point.
-__global__ void __launch_bounds__(256)
-k_prepare(BatchGeom g, BucketParams bp, int32_t* __restrict__ neg_ids, uint32_t* __restrict__ keys) {
-    int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (o >= g.n_occ) return;
-    int si = (int)(o / g.per_side);
-    int64_t r = o - (int64_t)si * g.per_side;
-    int side = g.side_id[si];
-    const int32_t* eb = bp.edges + bp.batch_lo * 3;
-    uint32_t key;
-    if (r < g.P) {
-        key = (uint32_t)eb[r * 3 + 0];
-    } else if (r < 2 * (int64_t)g.P) {
-        key = bp.key_base_dst + (uint32_t)eb[(r - g.P) * 3 + 2];
-    } else if (g.roles == 3 && r < 3 * (int64_t)g.P) {
-        key = bp.key_base_rel + (uint32_t)eb[(r - 2 * (int64_t)g.P) * 3 + 1];
-    } else {
-        int64_t q = r - (int64_t)g.roles * g.P;
-        int k = (int)(q % g.N);
-        int64_t ct = q / g.N;
-        int t = (int)(ct % g.T);
-        int c = (int)(ct / g.T);
-        uint64_t h = hash_fold(hash_fold(hash_fold(bp.hash_prefix, (uint64_t)c), (uint64_t)side), (uint64_t)k);
-        int32_t id;
-        if (k < g.N - bp.num_degree_negs) {
-            uint64_t rows = (uint64_t)(side == 0 ? bp.rows_valid_dst : bp.rows_valid_src);
-            id = (int32_t)__umul64hi(h, rows);
-        } else {
-            uint64_t e = __umul64hi(h, (uint64_t)bp.m);
-            id = bp.edges[e * 3 + (side == 0 ? 2 : 0)];
-        }
-        key = (side == 0 ? bp.key_base_dst : 0u) + (uint32_t)id;
-        if (t == 0) neg_ids[((int64_t)si * g.nchunks + c) * g.N + k] = id;
-    }
-    keys[o] = key;
-}
-
-hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    if (g.n_occ <= 0) return hipSuccess;
-    unsigned blocks = (unsigned)((g.n_occ + 255) / 256);
-    hipLaunchKernelGGL(k_prepare, dim3(blocks), dim3(256), 0, st, g, bp, ws.neg_ids, ws.keys[0]);
     return hipGetLastError();
 }
 

@@ -1,12 +1,34 @@
-// Stable LSD radix sort of (key, occurrence index) pairs and the segment heads of the
-// sorted keys.  This is what makes the deterministic update mode deterministic: equal
-// keys keep their occurrence order, so the gradient rows of one table row are always
-// summed in the same order (paper Sec. 2.1 stage 6; the sorting itself is this
-// library's design, the paper does not describe its update kernel).
+// The index side of a batch: sort keys of the gradient rows (with the sampled negative ids), a stable
+// LSD radix sort of (key, occurrence index) pairs and the segment heads of the sorted keys.  This is
+// what makes the deterministic update mode deterministic: equal keys keep their occurrence order, so
+// the gradient rows of one table row are always summed in the same order (paper Sec. 2.1 stages 2 and
+// 6; the sorting itself is this library's design, the paper does not describe its update kernel).
+// Large batches: many short kernels of small workgroups (a histogram, a three-kernel scan and a scatter
+// per 8-bit digit), which slip in between the workgroups of the previous batch's kernels with little
+// harm.  (A version with a third of the launches -- 8192-key tiles, every scatter workgroup deriving its
+// offsets from the whole matrix of tile counts, no scan kernels -- needed less kernel time alone, 133 against
+// 180 us per c2 batch, and made the step slower, 1.06 against 1.00 ms: its 512-thread workgroups hold a compute
+// unit for 25 us each, and a batch-kernel workgroup needs the unit whole.)  A batch of at most
+// kSmallSortMax gradient rows is sorted, cut into segments and planned by one workgroup in one launch.
 #include "legend_internal.h"
 #include "device_utils.h"
+#include "index_side.h"
 
 namespace legend {
+
+// One thread per occurrence (gradient row) of the batch: its sort key, and for negative rows the sampled id.
+__global__ void __launch_bounds__(256)
+k_prepare(BatchGeom g, BucketParams bp, int32_t* __restrict__ neg_ids, uint32_t* __restrict__ keys) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o < g.n_occ) keys[o] = occurrence_key(g, bp, o, neg_ids);
+}
+
+hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    if (g.n_occ <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((g.n_occ + 255) / 256);
+    hipLaunchKernelGGL(k_prepare, dim3(blocks), dim3(256), 0, st, g, bp, ws.neg_ids, ws.keys[0]);
+    return hipGetLastError();
+}
 
 constexpr int kSortThreads = 256;
 constexpr int kSortItems = 8;
@@ -217,7 +239,7 @@ k_radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict
     }
 }
 
-hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf) {
+static hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf) {
     *out_buf = 0;
     if (n <= 0) return hipSuccess;
     int passes = (key_bits + 7) / 8;
@@ -238,7 +260,7 @@ hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace&
     return hipGetLastError();
 }
 
-hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws) {
+static hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws) {
     if (n <= 0) return hipSuccess;
     return scan_launch(st, 1, sorted_keys, n, ws.scan_tmp, ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total);
 }
@@ -246,7 +268,9 @@ hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_key
 // ------------------------------------------------------------------------------------------
 // Small batches (n <= kSmallSortMax): one workgroup sorts the pairs in LDS, emits the segment
 // heads and (deterministic mode) lists the rows with many gradient rows and their units, so a
-// latency-bound tiny batch pays one launch instead of some twenty.
+// latency-bound tiny batch pays one launch instead of some twenty.  (Making the keys in this kernel
+// as well was tried: one workgroup walking a few thousand occurrences, each with its 64-bit index
+// arithmetic and hashes, took longer than the launch it saved: 89 against 54 us per c1 batch.)
 // Same stable ranking as the multi-block scatter: wave w owns a contiguous quarter of the keys.
 // ------------------------------------------------------------------------------------------
 
@@ -408,13 +432,14 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
     }
 }
 
-hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf,
-                                    bool plan_long) {
+hipError_t launch_sort_and_segments(hipStream_t st, const BatchGeom& g, const BucketParams& bp, int key_bits,
+                                    const Workspace& ws, int* out_buf, bool plan_long) {
     *out_buf = 0;
+    const int64_t n = g.n_occ;
     if (n <= 0) return hipSuccess;
+    int passes = (key_bits + 7) / 8;
+    if (passes < 1) passes = 1;
     if (n <= kSmallSortMax) {
-        int passes = (key_bits + 7) / 8;
-        if (passes < 1) passes = 1;
         const size_t lds = (4 * (size_t)kSmallSortMax + 2 * 4 * kRadix + 8) * sizeof(uint32_t);
         static PerDeviceFlag attr_set;
         if (attr_set.pending()) {

@@ -81,7 +81,7 @@ struct Workspace {
     uint32_t* scan_tmp;       // block sums of the generic scan
     uint32_t* uniq_keys;      // [n_occ]
     uint32_t* seg_start;      // [n_occ + 1]
-    uint32_t* counters;       // [0] unique rows of the batch, [1] error flag, [2] long rows, [3] units of long rows
+    uint32_t* counters;       // [8]: [0] unique rows of the batch, [1] error flag, [2] long rows, [3] units of long rows
     uint32_t* long_list;      // unique-row indices of rows with many gradient rows
     uint32_t* unit_start;     // first unit of each long row (+ total)
     double*   long_partial;   // [units][dim] fp64 partial sums
@@ -124,19 +124,18 @@ constexpr uint64_t kInitTagNode = 0x6E6F6465ull, kInitTagRel = 0x72656C73ull;
 hipError_t launch_init_fill(hipStream_t st, float* out, int64_t rows, int32_t dim, int64_t row0, uint64_t seed,
                             uint64_t table_tag, float init_std);
 hipError_t launch_fill_u32(hipStream_t st, uint32_t* p, uint32_t v, int64_t n);
+// index side of a batch: keys and negative ids (launch_prepare), then the stable sort, the segment heads
+// and, with plan_long, the rows with many gradient rows and their units; the sorted occurrence
+// indices end up in ws.vals[*out_buf].  Batches of at most kSmallSortMax gradient rows do all of it in
+// the one launch of launch_sort_and_segments.
 hipError_t launch_prepare(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
-// sorts ws.keys[0]/vals[0] (n_occ entries); result buffer index returned in *out_buf
-hipError_t launch_sort(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf);
-hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sorted_keys, const Workspace& ws);
-// sort + segment heads; small inputs take a single-workgroup kernel, which with plan_long also lists
-// the long rows and their units (what launch_long_plan does for larger inputs)
-hipError_t launch_sort_and_segments(hipStream_t st, int64_t n, int key_bits, const Workspace& ws, int* out_buf,
-                                    bool plan_long);
+hipError_t launch_sort_and_segments(hipStream_t st, const BatchGeom& g, const BucketParams& bp, int key_bits,
+                                    const Workspace& ws, int* out_buf, bool plan_long);
+// long rows and their units from the segment bounds; nothing to do for n_occ <= kSmallSortMax
+hipError_t launch_long_plan(hipStream_t st, int64_t n_occ, const Workspace& ws);
 // redo = false: the batch computation; redo = true: second launch over the workgroups the single-sweep kernel flagged
 bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws, bool redo);
-// long rows and their units from the segment bounds; nothing to do for n_occ <= kSmallSortMax
-hipError_t launch_long_plan(hipStream_t st, int64_t n_occ, const Workspace& ws);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, bool long_rows);
 hipError_t launch_update_atomic(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);

@@ -129,6 +129,7 @@ struct legend_ctx {
     double prof_ms[KC_COUNT] = {0};
     int64_t prof_launches[KC_COUNT] = {0};
     int64_t batches_done = 0;
+    bool index_after_chunk = false;         // LEGEND_INDEX_AFTER_CHUNK=1: the next batch's index side starts when this batch's chunk kernel has finished, not when it is launched (a measurement knob)
     bool serial_sort = false;               // LEGEND_SERIAL_SORT=1: everything on the compute stream, batch after batch (for per-kernel timing)
     bool keep_loss = false;                 // epoch driver: do not reset the device loss sum per bucket
     bool part_tables_dirty = false;         // d_part_emb / d_part_state lag behind part_slot
@@ -455,7 +456,7 @@ int enqueue_index_side(legend_ctx* c, hipStream_t st, const BatchGeom& g, const 
     {
         ProfScope ps(c, KC_SORT, st);
         const bool plan_long = c->cfg.update_mode != LEGEND_UPDATE_ATOMIC;
-        HIP_TRY(c, launch_sort_and_segments(st, g.n_occ, c->key_bits, ws, sorted_buf, plan_long));
+        HIP_TRY(c, launch_sort_and_segments(st, g, bp, c->key_bits, ws, sorted_buf, plan_long));
         if (plan_long) HIP_TRY(c, launch_long_plan(st, g.n_occ, ws));
     }
     return LEGEND_OK;
@@ -521,6 +522,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     {
         const char* e = std::getenv("LEGEND_SERIAL_SORT");
         c->serial_sort = e && e[0] == '1';
+        const char* wc = std::getenv("LEGEND_INDEX_AFTER_CHUNK");
+        c->index_after_chunk = wc && wc[0] == '1';
     }
     c->nrel_rows = std::max(cfg->num_relations, 1);
     c->host_part.assign(c->n, nullptr);
@@ -651,7 +654,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     INIT_RC(dev_alloc(c, &w.scan_tmp, (size_t)std::max<int64_t>(nblk, (nblk * 256 + 2047) / 2048) + 2));
     INIT_RC(dev_alloc(c, &w.uniq_keys, (size_t)occ));
     INIT_RC(dev_alloc(c, &w.seg_start, (size_t)occ + 1));
-    INIT_RC(dev_alloc(c, &w.counters, 4));
+    INIT_RC(dev_alloc(c, &w.counters, 8));
     INIT_RC(dev_alloc(c, &w.long_list, (size_t)update_long_rows_capacity(occ)));
     INIT_RC(dev_alloc(c, &w.unit_start, (size_t)update_long_rows_capacity(occ) + 1));
     INIT_RC(dev_alloc(c, &w.long_partial, (size_t)update_long_units_capacity(occ) * c->d));
@@ -698,10 +701,10 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         INIT_RC(dev_alloc(c, &o.scan_tmp, (size_t)std::max<int64_t>(nblk, (nblk * 256 + 2047) / 2048) + 2));
         INIT_RC(dev_alloc(c, &o.uniq_keys, (size_t)occ));
         INIT_RC(dev_alloc(c, &o.seg_start, (size_t)occ + 1));
-        INIT_RC(dev_alloc(c, &o.counters, 4));
-        INIT_TRY(hipMemset(o.counters, 0, 4 * sizeof(uint32_t)));
+        INIT_RC(dev_alloc(c, &o.counters, 8));
+        INIT_TRY(hipMemset(o.counters, 0, 8 * sizeof(uint32_t)));
     }
-    INIT_TRY(hipMemset(w.counters, 0, 4 * sizeof(uint32_t)));
+    INIT_TRY(hipMemset(w.counters, 0, 8 * sizeof(uint32_t)));
     INIT_TRY(hipMemset(w.uniq_total, 0, sizeof(unsigned long long)));
     INIT_TRY(hipMemset(w.loss_sum, 0, sizeof(double)));
     INIT_TRY(hipDeviceSynchronize());
@@ -860,6 +863,10 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             BucketParams keep = bp;
             batch_params(b + 1, &gn);
             if (b > batch_begin) HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_updated[nxt], 0));
+            if (c->index_after_chunk) {
+                HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
+                HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_chunk_done, 0));
+            }
             rc = enqueue_index_side(c, c->aux, gn, bp, nxt ? c->ws_odd : c->ws, &sorted_of[nxt]);
             if (rc) return rc;
             HIP_TRY(c, hipEventRecord(c->ev_index[nxt], c->aux));
