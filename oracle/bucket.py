@@ -41,6 +41,7 @@ class OracleConfig:
     lr: float = 0.1
     eps: float = 1e-10
     neg_weight: float = -1.0      # logistic only; < 0 means 1 / num_negs
+    margin: float = 1.0           # margin loss only
     seed: int = 0
     round_composed: bool = True   # translational score: u, v as fp32 numbers (False only for derivative checks)
 
@@ -148,7 +149,7 @@ def batch_gradients(tab: Tables, i: int, j: int, bucket_edges: np.ndarray, b: in
             neg_rows = neg_table[ids].astype(np.float64)
             out = model.chunk_side(cfg.score, cfg.loss, cfg.w_neg, is_dst,
                                    s_all[sl], r_all[sl] if uses_rel else None, d_all[sl],
-                                   neg_rows, rounded=cfg.round_composed)
+                                   neg_rows, rounded=cfg.round_composed, margin=cfg.margin)
             loss += float(out["loss"].sum())
             node_keys[ti].append(e[sl, 0].astype(np.int64)); node_grads[ti].append(out["g_s"])
             node_keys[tj].append(e[sl, 2].astype(np.int64)); node_grads[tj].append(out["g_d"])

@@ -19,8 +19,13 @@ any precision; sign(0) = 0.
 
 Loss: Eq. 1 as printed (the log-sum-exp runs over the sampled negatives only),
 the variant of Eq. 1 whose log-sum-exp also contains the positive score (the
-usual sampled softmax / cross-entropy; not the paper's default), or a logistic
-loss.  All are sums, not means.
+usual sampled softmax / cross-entropy; not the paper's default), a logistic
+loss, or a margin-based ranking loss (Sec. 8 says other objectives fit the same
+frame and names none; the textbook pairwise hinge is used):
+    l_e = sum_k max(0, margin - f_e + S_ek),
+every sampled negative that is not at least `margin` below the positive pays for
+the shortfall.  Its derivative is an indicator: dl/dS_ek = [margin - f_e + S_ek > 0]
+(0 on the hinge itself), dl/df_e = minus their number.  All are sums, not means.
 """
 
 from __future__ import annotations
@@ -28,7 +33,7 @@ from __future__ import annotations
 import numpy as np
 
 DOT, DISTMULT, COMPLEX, TRANSE = 0, 1, 2, 3
-SOFTMAX, LOGISTIC, SOFTMAX_POS = 0, 1, 2
+SOFTMAX, LOGISTIC, SOFTMAX_POS, MARGIN = 0, 1, 2, 3
 
 
 def _halves(x):
@@ -90,11 +95,15 @@ def positive_scores(score, s, r, d, rounded=True):
     return np.sum(compose_u(score, s, r) * d, axis=-1)
 
 
-def side_loss(loss, f, S, neg_weight):
+def side_loss(loss, f, S, neg_weight, margin=1.0):
     """Loss terms and their derivatives for one chunk and one corrupted side.
 
     f: positive scores [C]; S: negative scores [C, N].
     Returns (loss_e [C], a_e = dl/df [C], W = dl/dS [C, N])."""
+    if loss == MARGIN:
+        short = margin - f[:, None] + S                      # how far each negative is from being `margin` below
+        W = (short > 0.0).astype(np.float64)
+        return np.maximum(short, 0.0).sum(axis=1), -W.sum(axis=1), W
     if loss == SOFTMAX:
         m = S.max(axis=1, keepdims=True)
         ex = np.exp(S - m)
@@ -139,7 +148,7 @@ def chain_from_v(score, g_v, r, d):
     return cmul(r, g_v), cmul_conj(g_v, d)
 
 
-def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, rounded=True):
+def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, rounded=True, margin=1.0):
     """Loss and gradients of one chunk for one corrupted side.
 
     s, r, d: [C, dim] float64 rows of the chunk's positive edges (r ignored for Dot).
@@ -153,10 +162,10 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, rounded=True
         q = compose_v(score, r, d, rounded) if score == TRANSE else compose_v(score, r, d)       # meets source-like rows
         other = s
     if score == TRANSE:
-        return _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs)
+        return _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, margin)
     f = np.sum(q * other, axis=1)
     S = q @ negs.T
-    l, a, W = side_loss(loss, f, S, neg_weight)
+    l, a, W = side_loss(loss, f, S, neg_weight, margin)
     g_q = a[:, None] * other + W @ negs
     g_other = a[:, None] * q
     g_neg = W.T @ q
@@ -169,13 +178,13 @@ def chunk_side(score, loss, neg_weight, side_is_dst, s, r, d, negs, rounded=True
     return dict(loss=l, f=f, S=S, W=W, a=a, q=q, g_s=g_s, g_r=g_r, g_d=g_d, g_neg=g_neg)
 
 
-def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs):
+def _chunk_side_translational(loss, neg_weight, side_is_dst, q, other, negs, margin=1.0):
     """chunk_side for the translational score: pair score -|q - row|_1,
     d(pair)/dq = -sign(q - row), d(pair)/drow = +sign(q - row)."""
     f = -np.abs(q - other).sum(axis=1)
     sg = np.sign(q[:, None, :] - negs[None, :, :])            # [C, N, dim]
     S = -np.abs(q[:, None, :] - negs[None, :, :]).sum(axis=-1)
-    l, a, W = side_loss(loss, f, S, neg_weight)
+    l, a, W = side_loss(loss, f, S, neg_weight, margin)
     sg_pos = np.sign(q - other)
     g_q = -a[:, None] * sg_pos - np.einsum("ck,ckj->cj", W, sg)
     g_other = a[:, None] * sg_pos

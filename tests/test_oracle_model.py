@@ -143,6 +143,33 @@ def test_softmax_with_positive_closed_forms_and_library_cross_entropy():
     np.testing.assert_allclose(a + W.sum(1), 0.0, atol=1e-15)
 
 
+def test_margin_ranking_loss_closed_forms_and_library_margin_ranking_loss():
+    # one negative: it pays margin - f + S when it is less than the margin below the positive, else nothing
+    l, a, W = model.side_loss(model.MARGIN, np.array([0.3]), np.array([[0.1]]), 1.0, margin=1.0)
+    assert l[0] == pytest.approx(0.8) and a[0] == -1.0 and W[0, 0] == 1.0
+    l, a, W = model.side_loss(model.MARGIN, np.array([2.0]), np.array([[0.5]]), 1.0, margin=1.0)
+    assert l[0] == 0.0 and a[0] == 0.0 and W[0, 0] == 0.0
+    l, a, W = model.side_loss(model.MARGIN, np.array([1.5]), np.array([[0.5]]), 1.0, margin=1.0)      # on the hinge itself
+    assert l[0] == 0.0 and a[0] == 0.0 and W[0, 0] == 0.0
+    # several: only the violators count, dl/df is minus their number
+    l, a, W = model.side_loss(model.MARGIN, np.array([1.0, -1.0]), np.array([[0.5, -3.0, 0.9], [4.0, -2.5, -1.75]]), 1.0, margin=0.5)
+    np.testing.assert_allclose(l, [0.0 + 0.0 + 0.4, 5.5 + 0.0 + 0.0])
+    np.testing.assert_array_equal(W, [[0, 0, 1], [1, 0, 0]])
+    np.testing.assert_array_equal(a, [-1, -1])
+    # the library's pairwise ranking loss: max(0, -y (x1 - x2) + margin) with y = 1, x1 the positive, x2 a negative
+    rng = np.random.default_rng(8)
+    f, S = rng.standard_normal(7), rng.standard_normal((7, 11))
+    tf = torch.tensor(f, requires_grad=True)
+    tS = torch.tensor(S, requires_grad=True)
+    lib = torch.nn.functional.margin_ranking_loss(tf[:, None].expand(7, 11), tS, torch.ones(7, 11, dtype=torch.float64),
+                                                  margin=0.7, reduction="none")
+    l, a, W = model.side_loss(model.MARGIN, f, S, 1.0, margin=0.7)
+    np.testing.assert_allclose(l, lib.sum(1).detach().numpy(), rtol=1e-14)
+    lib.sum().backward()
+    np.testing.assert_allclose(a, tf.grad.numpy(), rtol=0, atol=0)
+    np.testing.assert_allclose(W, tS.grad.numpy(), rtol=0, atol=0)
+
+
 # ---------------------------------------------------------------- gradients
 
 def _tiny(score, loss, corrupt, i, j, seed=0, degree_negs=0):
@@ -165,12 +192,22 @@ def _loss_only(cfg, node, rel, edges, i, j):
 
 
 @pytest.mark.parametrize("score", [model.DOT, model.DISTMULT, model.COMPLEX, model.TRANSE])
-@pytest.mark.parametrize("loss", [model.SOFTMAX, model.LOGISTIC, model.SOFTMAX_POS])
+@pytest.mark.parametrize("loss", [model.SOFTMAX, model.LOGISTIC, model.SOFTMAX_POS, model.MARGIN])
 @pytest.mark.parametrize("corrupt", [0, 1, 2])
 @pytest.mark.parametrize("bucket", [(0, 0), (0, 1), (1, 0)])
 def test_gradients_match_central_finite_differences(score, loss, corrupt, bucket):
     i, j = bucket
     cfg, node32, rel32, edges = _tiny(score, loss, corrupt, i, j, degree_negs=1)
+    if loss == model.MARGIN:
+        # the hinge has kinks; the differences below are taken away from them: no sampled negative of these
+        # tables sits within 1e-3 of its hinge (checked), the step is 1e-6
+        cfg.margin = 0.8
+        shortfalls = []
+        batch_gradients(Tables(cfg, node32, rel32), i, j, edges, 0, 0,
+                        record={"observer": lambda si, dst, c, er, ids, s, r, d, negs, out:
+                                shortfalls.append(cfg.margin - out["f"][:, None] + out["S"])})
+        assert min(float(np.abs(x).min()) for x in shortfalls) > 1e-3
+        assert any((x > 0).any() for x in shortfalls)
     # the translational u, v are exact here: the differences perturb below fp32 resolution.  Its
     # kinks (a component of u equal to that of a row it meets: a negative that is the edge's own
     # endpoint and a zero relation component) do not occur in these continuous random tables.
@@ -203,6 +240,43 @@ def test_gradients_match_central_finite_differences(score, loss, corrupt, bucket
         np.testing.assert_allclose(drel, fdr, rtol=2e-6, atol=2e-8)
     else:
         assert grel is None
+
+
+@pytest.mark.parametrize("score", [model.DOT, model.COMPLEX])
+def test_margin_gradients_match_autograd_on_the_pairwise_hinge_written_edge_by_edge(score):
+    i, j = 1, 0
+    cfg, node32, rel32, edges = _tiny(score, model.MARGIN, 2, i, j, seed=6)
+    cfg.margin = 0.6
+    tab = Tables(cfg, node32, rel32)
+    loss, gnode, grel = batch_gradients(tab, i, j, edges, 0, 0)
+    neg = negatives.batch_negatives(cfg, 0, i, j, 0, edges, edges)
+    tn = torch.tensor(node32, dtype=torch.float64, requires_grad=True)
+    tr = torch.tensor(rel32, dtype=torch.float64, requires_grad=True)
+    total = torch.zeros((), dtype=torch.float64)
+    for e_idx, (sl, rl, dl) in enumerate(edges):
+        c = e_idx // cfg.chunk_size
+        s, r, d = tn[i * 4 + sl], tr[rl], tn[j * 4 + dl]
+        f = _torch_score(score, s, r, d)
+        for k in neg[0, c]:
+            total = total + torch.clamp(cfg.margin - f + _torch_score(score, s, r, tn[j * 4 + int(k)]), min=0.0)
+        for k in neg[1, c]:
+            total = total + torch.clamp(cfg.margin - f + _torch_score(score, tn[i * 4 + int(k)], r, d), min=0.0)
+    total.backward()
+    assert float(total) > 0 and abs(float(total) - loss) < 1e-10
+    kinds = []
+    batch_gradients(Tables(cfg, node32, rel32), i, j, edges, 0, 0,
+                    record={"observer": lambda si, dst, c, er, ids, s, r, d, negs, out: kinds.append(out["W"])})
+    assert any((w == 1).any() for w in kinds) and any((w == 0).any() for w in kinds)      # violators and satisfied pairs
+    dense = np.zeros((8, 6))
+    for slot, part in ((0, i), (1, j)):
+        if slot in gnode:
+            rows, g = gnode[slot]
+            dense[part * 4 + rows] += g
+    np.testing.assert_allclose(dense, tn.grad.numpy(), rtol=1e-10, atol=1e-12)
+    if score != model.DOT:
+        drel = np.zeros((3, 6))
+        drel[grel[0]] = grel[1]
+        np.testing.assert_allclose(drel, tr.grad.numpy(), rtol=1e-10, atol=1e-12)
 
 
 def _torch_score(score, s, r, d):
