@@ -50,10 +50,12 @@ typedef enum legend_status {
  * result u = theta_s + theta_r (v = theta_d - theta_r on the source side) is the
  * fp32 sum, and the derivative of |.| at 0 is taken as 0.  dim <= 128. */
 enum { LEGEND_SCORE_DOT = 0, LEGEND_SCORE_DISTMULT = 1, LEGEND_SCORE_COMPLEX = 2, LEGEND_SCORE_TRANSE_L1 = 3 };
-/* Eq. 1 as printed (log-sum-exp over the sampled negatives only), logistic, or
- * the variant of Eq. 1 whose log-sum-exp also holds the positive score (sampled
- * cross-entropy: -f + log(exp f + sum_k exp S_k)). */
-enum { LEGEND_LOSS_SOFTMAX = 0, LEGEND_LOSS_LOGISTIC = 1, LEGEND_LOSS_SOFTMAX_POS = 2 };
+/* Eq. 1 as printed (log-sum-exp over the sampled negatives only), logistic, the
+ * variant of Eq. 1 whose log-sum-exp also holds the positive score (sampled
+ * cross-entropy: -f + log(exp f + sum_k exp S_k)), or the margin-based ranking
+ * loss sum_k max(0, margin - f + S_k) (Sec. 8: other objectives fit the same
+ * frame; product scores with dim <= 128 only, LEGEND_E_INVAL otherwise). */
+enum { LEGEND_LOSS_SOFTMAX = 0, LEGEND_LOSS_LOGISTIC = 1, LEGEND_LOSS_SOFTMAX_POS = 2, LEGEND_LOSS_MARGIN = 3 };
 /* Which endpoint of a positive edge is replaced by sampled nodes. */
 enum { LEGEND_CORRUPT_DST = 0, LEGEND_CORRUPT_SRC = 1, LEGEND_CORRUPT_BOTH = 2 };
 /* Embedding update (Sec. 2.1 stage 6): gradient rows of one table row are summed
@@ -88,6 +90,8 @@ typedef struct legend_config {
                                   < 0 selects 1 / num_negs                          */
     float    init_std;         /* standard deviation of the seeded initial embeddings
                                   (used only for a table whose init pointer is NULL) */
+    float    margin;           /* LEGEND_LOSS_MARGIN: how far below its positive a
+                                  negative must score to cost nothing (>= 0)        */
     uint64_t seed;             /* seed of the negative-sampling counter hash        */
     void*    compute_stream;   /* borrowed hipStream_t, or NULL: library creates    */
     void*    copy_stream;      /* borrowed hipStream_t, or NULL: library creates    */

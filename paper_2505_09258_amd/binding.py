@@ -20,7 +20,7 @@ LEGEND_OK = 0
 LEGEND_E_INVAL, LEGEND_E_NOMEM, LEGEND_E_NOT_RESIDENT = -1, -2, -3
 LEGEND_E_RANGE, LEGEND_E_HIP, LEGEND_E_STATE = -4, -5, -6
 SCORE_DOT, SCORE_DISTMULT, SCORE_COMPLEX, SCORE_TRANSE_L1 = 0, 1, 2, 3
-LOSS_SOFTMAX, LOSS_LOGISTIC, LOSS_SOFTMAX_POS = 0, 1, 2
+LOSS_SOFTMAX, LOSS_LOGISTIC, LOSS_SOFTMAX_POS, LOSS_MARGIN = 0, 1, 2, 3
 CORRUPT_DST, CORRUPT_SRC, CORRUPT_BOTH = 0, 1, 2
 UPDATE_DETERMINISTIC, UPDATE_ATOMIC = 0, 1
 MEM_HOST, MEM_DEVICE = 0, 1
@@ -44,7 +44,7 @@ class legend_config(C.Structure):
         ("corrupt", C.c_int32), ("update_mode", C.c_int32), ("batch_size", C.c_int32),
         ("chunk_size", C.c_int32), ("num_negs", C.c_int32), ("num_degree_negs", C.c_int32),
         ("lr", C.c_float), ("eps", C.c_float), ("neg_weight", C.c_float), ("init_std", C.c_float),
-        ("seed", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
+        ("margin", C.c_float), ("seed", C.c_uint64), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
     ]
 
 
@@ -137,7 +137,7 @@ def _as(a, dtype) -> Optional[np.ndarray]:
 
 def make_config(*, num_nodes, dim, num_partitions=1, buffer_capacity=None, num_relations=0, score=SCORE_DOT,
                 loss=LOSS_SOFTMAX, corrupt=CORRUPT_DST, update_mode=UPDATE_DETERMINISTIC, batch_size, chunk_size,
-                num_negs, num_degree_negs=0, lr=0.1, eps=1e-10, neg_weight=-1.0, init_std=1e-3, seed=0, device=0,
+                num_negs, num_degree_negs=0, lr=0.1, eps=1e-10, neg_weight=-1.0, init_std=1e-3, margin=1.0, seed=0, device=0,
                 compute_stream=None, copy_stream=None) -> legend_config:
     cfg = legend_config()
     cfg.struct_size = C.sizeof(legend_config)
@@ -149,7 +149,7 @@ def make_config(*, num_nodes, dim, num_partitions=1, buffer_capacity=None, num_r
     cfg.buffer_capacity = num_partitions if buffer_capacity is None else buffer_capacity
     cfg.score, cfg.loss, cfg.corrupt, cfg.update_mode = score, loss, corrupt, update_mode
     cfg.batch_size, cfg.chunk_size, cfg.num_negs, cfg.num_degree_negs = batch_size, chunk_size, num_negs, num_degree_negs
-    cfg.lr, cfg.eps, cfg.neg_weight, cfg.init_std = lr, eps, neg_weight, init_std
+    cfg.lr, cfg.eps, cfg.neg_weight, cfg.init_std, cfg.margin = lr, eps, neg_weight, init_std, margin
     cfg.seed = seed & ((1 << 64) - 1)
     cfg.compute_stream = compute_stream
     cfg.copy_stream = copy_stream

@@ -226,7 +226,10 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     const int ntiles = (N + kNegTile - 1) / kNegTile;
     const int srow = tid >> 2;                // 4 threads per row for the row-wise reductions
     const int sq = tid & 3;
-    float neg_loss = 0.f;                     // logistic: this lane's share of the weighted softplus terms
+    float neg_loss = 0.f;                     // logistic / margin: this lane's share of the negatives' loss terms
+    float cnt_l[LOSS == LEGEND_LOSS_MARGIN ? 16 : 1];         // margin: violating negatives per row among this lane's columns
+#pragma unroll
+    for (int v = 0; v < (LOSS == LEGEND_LOSS_MARGIN ? 16 : 1); ++v) cnt_l[v] = 0.f;
 
     if (LOSS == LEGEND_LOSS_SOFTMAX) {
         // ---- sweep 1: running max and sum of exp, per lane over its own columns -------------
@@ -354,6 +357,13 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                 if (col_ok && r < nrows) {
                     if (LOSS == LEGEND_LOSS_SOFTMAX) {
                         wv = fast_exp(acc[v] - lse_s[r]);
+                    } else if (LOSS == LEGEND_LOSS_MARGIN) {
+                        // pairwise hinge max(0, margin - f + S): dL/dS is 1 for a negative less than the margin
+                        // below the positive (0 on the hinge itself)
+                        const float sh = (bp.margin - pos_s[r]) + acc[v];
+                        wv = sh > 0.f ? 1.f : 0.f;
+                        neg_loss += fmaxf(sh, 0.f);
+                        cnt_l[LOSS == LEGEND_LOSS_MARGIN ? v : 0] += wv;
                     } else {
                         wv = wneg * sigmoidf(acc[v]);
                         neg_loss += wneg * softplusf(acc[v]);
@@ -487,7 +497,23 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
             }
         }
     }
-    if (LOSS == LEGEND_LOSS_LOGISTIC) {
+    if (LOSS == LEGEND_LOSS_MARGIN) {
+        // dL/df of a row is minus the number of its violating negatives: combine the 64 per-lane counts of
+        // every row (two waves x 32 lanes); small integers, exact in any order
+        __syncthreads();                      // the last tile's W has been consumed
+        const int pcol = cbA * 32 + i32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Ws[acc_row(rbA, v) * kWS + pcol] = cnt_l[LOSS == LEGEND_LOSS_MARGIN ? v : 0];
+        __syncthreads();
+        const float* wr = Ws + srow * kWS + sq * 16;
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) sum += wr[j];
+        sum += wave_shfl_xor(sum, 1);
+        sum += wave_shfl_xor(sum, 2);
+        if (sq == 0) rowloss_s[srow] = sum;
+    }
+    if (LOSS == LEGEND_LOSS_LOGISTIC || LOSS == LEGEND_LOSS_MARGIN) {
         // workgroup total of the negative terms: lanes -> wave -> LDS
         for (int off = kWave / 2; off > 0; off >>= 1) neg_loss += __shfl_down(neg_loss, off, kWave);
         if (lane == 0) lse_s[w] = neg_loss;
@@ -508,6 +534,7 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                     a = -1.f;
                 }
             }
+            else if (LOSS == LEGEND_LOSS_MARGIN) { a = -rowloss_s[prow]; row_loss = 0.f; }   // read by the row's four lanes before the slot is reused
             else { a = -sigmoidf(-f); row_loss = softplusf(-f); }
             const float* x = Ex + (int64_t)eb[prow * 3 + xcol] * d;
             const float* y = Ey + (int64_t)eb[prow * 3 + ycol] * d;
@@ -557,7 +584,7 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
     if (tid == 0) {
         double s = 0.0;
         for (int r = 0; r < kRowTile; ++r) s += (double)rowloss_s[r];
-        if (LOSS == LEGEND_LOSS_LOGISTIC)
+        if (LOSS == LEGEND_LOSS_LOGISTIC || LOSS == LEGEND_LOSS_MARGIN)
             for (int ww = 0; ww < kChunkThreads / kWave; ++ww) s += (double)lse_s[ww];
         loss_partial[blockIdx.x] = s;
     }
@@ -593,6 +620,9 @@ static hipError_t launch_chunks_nb(hipStream_t st, const BatchGeom& g, const Buc
     LEGEND_CHUNK_CASE(LEGEND_SCORE_DISTMULT, LEGEND_LOSS_LOGISTIC)
     LEGEND_CHUNK_CASE(LEGEND_SCORE_COMPLEX, LEGEND_LOSS_SOFTMAX)
     LEGEND_CHUNK_CASE(LEGEND_SCORE_COMPLEX, LEGEND_LOSS_LOGISTIC)
+    LEGEND_CHUNK_CASE(LEGEND_SCORE_DOT, LEGEND_LOSS_MARGIN)
+    LEGEND_CHUNK_CASE(LEGEND_SCORE_DISTMULT, LEGEND_LOSS_MARGIN)
+    LEGEND_CHUNK_CASE(LEGEND_SCORE_COMPLEX, LEGEND_LOSS_MARGIN)
 #undef LEGEND_CHUNK_CASE
     return hipErrorInvalidValue;
 }

@@ -62,13 +62,14 @@ struct BucketParams {
     int32_t rows_valid_dst;
     int32_t num_relations;
     int32_t dim;
-    int32_t score, loss;       // loss: LEGEND_LOSS_SOFTMAX or LEGEND_LOSS_LOGISTIC (kernel template parameter)
+    int32_t score, loss;       // loss: LEGEND_LOSS_SOFTMAX, _LOGISTIC or _MARGIN (kernel template parameter)
     int32_t softmax_with_pos;  // Eq. 1 variant: the positive score is a term of the log-sum-exp
     int32_t same_part;         // i == j
     uint32_t key_base_dst;     // key offset of table slot 1 (0 when same_part)
     uint32_t key_base_rel;     // key offset of the relation table
     int32_t num_degree_negs;
     float lr, eps, neg_weight;
+    float margin;              // margin loss: a negative should score this much below its positive
     uint64_t hash_prefix;      // hash state after (seed, epoch, i, j, b)
 };
 

@@ -424,7 +424,9 @@ int bucket_params(legend_ctx* c, int i, int j, const int32_t* dev_edges, int64_t
     p.num_relations = c->cfg.num_relations;
     p.dim = c->d;
     p.score = c->cfg.score;
-    p.loss = c->cfg.loss == LEGEND_LOSS_LOGISTIC ? LEGEND_LOSS_LOGISTIC : LEGEND_LOSS_SOFTMAX;
+    p.loss = c->cfg.loss == LEGEND_LOSS_LOGISTIC ? LEGEND_LOSS_LOGISTIC
+             : (c->cfg.loss == LEGEND_LOSS_MARGIN ? LEGEND_LOSS_MARGIN : LEGEND_LOSS_SOFTMAX);
+    p.margin = c->cfg.margin;
     p.softmax_with_pos = c->cfg.loss == LEGEND_LOSS_SOFTMAX_POS ? 1 : 0;
     p.same_part = i == j;
     p.key_base_dst = i == j ? 0u : (uint32_t)c->Rp;
@@ -481,8 +483,10 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "num_nodes, dim, num_partitions must be positive and num_partitions <= num_nodes");
     if (!dim_supported(cfg->dim))
         return fail(LEGEND_E_INVAL, "dim %d is not supported (1..%d)", cfg->dim, max_dim_supported());
-    if (cfg->score < 0 || cfg->score > 3 || cfg->loss < 0 || cfg->loss > 2 || cfg->corrupt < 0 || cfg->corrupt > 2)
+    if (cfg->score < 0 || cfg->score > 3 || cfg->loss < 0 || cfg->loss > 3 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
+    if (cfg->loss == LEGEND_LOSS_MARGIN && (cfg->score == LEGEND_SCORE_TRANSE_L1 || cfg->dim > 128 || !(cfg->margin >= 0.f)))
+        return fail(LEGEND_E_INVAL, "the margin loss is implemented for the product scores with dim <= 128 and needs margin >= 0");
     if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)
         return fail(LEGEND_E_INVAL, "unknown update_mode %d", cfg->update_mode);
     if (cfg->score == LEGEND_SCORE_COMPLEX && (cfg->dim & 1)) return fail(LEGEND_E_INVAL, "ComplEx needs an even dim");

@@ -18,6 +18,13 @@ from __future__ import annotations
 import numpy as np
 
 DOT, DISTMULT, COMPLEX, TRANSE = 0, 1, 2, 3
+MARGIN_LOSS = 3
+# The margin loss decides per (positive, negative) pair whether the pair pays: margin - f + S > 0, a discrete decision
+# on fp32 scores whose summation order the oracle cannot reproduce.  A pair whose float64 shortfall lies within
+# BAND roundoffs times its magnitude A_ek + A_f + margin of zero may be decided either way: its whole gradient term
+# (not a rounding-sized share of it) goes into a second, unscaled magnitude.  Everything else about this loss is
+# exact (the weights are 0 or 1), so its ordinary magnitudes carry no widening.
+BAND = 16 * 2.0 ** -24
 
 
 def _halves(x):
@@ -38,13 +45,33 @@ def abs_compose(score, a, b):
     return np.concatenate([ar * br + ai * bi, ar * bi + ai * br], axis=-1)
 
 
-def chunk_magnitudes(score, side_is_dst, s, r, d, negs, out):
+def chunk_magnitudes(score, side_is_dst, s, r, d, negs, out, loss=None, margin=1.0):
     """Magnitudes for one chunk and one corrupted side.
 
     s, r, d, negs: the float64 rows the oracle's chunk_side was given; out: its result (W, a, S, f, q).
-    Returns dict(m_s, m_r (or None), m_d [C,dim], m_neg [N,dim], m_loss [C])."""
+    Returns dict(m_s, m_r (or None), m_d [C,dim], m_neg [N,dim], m_loss [C]); for the margin loss also
+    b_s, b_r, b_d, b_neg: the magnitudes of the terms whose hinge decision may fall either way."""
     W, a, q = out["W"], out["a"], out["q"]
     other = d if side_is_dst else s
+    if loss == MARGIN_LOSS and score != TRANSE:
+        x = s if side_is_dst else d
+        aq = abs_compose(score, x, r)
+        A_neg = aq @ np.abs(negs).T
+        A_f = np.sum(aq * np.abs(other), axis=1)
+        short = margin - out["f"][:, None] + out["S"]
+        flip = (np.abs(short) <= BAND * (A_neg + A_f[:, None] + margin)).astype(np.float64)
+        am = np.abs(a)
+        m_q = am[:, None] * np.abs(other) + W @ np.abs(negs)
+        m_other = am[:, None] * aq
+        b_q = flip.sum(axis=1)[:, None] * np.abs(other) + flip @ np.abs(negs)
+        b_other = flip.sum(axis=1)[:, None] * aq
+        def chain(v):
+            return (v if score == DOT else abs_compose(score, r, v)), (None if score == DOT else abs_compose(score, x, v))
+        m_x, m_r = chain(m_q)
+        b_x, b_r = chain(b_q)
+        return dict(m_neg=W.T @ aq, m_r=m_r, m_loss=(W * (A_neg + A_f[:, None])).sum(axis=1) + flip.sum(axis=1) * margin,
+                    m_s=m_x if side_is_dst else m_other, m_d=m_other if side_is_dst else m_x,
+                    b_neg=flip.T @ aq, b_r=b_r, b_s=b_x if side_is_dst else b_other, b_d=b_other if side_is_dst else b_x)
     if score == TRANSE:
         sg = np.abs(np.sign(q[:, None, :] - negs[None, :, :]))        # which terms exist: sign(0) = 0 contributes nothing
         sg_pos = np.abs(np.sign(q - other))
@@ -72,34 +99,45 @@ class BatchMagnitudes:
     """Observer for oracle.bucket.batch_gradients: collects the magnitudes of a batch's chunks and
     coalesces them by table row the way the gradients themselves are coalesced."""
 
-    def __init__(self, score, same_part):
-        self.score = score
+    def __init__(self, score, same_part, loss=None, margin=1.0):
+        self.score, self.loss, self.margin = score, loss, margin
         self.tj = 0 if same_part else 1
         self.keys = {0: [], 1: [], 2: []}
         self.mags = {0: [], 1: [], 2: []}
+        self.bands = {0: [], 1: [], 2: []}
         self.loss_magnitude = 0.0
 
     def __call__(self, si, side_is_dst, c, edge_rows, neg_ids, s, r, d, negs, out):
-        m = chunk_magnitudes(self.score, side_is_dst, s, r, d, negs, out)
+        m = chunk_magnitudes(self.score, side_is_dst, s, r, d, negs, out, self.loss, self.margin)
         self.loss_magnitude += float(m["m_loss"].sum())
         neg_slot = self.tj if side_is_dst else 0
-        for slot, keys, mag in ((0, edge_rows[:, 0], m["m_s"]), (self.tj, edge_rows[:, 2], m["m_d"]), (neg_slot, neg_ids, m["m_neg"])):
+        banded = "b_s" in m
+        for slot, keys, mag, band in ((0, edge_rows[:, 0], m["m_s"], m.get("b_s")), (self.tj, edge_rows[:, 2], m["m_d"], m.get("b_d")),
+                                      (neg_slot, neg_ids, m["m_neg"], m.get("b_neg"))):
             self.keys[slot].append(np.asarray(keys, np.int64))
             self.mags[slot].append(mag)
+            if banded:
+                self.bands[slot].append(band)
         if m["m_r"] is not None and self.score != DOT:
             self.keys[2].append(np.asarray(edge_rows[:, 1], np.int64))
             self.mags[2].append(m["m_r"])
+            if banded:
+                self.bands[2].append(m["b_r"])
 
     def coalesced(self):
-        """{slot: (unique rows, summed magnitudes)} for slots 0 (partition i), 1 (partition j != i), 2 (relations)."""
+        """{slot: (unique rows, summed magnitudes, summed either-way magnitudes or None)} for slots 0 (partition i),
+        1 (partition j != i), 2 (relations)."""
         res = {}
         for slot in (0, 1, 2):
             if not self.keys[slot]:
                 continue
             k = np.concatenate(self.keys[slot])
-            g = np.concatenate(self.mags[slot], axis=0)
             uniq, inv = np.unique(k, return_inverse=True)
-            acc = np.zeros((uniq.size, g.shape[1]))
-            np.add.at(acc, inv, g)
-            res[slot] = (uniq, acc)
+
+            def summed(parts):
+                g = np.concatenate(parts, axis=0)
+                acc = np.zeros((uniq.size, g.shape[1]))
+                np.add.at(acc, inv, g)
+                return acc
+            res[slot] = (uniq, summed(self.mags[slot]), summed(self.bands[slot]) if self.bands[slot] else None)
         return res

@@ -84,12 +84,16 @@ class OracleRun:
         self.last = {}
         self.loss = 0.0
 
-    def _allowances(self, state, rows, g, mag):
+    def _allowances(self, state, rows, g, mag, band=None):
+        """band: magnitude of gradient terms that may be present or absent as a whole (discrete decisions that
+        fall either way within rounding, tests/error_model.py); it enters unscaled."""
         lr, eps = self.cfg.lr, self.cfg.eps
         s_new = state[rows].astype(np.float64)               # after the update
         ke, ks = kappa_for(self.cfg.dim, "emb"), kappa_for(self.cfg.dim, "state")
-        fe = lr * ke * mag / (np.sqrt(s_new) + eps)
-        fs = 2.0 * np.abs(g) * ks * mag + (ks * mag) ** 2            # |(G + e)^2 - G^2| <= 2 |G| e + e^2
+        ee = ke * mag + (band if band is not None else 0.0)
+        es = ks * mag + (band if band is not None else 0.0)
+        fe = lr * ee / (np.sqrt(s_new) + eps)
+        fs = 2.0 * np.abs(g) * es + es ** 2                          # |(G + e)^2 - G^2| <= 2 |G| e + e^2
         return fe, fs
 
     def set_state(self, node_E, node_S, rel_E=None, rel_S=None):
@@ -119,7 +123,7 @@ class OracleRun:
         loss = 0.0
         self.last_loss_allowance = 0.0       # of this call's loss sum, absolute
         for b in range(batch_begin, nb):
-            watch = BatchMagnitudes(cfg.score, i == j)
+            watch = BatchMagnitudes(cfg.score, i == j, cfg.loss, cfg.margin)
             rec = {"observer": watch}
             loss += train_batch(self.tab, i, j, edges, b, epoch, record=rec)
             self.last_loss_allowance += kappa_for(cfg.dim, "loss") * watch.loss_magnitude
@@ -129,9 +133,9 @@ class OracleRun:
             for slot, part in ((0, i), (1, j)):
                 if slot in node:
                     rows, g = node[slot]
-                    mrows, mag = mags[slot]
+                    mrows, mag, band = mags[slot]
                     assert np.array_equal(rows, mrows)
-                    fe, fs = self._allowances(self.tab.S[part], rows, g, mag)
+                    fe, fs = self._allowances(self.tab.S[part], rows, g, mag, band)
                     if self.sparse:
                         self.last[part] = (rows, fe, fs)
                     else:
@@ -140,9 +144,9 @@ class OracleRun:
                         self.touched_node[part][rows] = True
             if rel is not None:
                 rows, g = rel
-                mrows, mag = mags[2]
+                mrows, mag, band = mags[2]
                 assert np.array_equal(rows, mrows)
-                fe, fs = self._allowances(self.tab.RS, rows, g, mag)
+                fe, fs = self._allowances(self.tab.RS, rows, g, mag, band)
                 self.fe_rel[rows] += fe
                 self.fs_rel[rows] += fs
                 self.touched_rel[rows] = True

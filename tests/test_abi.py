@@ -37,7 +37,7 @@ def test_config_struct_layout_matches_header_field_order():
     body = text[text.index("typedef struct legend_config {"):text.index("} legend_config;")]
     fields = re.findall(r"^\s+(?:uint32_t|int32_t|int64_t|uint64_t|float|void\*)\s+(\w+);", body, flags=re.M)
     assert fields == [f[0] for f in binding.legend_config._fields_]
-    assert ctypes.sizeof(binding.legend_config) == 104
+    assert ctypes.sizeof(binding.legend_config) == 112
 
 
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 8, 12, 16, 23])

@@ -10,7 +10,7 @@ from tests.parity_util import EMB_RTOL, STATE_RTOL, OracleRun, check_loss, check
 pytestmark = pytest.mark.gpu
 
 DOT, DISTMULT, COMPLEX, TRANSE = 0, 1, 2, 3
-SOFTMAX, LOGISTIC, SOFTMAX_POS = 0, 1, 2
+SOFTMAX, LOGISTIC, SOFTMAX_POS, MARGIN = 0, 1, 2, 3
 DST, SRC, BOTH = 0, 1, 2
 
 
@@ -55,6 +55,10 @@ CASES = [
     _case("dot_d32_above_small_sort", DOT, SOFTMAX, DST, 2_500, 0, 32, 1, 0, 0, 1_025, 32, 64, 20, 2_300, 0.2),
     # one negative more than the single-sweep kernel holds (1024): d = 100 through the two-sweep kernel
     _case("dot_d100_n1025", DOT, SOFTMAX, DST, 6_000, 0, 100, 2, 0, 1, 300, 50, 1_025, 300, 700, 0.2),
+    # margin-based ranking loss (pairwise hinge): about half of the pairs pay at these scales
+    dict(_case("dot_d100_margin", DOT, MARGIN, DST, 8_000, 0, 100, 2, 0, 1, 600, 50, 300, 60, 1_300, 0.3), margin=1.0),
+    dict(_case("distmult_d64_margin_both", DISTMULT, MARGIN, BOTH, 5_000, 9, 64, 2, 1, 1, 500, 64, 130, 0, 1_100, 0.5), margin=0.5),
+    dict(_case("complex_d20_margin_src", COMPLEX, MARGIN, SRC, 3_000, 5, 20, 1, 0, 0, 300, 33, 65, 10, 700, 0.6), margin=2.0),
 ]
 
 # One node row in 64 is four times larger than the rest, so that some chunks hold a score far
@@ -86,7 +90,7 @@ def _ocfg(c):
     return OracleConfig(num_nodes=c["V"], num_relations=c["nrel"], dim=c["d"], num_partitions=c["n"],
                         batch_size=c["B"], chunk_size=c["C"], num_negs=c["N"], num_degree_negs=c["ndeg"],
                         score=c["score"], loss=c["loss"], corrupt=c["corrupt"], lr=0.1, eps=1e-10,
-                        neg_weight=-1.0, seed=c["seed"])
+                        neg_weight=-1.0, seed=c["seed"], margin=c.get("margin", 1.0))
 
 
 def _gpu_ctx(c, node, rel, capacity=None, update_mode=0):
@@ -95,7 +99,7 @@ def _gpu_ctx(c, node, rel, capacity=None, update_mode=0):
                         update_mode=update_mode,
                         num_relations=c["nrel"], score=c["score"], loss=c["loss"], corrupt=c["corrupt"],
                         batch_size=c["B"], chunk_size=c["C"], num_negs=c["N"], num_degree_negs=c["ndeg"],
-                        lr=0.1, eps=1e-10, seed=c["seed"])
+                        lr=0.1, eps=1e-10, seed=c["seed"], margin=c.get("margin", 1.0))
     ctx = L.legend_init_partitions(cfg, node, rel if c["score"] else None)
     return L, ctx
 
@@ -282,7 +286,7 @@ def test_single_sweep_kernel_scores_beyond_the_reference_at_the_real_limit(c):
     assert 0 < seen[0][0] < seen[0][1] and all(k < n for k, n in seen) and sum(k for k, _ in seen[1:]) > 0, seen
 
 
-_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11] + [c for c in CASES if c["name"] == "transe_d100_both"]
+_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11] + [c for c in CASES if c["name"] in ("transe_d100_both", "distmult_d64_margin_both")]
 
 
 @pytest.mark.parametrize("c", _ATOMIC_CASES, ids=[c["name"] for c in _ATOMIC_CASES])
