@@ -306,10 +306,11 @@ int legend_batch_shape_of(legend_ctx* ctx, legend_batch_shape* out);
 /* Unique rows updated by the batches since the last call (sum), then cleared. */
 int legend_unique_rows_read(legend_ctx* ctx, int64_t* unique_rows, int64_t* batches);
 
-/* Workgroups (one row tile of one chunk) of the single-sweep batch kernel that
- * needed a second pass (scores too far above the softmax reference: repeated in
- * place with the exact row maxima, or handed over to the two-sweep kernel) since
- * the last call, then cleared.  A tuning aid: 0 early in training. */
+/* Workgroups (one row tile of one chunk) of the single-sweep batch kernel that met
+ * a score too far above their softmax reference (the reference is then raised in
+ * place and what was accumulated rescaled, or the chunk handed over to the
+ * two-sweep kernel) since the last call, then cleared.  A tuning aid: 0 early in
+ * training. */
 int legend_fallback_chunks_read(legend_ctx* ctx, int64_t* chunks);
 
 /*
