@@ -852,14 +852,18 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             ProfScope ps(c, KC_CHUNK_REDO);
             HIP_TRY(c, launch_chunks(c->compute, g, bp, ws, true));
         }
-        // the sum of the workgroups' loss terms is off the critical path when the second stream is in use
-        // (a batch of a few thousand gradient rows is bound by launch latency: it stays on one stream,
-        // where a kernel follows the other without a hop between streams)
-        const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536 && c->aux2 != nullptr;
+        // The table rows with many gradient rows are disjoint from the others: their two-level sums (and
+        // the sum of the workgroups' loss terms) run next to the main update kernel, on a third stream
+        // where the process has a hardware queue to spare for it, else on the index stream behind the
+        // next batch's index side (which ends well inside the update).  A batch of a few thousand gradient rows is bound by launch latency: it
+        // stays on one stream, where a kernel follows the other without a hop between streams.
+        const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536;
+        hipStream_t ls = !aside ? c->compute : c->aux2 ? c->aux2 : c->aux;
         if (!aside) {
             ProfScope ps(c, KC_MISC);
             HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, ws));
         }
+        if (aside) HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
         if (ahead && b + 1 < batch_end) {
             // next batch's index side: its workspace is free once the update of batch b-1 is done
             const int nxt = cur ^ 1;
@@ -868,7 +872,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             batch_params(b + 1, &gn);
             if (b > batch_begin) HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_updated[nxt], 0));
             if (c->index_after_chunk) {
-                HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
+                if (!aside) HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
                 HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_chunk_done, 0));
             }
             rc = enqueue_index_side(c, c->aux, gn, bp, nxt ? c->ws_odd : c->ws, &sorted_of[nxt]);
@@ -880,20 +884,16 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
             ProfScope ps(c, KC_UPDATE);
             HIP_TRY(c, launch_update_atomic(c->compute, g, bp, ws));
         } else {
-            // the table rows with many gradient rows are disjoint from the others: their two-level
-            // sums run on a stream of their own next to the main update kernel
-            hipStream_t ls = aside ? c->aux2 : c->compute;
             if (aside) {
-                HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
-                HIP_TRY(c, hipStreamWaitEvent(c->aux2, c->ev_chunk_done, 0));
-                ProfScope ps(c, KC_MISC, c->aux2);
-                HIP_TRY(c, launch_loss_reduce(c->aux2, (int64_t)g.sides * g.nchunks * g.T, ws));
+                HIP_TRY(c, hipStreamWaitEvent(ls, c->ev_chunk_done, 0));
+                ProfScope ps(c, KC_MISC, ls);
+                HIP_TRY(c, launch_loss_reduce(ls, (int64_t)g.sides * g.nchunks * g.T, ws));
             }
             {
                 ProfScope ps(c, KC_UPDATE_LONG, ls);
                 HIP_TRY(c, launch_update(ls, g, bp, ws, ws.vals[sorted_of[cur]], true));
             }
-            if (aside) HIP_TRY(c, hipEventRecord(c->ev_long_done, c->aux2));
+            if (aside) HIP_TRY(c, hipEventRecord(c->ev_long_done, ls));
             {
                 ProfScope ps(c, KC_UPDATE);
                 HIP_TRY(c, launch_update(c->compute, g, bp, ws, ws.vals[sorted_of[cur]], false));
