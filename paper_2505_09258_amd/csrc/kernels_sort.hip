@@ -271,15 +271,18 @@ static hipError_t launch_segments(hipStream_t st, int64_t n, const uint32_t* sor
 // latency-bound tiny batch pays one launch instead of some twenty.  (Making the keys in this kernel
 // as well was tried: one workgroup walking a few thousand occurrences, each with its 64-bit index
 // arithmetic and hashes, took longer than the launch it saved: 89 against 54 us per c1 batch.)
-// Same stable ranking as the multi-block scatter: wave w owns a contiguous quarter of the keys.
+// Same stable ranking as the multi-block scatter: wave w of the sixteen owns a contiguous share of the keys.
 // ------------------------------------------------------------------------------------------
 
-__global__ void __launch_bounds__(kSortThreads)
+constexpr int kSmallThreads = 1024;
+static_assert(kSmallThreads >= kRadix && kSmallSortMax % kSmallThreads == 0, "small sort geometry");
+
+__global__ void __launch_bounds__(kSmallThreads)
 k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, uint32_t* __restrict__ vals_out,
                       uint32_t* __restrict__ uniq_keys, uint32_t* __restrict__ seg_start,
                       uint32_t* __restrict__ counters, unsigned long long* __restrict__ uniq_total,
                       uint32_t* __restrict__ long_list, uint32_t* __restrict__ unit_start, int plan_long) {
-    constexpr int kWaves = kSortThreads / kWave;
+    constexpr int kWaves = kSmallThreads / kWave;
     extern __shared__ uint32_t sm[];
     auto kb = [&](int b) { return sm + b * kSmallSortMax; };                     // key buffers 0 / 1
     auto vb = [&](int b) { return sm + (2 + b) * kSmallSortMax; };               // value buffers 0 / 1
@@ -287,14 +290,14 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
     uint32_t* pos0 = cnt + kWaves * kRadix;            // [kWaves][256]
     uint32_t* wsum = pos0 + kWaves * kRadix;           // [kWaves] + carry
     const int tid = threadIdx.x, w = tid / kWave, lane = lane_id();
-    for (int i = tid; i < n; i += kSortThreads) { kb(0)[i] = keys_in[i]; vb(0)[i] = (uint32_t)i; }
+    for (int i = tid; i < n; i += kSmallThreads) { kb(0)[i] = keys_in[i]; vb(0)[i] = (uint32_t)i; }
     __syncthreads();
     const int per_wave = (n + kWaves - 1) / kWaves;
     const int lo = min(n, w * per_wave), hi = min(n, lo + per_wave);
     int cur = 0;
     for (int p = 0; p < passes; ++p) {
         const int shift = 8 * p;
-        for (int i = tid; i < kWaves * kRadix; i += kSortThreads) cnt[i] = 0;
+        for (int i = tid; i < kWaves * kRadix; i += kSmallThreads) cnt[i] = 0;
         __syncthreads();
         volatile uint32_t* mycnt = cnt + w * kRadix;
         // pass 1 over the wave's keys: rank among equal digits inside the wave (kept in pos0's place later)
@@ -317,33 +320,38 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
             if (valid) vb(cur ^ 1)[i] = prefix + (uint32_t)__popcll(lower);   // rank, parked in the spare buffer
         }
         __syncthreads();
-        // exclusive scan over digits of the per-digit totals, then per-wave starting positions
+        // exclusive scan over digits of the per-digit totals (the first kRadix threads, one digit each), then
+        // per-wave starting positions
         {
             const int d = tid;
             uint32_t tot = 0;
+            if (d < kRadix) {
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) tot += cnt[ww * kRadix + d];
+                for (int ww = 0; ww < kWaves; ++ww) tot += cnt[ww * kRadix + d];
+            }
             uint32_t incl = tot;
             for (int off = 1; off < kWave; off <<= 1) {
                 const uint32_t t = __shfl_up(incl, off, kWave);
                 if (lane >= off) incl += t;
             }
-            if (lane == kWave - 1) wsum[w] = incl;
+            if (d < kRadix && lane == kWave - 1) wsum[w] = incl;
             __syncthreads();
-            uint32_t run = incl - tot;
-            for (int ww = 0; ww < w; ++ww) run += wsum[ww];
+            if (d < kRadix) {
+                uint32_t run = incl - tot;
+                for (int ww = 0; ww < w; ++ww) run += wsum[ww];
 #pragma unroll
-            for (int ww = 0; ww < kWaves; ++ww) {
-                pos0[ww * kRadix + d] = run;
-                run += cnt[ww * kRadix + d];
+                for (int ww = 0; ww < kWaves; ++ww) {
+                    pos0[ww * kRadix + d] = run;
+                    run += cnt[ww * kRadix + d];
+                }
             }
         }
         __syncthreads();
         // scatter: ranks were parked in vbuf[cur^1]; move pairs through registers to avoid overwriting them
-        uint32_t mk[kSmallSortMax / kSortThreads], mv[kSmallSortMax / kSortThreads], mp[kSmallSortMax / kSortThreads];
+        uint32_t mk[kSmallSortMax / kSmallThreads], mv[kSmallSortMax / kSmallThreads], mp[kSmallSortMax / kSmallThreads];
 #pragma unroll
-        for (int r = 0; r < kSmallSortMax / kSortThreads; ++r) {
-            const int i = tid + r * kSortThreads;
+        for (int r = 0; r < kSmallSortMax / kSmallThreads; ++r) {
+            const int i = tid + r * kSmallThreads;
             if (i < n) {
                 const int ww = min(kWaves - 1, i / per_wave);
                 mk[r] = kb(cur)[i];
@@ -353,18 +361,18 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
         }
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < kSmallSortMax / kSortThreads; ++r) {
-            const int i = tid + r * kSortThreads;
+        for (int r = 0; r < kSmallSortMax / kSmallThreads; ++r) {
+            const int i = tid + r * kSmallThreads;
             if (i < n) { kb(cur ^ 1)[mp[r]] = mk[r]; vb(cur ^ 1)[mp[r]] = mv[r]; }
         }
         __syncthreads();
         cur ^= 1;
     }
     // sorted values out; segment heads by a block scan of the head flags
-    for (int i = tid; i < n; i += kSortThreads) vals_out[i] = vb(cur)[i];
+    for (int i = tid; i < n; i += kSmallThreads) vals_out[i] = vb(cur)[i];
     if (tid == 0) wsum[kWaves] = 0;
     __syncthreads();
-    for (int base = 0; base < n; base += kSortThreads) {
+    for (int base = 0; base < n; base += kSmallThreads) {
         const int i = base + tid;
         const uint32_t key = i < n ? kb(cur)[i] : 0u;
         const uint32_t flag = (i < n && (i == 0 || key != kb(cur)[i - 1])) ? 1u : 0u;
@@ -379,7 +387,7 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
         for (int ww = 0; ww < w; ++ww) run += wsum[ww];
         if (flag) { uniq_keys[run] = key; seg_start[run] = (uint32_t)i; }
         __syncthreads();
-        if (tid == kSortThreads - 1) wsum[kWaves] = run + flag;
+        if (tid == kSmallThreads - 1) wsum[kWaves] = run + flag;
         __syncthreads();
     }
     const uint32_t total = wsum[kWaves];
@@ -396,12 +404,12 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
     if (plan_long) {
         // table rows with many gradient rows, in no particular order, then the exclusive prefix of
         // their unit counts
-        for (uint32_t u = tid; u < total; u += kSortThreads)
+        for (uint32_t u = tid; u < total; u += kSmallThreads)
             if (seg_start[u + 1] - seg_start[u] > (uint32_t)kLongLen) long_list[atomicAdd(&wsum[kWaves + 1], 1u)] = u;
         __threadfence_block();
         __syncthreads();
         n_long = wsum[kWaves + 1];
-        for (uint32_t base = 0; base < n_long; base += kSortThreads) {
+        for (uint32_t base = 0; base < n_long; base += kSmallThreads) {
             const uint32_t r = base + tid;
             uint32_t v = 0;
             if (r < n_long) {
@@ -420,7 +428,7 @@ k_small_sort_segments(const uint32_t* __restrict__ keys_in, int n, int passes, u
             const uint32_t carry = wsum[kWaves + 2];
             if (r < n_long) unit_start[r] = carry + woff + incl - v;
             __syncthreads();
-            if (tid == kSortThreads - 1) wsum[kWaves + 2] = carry + woff + incl;
+            if (tid == kSmallThreads - 1) wsum[kWaves + 2] = carry + woff + incl;
             __syncthreads();
         }
         units = wsum[kWaves + 2];
@@ -440,7 +448,7 @@ hipError_t launch_sort_and_segments(hipStream_t st, const BatchGeom& g, const Bu
     int passes = (key_bits + 7) / 8;
     if (passes < 1) passes = 1;
     if (n <= kSmallSortMax) {
-        const size_t lds = (4 * (size_t)kSmallSortMax + 2 * 4 * kRadix + 8) * sizeof(uint32_t);
+        const size_t lds = (4 * (size_t)kSmallSortMax + 2 * (kSmallThreads / kWave) * kRadix + (kSmallThreads / kWave) + 8) * sizeof(uint32_t);
         static PerDeviceFlag attr_set;
         if (attr_set.pending()) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_small_sort_segments),
@@ -448,7 +456,7 @@ hipError_t launch_sort_and_segments(hipStream_t st, const BatchGeom& g, const Bu
             if (e != hipSuccess) return e;
             attr_set.set();
         }
-        hipLaunchKernelGGL(k_small_sort_segments, dim3(1), dim3(kSortThreads), lds, st, ws.keys[0], (int)n, passes,
+        hipLaunchKernelGGL(k_small_sort_segments, dim3(1), dim3(kSmallThreads), lds, st, ws.keys[0], (int)n, passes,
                            ws.vals[1], ws.uniq_keys, ws.seg_start, ws.counters, ws.uniq_total, ws.long_list,
                            ws.unit_start, plan_long ? 1 : 0);
         *out_buf = 1;

@@ -113,20 +113,17 @@ k_long_list(uint32_t* __restrict__ counters, const uint32_t* __restrict__ seg_st
         if (seg_start[u + 1] - seg_start[u] > (uint32_t)kLongLen) long_list[atomicAdd(&counters[2], 1u)] = u;
 }
 
-// LPR lanes (a float4 each) own one table row.  Rows with many gradient rows are left to the
-// kernels below.
+// LPR lanes (a float4 each) own one table row: the rows u0, u0 + stride, ... of the batch's unique rows.
+// Rows with many gradient rows are left to the kernels below.
 template <int LPR>
-__global__ void __launch_bounds__(256)
-k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
-         const uint32_t* __restrict__ seg_start, const uint32_t* __restrict__ sorted_vals,
-         const float* __restrict__ grad, UpdateTables tb, int d, float lr, float eps) {
-    const int groups_per_block = 256 / LPR;
-    const int gl = threadIdx.x / LPR;
+__device__ inline void update_short_rows(uint32_t u0, uint32_t stride, uint32_t n_unique,
+                                         const uint32_t* __restrict__ uniq_keys, const uint32_t* __restrict__ seg_start,
+                                         const uint32_t* __restrict__ sorted_vals, const float* __restrict__ grad,
+                                         const UpdateTables& tb, int d, float lr, float eps) {
     const int col4 = threadIdx.x % LPR;
     const int c0 = col4 * 4;
     const bool vec4 = (d & 3) == 0;
-    const uint32_t n_unique = counters[0];
-    for (uint32_t u = blockIdx.x * groups_per_block + gl; u < n_unique; u += gridDim.x * groups_per_block) {
+    for (uint32_t u = u0; u < n_unique; u += stride) {
         const uint32_t lo = seg_start[u], hi = seg_start[u + 1];
         if (hi - lo > (uint32_t)kLongLen) continue;
         if (vec4 && d <= 4 * LPR) {
@@ -157,6 +154,16 @@ k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uni
             apply_row(tb, uniq_keys[u], acc, d, cc, vec4, lr, eps);
         }
     }
+}
+
+template <int LPR>
+__global__ void __launch_bounds__(256)
+k_update(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
+         const uint32_t* __restrict__ seg_start, const uint32_t* __restrict__ sorted_vals,
+         const float* __restrict__ grad, UpdateTables tb, int d, float lr, float eps) {
+    constexpr int groups_per_block = 256 / LPR;
+    update_short_rows<LPR>(blockIdx.x * groups_per_block + threadIdx.x / LPR, gridDim.x * groups_per_block, counters[0],
+                           uniq_keys, seg_start, sorted_vals, grad, tb, d, lr, eps);
 }
 
 // Units of the two-level path: long row r owns ceil(len / kUnit) consecutive units;
@@ -197,20 +204,42 @@ k_long_plan(uint32_t* __restrict__ counters, const uint32_t* __restrict__ long_l
     }
 }
 
-// One block per unit: eight groups sum 32 consecutive gradient rows each, the eight partial
-// sums are added in group order; the result is an fp64 row in `partial`.
+// One block per unit: the block's groups sum kUnit / GROUPS consecutive gradient rows each, the partial
+// sums are added in group order by the lanes of group 0, which get the unit's fp64 sum of columns cc..cc+3.
+template <int LPR>
+__device__ inline void unit_sum(uint32_t lo_unit, uint32_t seg_hi, const uint32_t* __restrict__ sorted_vals,
+                                const float* __restrict__ grad, int d, int cbase, bool vec4, double* psum, double tot[4]) {
+    constexpr int GROUPS = 256 / LPR;
+    constexpr int PER_GROUP = kUnit / GROUPS;
+    const int gl = threadIdx.x / LPR;
+    const int col4 = threadIdx.x % LPR;
+    const int cc = cbase + col4 * 4;
+    const uint32_t lo = lo_unit + gl * PER_GROUP;
+    const uint32_t hi = min(seg_hi, lo + PER_GROUP);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    if (cc < d && lo < hi) sum_rows(grad, sorted_vals, lo, hi, d, cc, vec4, acc);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) psum[(gl * LPR + col4) * 4 + j] = acc[j];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tot[j] = 0.0;
+    if (gl == 0 && cc < d) {
+        for (int gq = 0; gq < GROUPS; ++gq)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tot[j] += psum[(gq * LPR + col4) * 4 + j];
+    }
+    __syncthreads();
+}
+
 template <int LPR>
 __global__ void __launch_bounds__(256)
 k_long_partial(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ long_list,
                const uint32_t* __restrict__ unit_start, const uint32_t* __restrict__ seg_start,
                const uint32_t* __restrict__ sorted_vals, const float* __restrict__ grad, int d,
                double* __restrict__ partial) {
-    constexpr int GROUPS = 256 / LPR;
-    constexpr int PER_GROUP = kUnit / GROUPS;
     extern __shared__ double psum[];          // [GROUPS][4 * LPR]
     const int gl = threadIdx.x / LPR;
     const int col4 = threadIdx.x % LPR;
-    const int c0 = col4 * 4;
     const bool vec4 = (d & 3) == 0;
     const uint32_t n_long = counters[2], n_units = counters[3];
     for (uint32_t unit = blockIdx.x; unit < n_units; unit += gridDim.x) {
@@ -221,23 +250,12 @@ k_long_partial(const uint32_t* __restrict__ counters, const uint32_t* __restrict
         }
         const uint32_t u = long_list[a];
         const uint32_t seg_lo = seg_start[u], seg_hi = seg_start[u + 1];
-        const uint32_t lo = seg_lo + (unit - unit_start[a]) * kUnit + gl * PER_GROUP;
-        const uint32_t hi = min(seg_hi, lo + PER_GROUP);
         for (int cbase = 0; cbase < d; cbase += 4 * LPR) {     // uniform trip count across the block
-            const int cc = cbase + c0;
-            double acc[4] = {0.0, 0.0, 0.0, 0.0};
-            if (cc < d && lo < hi) sum_rows(grad, sorted_vals, lo, hi, d, cc, vec4, acc);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) psum[(gl * LPR + col4) * 4 + j] = acc[j];
-            __syncthreads();
-            if (gl == 0 && cc < d) {
-                double tot[4] = {0.0, 0.0, 0.0, 0.0};
-                for (int gq = 0; gq < GROUPS; ++gq)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) tot[j] += psum[(gq * LPR + col4) * 4 + j];
+            const int cc = cbase + col4 * 4;
+            double tot[4];
+            unit_sum<LPR>(seg_lo + (unit - unit_start[a]) * kUnit, seg_hi, sorted_vals, grad, d, cbase, vec4, psum, tot);
+            if (gl == 0 && cc < d)
                 for (int j = 0; j < 4 && cc + j < d; ++j) partial[(int64_t)unit * d + cc + j] = tot[j];
-            }
-            __syncthreads();
         }
     }
 }
@@ -263,6 +281,57 @@ k_long_final(const uint32_t* __restrict__ counters, const uint32_t* __restrict__
             }
             apply_row(tb, uniq_keys[long_list[r]], acc, d, cc, vec4, lr, eps);
         }
+    }
+}
+
+// A batch of at most kSmallSortMax gradient rows is bound by launch latency: one launch does what
+// k_loss_reduce, k_update, k_long_partial and k_long_final do, with the same sums in the same order.
+//   blocks [0, row_blocks)            the table rows with few gradient rows
+//   blocks [row_blocks, gridDim - 1)  one block per table row with many: its units one after the other
+//   the last block                    the sum of the workgroups' loss terms
+template <int LPR>
+__global__ void __launch_bounds__(256)
+k_update_small(const uint32_t* __restrict__ counters, const uint32_t* __restrict__ uniq_keys,
+               const uint32_t* __restrict__ seg_start, const uint32_t* __restrict__ sorted_vals,
+               const uint32_t* __restrict__ long_list, const float* __restrict__ grad, UpdateTables tb, int d, float lr,
+               float eps, int row_blocks, const double* __restrict__ loss_partial, int64_t loss_n,
+               double* __restrict__ loss_sum) {
+    __shared__ double psum[4 * 256];
+    constexpr int groups_per_block = 256 / LPR;
+    const int b = blockIdx.x;
+    if (b < row_blocks) {
+        update_short_rows<LPR>(b * groups_per_block + threadIdx.x / LPR, row_blocks * groups_per_block, counters[0],
+                               uniq_keys, seg_start, sorted_vals, grad, tb, d, lr, eps);
+        return;
+    }
+    if (b == (int)gridDim.x - 1) {
+        double s = 0.0;
+        for (int64_t i = threadIdx.x; i < loss_n; i += 256) s += loss_partial[i];
+        psum[threadIdx.x] = s;
+        __syncthreads();
+        for (int off = 128; off > 0; off >>= 1) {
+            if ((int)threadIdx.x < off) psum[threadIdx.x] += psum[threadIdx.x + off];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0 && loss_n > 0) *loss_sum += psum[0];
+        return;
+    }
+    const uint32_t r = (uint32_t)(b - row_blocks);
+    if (r >= counters[2]) return;                              // uniform
+    const uint32_t u = long_list[r];
+    const uint32_t seg_lo = seg_start[u], seg_hi = seg_start[u + 1];
+    const bool vec4 = (d & 3) == 0;
+    const int gl = threadIdx.x / LPR, col4 = threadIdx.x % LPR;
+    for (int cbase = 0; cbase < d; cbase += 4 * LPR) {
+        const int cc = cbase + col4 * 4;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        for (uint32_t lo = seg_lo; lo < seg_hi; lo += kUnit) {
+            double tot[4];
+            unit_sum<LPR>(lo, seg_hi, sorted_vals, grad, d, cbase, vec4, psum, tot);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] += tot[j];
+        }
+        if (gl == 0 && cc < d) apply_row(tb, uniq_keys[u], acc, d, cc, vec4, lr, eps);
     }
 }
 
@@ -317,6 +386,35 @@ hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams&
     if (d <= 64) return launch_update_lpr<16>(st, g, bp, ws, sorted_vals, tb, long_rows);
     if (d <= 128) return launch_update_lpr<32>(st, g, bp, ws, sorted_vals, tb, long_rows);
     return launch_update_lpr<64>(st, g, bp, ws, sorted_vals, tb, long_rows);
+}
+
+template <int LPR>
+static hipError_t launch_update_small_lpr(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                                          const uint32_t* sorted_vals, const UpdateTables& tb, int64_t loss_n) {
+    const int groups = 256 / LPR;
+    const int row_blocks = (int)((g.n_occ + groups - 1) / groups);
+    const int long_blocks = (int)update_long_rows_capacity(g.n_occ);
+    hipLaunchKernelGGL(k_update_small<LPR>, dim3((unsigned)(row_blocks + long_blocks + 1)), dim3(256), 0, st, ws.counters,
+                       ws.uniq_keys, ws.seg_start, sorted_vals, ws.long_list, ws.grad, tb, bp.dim, bp.lr, bp.eps, row_blocks,
+                       ws.loss_partial, loss_n, ws.loss_sum);
+    return hipGetLastError();
+}
+
+bool update_is_small(const BatchGeom& g) { return g.n_occ > 0 && g.n_occ <= kSmallSortMax; }
+
+// Whole deterministic update of a small batch (update_is_small) and the sum of its loss terms, one launch.
+hipError_t launch_update_small(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                               const uint32_t* sorted_vals, int64_t loss_n) {
+    UpdateTables tb;
+    tb.E[0] = bp.E_src; tb.S[0] = bp.S_src;
+    tb.E[1] = bp.E_dst; tb.S[1] = bp.S_dst;
+    tb.E[2] = bp.E_rel; tb.S[2] = bp.S_rel;
+    tb.key_base[0] = 0; tb.key_base[1] = bp.key_base_dst; tb.key_base[2] = bp.key_base_rel;
+    const int d = bp.dim;
+    if (d <= 32) return launch_update_small_lpr<8>(st, g, bp, ws, sorted_vals, tb, loss_n);
+    if (d <= 64) return launch_update_small_lpr<16>(st, g, bp, ws, sorted_vals, tb, loss_n);
+    if (d <= 128) return launch_update_small_lpr<32>(st, g, bp, ws, sorted_vals, tb, loss_n);
+    return launch_update_small_lpr<64>(st, g, bp, ws, sorted_vals, tb, loss_n);
 }
 
 // Atomic mode: the batch gradient of every table row already sits in a dense fp32 accumulator

@@ -139,6 +139,10 @@ bool chunks_use_single_sweep(const BatchGeom& g, const BucketParams& bp, const W
 hipError_t launch_chunks(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws, bool redo);
 hipError_t launch_update(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
                          const uint32_t* sorted_vals, bool long_rows);
+// batches of at most kSmallSortMax gradient rows: loss sum, short and long rows in one launch
+bool update_is_small(const BatchGeom& g);
+hipError_t launch_update_small(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws,
+                               const uint32_t* sorted_vals, int64_t loss_n);
 hipError_t launch_update_atomic(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 hipError_t launch_loss_reduce(hipStream_t st, int64_t nwg, const Workspace& ws);
 hipError_t launch_score(hipStream_t st, const int64_t* src, const int32_t* rel, const int64_t* dst, int64_t m,

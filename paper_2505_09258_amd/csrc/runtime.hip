@@ -859,9 +859,12 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         // stays on one stream, where a kernel follows the other without a hop between streams.
         const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536;
         hipStream_t ls = !aside ? c->compute : c->aux2 ? c->aux2 : c->aux;
-        if (!aside) {
+        // ... and a batch of at most a few thousand has its loss sum and its whole update in one launch
+        const bool small = !bp.atomic_mode && update_is_small(g);
+        const int64_t loss_terms = (int64_t)g.sides * g.nchunks * g.T;
+        if (!aside && !small) {
             ProfScope ps(c, KC_MISC);
-            HIP_TRY(c, launch_loss_reduce(c->compute, (int64_t)g.sides * g.nchunks * g.T, ws));
+            HIP_TRY(c, launch_loss_reduce(c->compute, loss_terms, ws));
         }
         if (aside) HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
         if (ahead && b + 1 < batch_end) {
@@ -883,11 +886,14 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         if (bp.atomic_mode) {
             ProfScope ps(c, KC_UPDATE);
             HIP_TRY(c, launch_update_atomic(c->compute, g, bp, ws));
+        } else if (small) {
+            ProfScope ps(c, KC_UPDATE);
+            HIP_TRY(c, launch_update_small(c->compute, g, bp, ws, ws.vals[sorted_of[cur]], loss_terms));
         } else {
             if (aside) {
                 HIP_TRY(c, hipStreamWaitEvent(ls, c->ev_chunk_done, 0));
                 ProfScope ps(c, KC_MISC, ls);
-                HIP_TRY(c, launch_loss_reduce(ls, (int64_t)g.sides * g.nchunks * g.T, ws));
+                HIP_TRY(c, launch_loss_reduce(ls, loss_terms, ws));
             }
             {
                 ProfScope ps(c, KC_UPDATE_LONG, ls);
