@@ -113,10 +113,10 @@ struct legend_ctx {
     hipStream_t aux2 = nullptr;             // update of the table rows with many gradient rows, next to the other rows' update
     hipEvent_t ev_chunk_done = nullptr, ev_long_done = nullptr;
     hipEvent_t ev_start = nullptr;          // compute stream has reached the start of a bucket call
-    hipEvent_t ev_index[2] = {nullptr, nullptr};    // index side of a batch complete (per workspace)
-    hipEvent_t ev_updated[2] = {nullptr, nullptr};  // update of a batch complete: its index buffers are free
+    hipEvent_t ev_index[3] = {nullptr, nullptr, nullptr};    // index side of a batch complete (per workspace)
+    hipEvent_t ev_updated[3] = {nullptr, nullptr, nullptr};  // update of a batch complete: its index buffers are free
     Workspace ws{};                         // even batches of a call; also every serial path
-    Workspace ws_odd{};                     // odd batches: own index-side buffers, the rest shared with ws
+    Workspace ws_alt[2]{};                  // batches 1 and 2 (mod 3): own index-side buffers, the rest shared with ws
     BatchGeom gmax{};
     int key_bits = 0;
     int32_t* edges_dev = nullptr;
@@ -326,17 +326,21 @@ void free_ctx(legend_ctx* c) {
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
     void* frees[] = {c->E_rel, c->S_rel, c->d_part_emb, c->d_part_state, c->ws.neg_ids, c->ws.keys[0], c->ws.keys[1],
                      c->ws.vals[0], c->ws.vals[1], c->ws.ghist, c->ws.scan_tmp, c->ws.uniq_keys, c->ws.seg_start,
-                     c->ws.counters, c->ws_odd.neg_ids, c->ws_odd.keys[0], c->ws_odd.keys[1], c->ws_odd.vals[0], c->ws_odd.vals[1],
-                     c->ws_odd.ghist, c->ws_odd.scan_tmp, c->ws_odd.uniq_keys, c->ws_odd.seg_start, c->ws_odd.counters, c->ws_odd.long_list, c->ws_odd.unit_start, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->ws.gemm_Q, c->ws.gemm_G, c->ws.gemm_f,
+                     c->ws.counters, c->ws.long_list, c->ws.unit_start, c->ws.long_partial, c->ws.uniq_total, c->ws.grad, c->ws.loss_partial, c->ws.redo, c->ws.redo_total, c->ws.loss_sum, c->ws.gemm_Q, c->ws.gemm_G, c->ws.gemm_f,
                      c->ws.gemm_a, c->ws.gemm_S, c->edges_dev,
                      c->io_dev};
     for (void* p : frees) if (p) (void)hipFree(p);
+    for (Workspace& o : c->ws_alt) {
+        void* own[] = {o.neg_ids, o.keys[0], o.keys[1], o.vals[0], o.vals[1], o.ghist, o.scan_tmp, o.uniq_keys, o.seg_start,
+                       o.counters, o.long_list, o.unit_start};
+        for (void* p : own) if (p) (void)hipFree(p);
+    }
     if (c->aux) { (void)hipStreamSynchronize(c->aux); (void)hipStreamDestroy(c->aux); }
     if (c->aux2) { (void)hipStreamSynchronize(c->aux2); (void)hipStreamDestroy(c->aux2); }
     if (c->ev_chunk_done) (void)hipEventDestroy(c->ev_chunk_done);
     if (c->ev_long_done) (void)hipEventDestroy(c->ev_long_done);
     if (c->ev_start) (void)hipEventDestroy(c->ev_start);
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < 3; ++k) {
         if (c->ev_index[k]) (void)hipEventDestroy(c->ev_index[k]);
         if (c->ev_updated[k]) (void)hipEventDestroy(c->ev_updated[k]);
     }
@@ -573,7 +577,7 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
     INIT_TRY(hipEventCreateWithFlags(&c->ev_chunk_done, hipEventDisableTiming));
     INIT_TRY(hipEventCreateWithFlags(&c->ev_long_done, hipEventDisableTiming));
     INIT_TRY(hipEventCreateWithFlags(&c->ev_start, hipEventDisableTiming));
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < 3; ++k) {
         INIT_TRY(hipEventCreateWithFlags(&c->ev_index[k], hipEventDisableTiming));
         INIT_TRY(hipEventCreateWithFlags(&c->ev_updated[k], hipEventDisableTiming));
     }
@@ -686,10 +690,10 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         INIT_RC(dev_alloc(c, &w.gemm_a, rows));
         INIT_RC(dev_alloc(c, &w.gemm_S, (size_t)nwg * c->gmax.rows_tile * (size_t)gemm_npad(c->gmax.N)));
     }
-    {
-        // second set of index-side buffers, so that the index side of batch b+1 can be built while
-        // batch b is still being computed and applied
-        Workspace& o = c->ws_odd;
+    // Two more sets of index-side buffers: the index side of batch b+1 is built while batch b is still
+    // being computed and applied, into the set that batch b-2 has released (so it does not wait for
+    // the update of batch b-1 either).
+    for (Workspace& o : c->ws_alt) {
         o = w;
         o.neg_ids = nullptr; o.keys[0] = o.keys[1] = nullptr; o.vals[0] = o.vals[1] = nullptr;
         o.ghist = nullptr; o.scan_tmp = nullptr; o.uniq_keys = nullptr; o.seg_start = nullptr; o.counters = nullptr;
@@ -821,7 +825,8 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         bp.batch_lo = b * B;
         bp.hash_prefix = batch_hash_prefix(c, epoch, i, j, b);
     };
-    int sorted_of[2] = {0, 0};
+    int sorted_of[3] = {0, 0, 0};
+    auto wset = [&](int k) -> const Workspace& { return k == 0 ? c->ws : c->ws_alt[k - 1]; };
     const bool ahead = !c->serial_sort;
     if (ahead && batch_begin < batch_end) {
         BatchGeom g0;
@@ -833,8 +838,8 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         HIP_TRY(c, hipEventRecord(c->ev_index[0], c->aux));
     }
     for (int64_t b = batch_begin; b < batch_end; ++b) {
-        const int cur = ahead ? (int)((b - batch_begin) & 1) : 0;
-        const Workspace& ws = cur ? c->ws_odd : c->ws;
+        const int cur = ahead ? (int)((b - batch_begin) % 3) : 0;
+        const Workspace& ws = wset(cur);
         BatchGeom g;
         batch_params(b, &g);
         edges_done += g.P;
@@ -868,17 +873,17 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         }
         if (aside) HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
         if (ahead && b + 1 < batch_end) {
-            // next batch's index side: its workspace is free once the update of batch b-1 is done
-            const int nxt = cur ^ 1;
+            // next batch's index side: its buffers are free once the update of batch b-2 is done
+            const int nxt = (cur + 1) % 3;
             BatchGeom gn;
             BucketParams keep = bp;
             batch_params(b + 1, &gn);
-            if (b > batch_begin) HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_updated[nxt], 0));
+            if (b - batch_begin >= 2) HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_updated[nxt], 0));
             if (c->index_after_chunk) {
                 if (!aside) HIP_TRY(c, hipEventRecord(c->ev_chunk_done, c->compute));
                 HIP_TRY(c, hipStreamWaitEvent(c->aux, c->ev_chunk_done, 0));
             }
-            rc = enqueue_index_side(c, c->aux, gn, bp, nxt ? c->ws_odd : c->ws, &sorted_of[nxt]);
+            rc = enqueue_index_side(c, c->aux, gn, bp, wset(nxt), &sorted_of[nxt]);
             if (rc) return rc;
             HIP_TRY(c, hipEventRecord(c->ev_index[nxt], c->aux));
             bp = keep;
