@@ -257,11 +257,13 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
 }
 
 // ---- row statistics and weights ------------------------------------------------------------
-// One workgroup (16 waves) per row tile, one wave per row at a time; a row of scores is read
-// from the cache-resident buffer for the maximum, for the sum, and a third time to be replaced
-// by the weights W = dL/dS: exp(S - lse) for the softmax losses, w sigmoid(S) for the logistic
-// loss, 0 in the padding up to Npad.  rowa = dL/df, loss_partial[tile] = sum over the tile's rows.
+// One workgroup (16 waves) per row tile, one wave per row at a time.  A row of at most 1024 scores
+// is read once into registers (16 per lane), reduced, and written back as the weights W = dL/dS:
+// exp(S - lse) for the softmax losses, w sigmoid(S) for the logistic loss, 0 in the padding up to
+// Npad; a longer row is read from the cache-resident buffer once per pass instead.
+// rowa = dL/df, loss_partial[tile] = sum over the tile's rows.
 constexpr int kStatThreads = 1024;
+constexpr int kStatRegs = 16;                 // scores of a row per lane on the register path
 template <int LOSS>
 __global__ void __launch_bounds__(kStatThreads)
 k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float* __restrict__ fpos, int Npad,
@@ -272,6 +274,7 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
     const TileCoord tc = tile_coord(g, blockIdx.x);
     const int N = g.N;
     float* Stile = S + (int64_t)tc.wgrow * g.rows_tile * Npad;
+    const bool in_regs = Npad <= kStatRegs * kWave;
     double loss = 0.0;
     for (int row = w; row < tc.nrows; row += WAVES) {
         float* s = Stile + (int64_t)row * kGNeg;          // element n of the row sits at s[(n / 64) * tstride + n % 64]
@@ -279,13 +282,30 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
         auto at = [&](int n) -> float& { return s[(n >> 6) * tstride + (n & 63)]; };
         const int64_t ridx = (int64_t)tc.si * g.P + tc.e0 + row;
         const float f = fpos[ridx];
+        float x[kStatRegs];                               // x[j] = score lane + 64 j (register path)
+        if (in_regs) {
+#pragma unroll
+            for (int j = 0; j < kStatRegs; ++j) x[j] = lane + kWave * j < N ? s[j * tstride + lane] : -INFINITY;
+        }
         if (LOSS == LEGEND_LOSS_SOFTMAX) {
             float m = -INFINITY;
-            for (int n = lane; n < N; n += kWave) m = fmaxf(m, at(n));
+            if (in_regs) {
+#pragma unroll
+                for (int j = 0; j < kStatRegs; ++j) m = fmaxf(m, x[j]);
+            } else {
+                for (int n = lane; n < N; n += kWave) m = fmaxf(m, at(n));
+            }
             for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
             if (bp.softmax_with_pos) m = fmaxf(m, f);
             float l = 0.f;
-            for (int n = lane; n < N; n += kWave) l += fast_exp(at(n) - m);
+            if (in_regs) {
+#pragma unroll
+                for (int j = 0; j < kStatRegs; ++j) {     // same order of the lane's terms as the strided loop
+                    if (lane + kWave * j < N) { x[j] = fast_exp(x[j] - m); l += x[j]; }
+                }
+            } else {
+                for (int n = lane; n < N; n += kWave) l += fast_exp(at(n) - m);
+            }
             for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off, kWave);
             float a = -1.f;
             if (bp.softmax_with_pos) {
@@ -294,14 +314,32 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
                 l += pf;
             }
             const float il = 1.f / l;
-            for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? fast_exp(at(n) - m) * il : 0.f;
+            if (in_regs) {
+#pragma unroll
+                for (int j = 0; j < kStatRegs; ++j) {
+                    const int n = lane + kWave * j;
+                    if (n < Npad) s[j * tstride + lane] = n < N ? x[j] * il : 0.f;
+                }
+            } else {
+                for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? fast_exp(at(n) - m) * il : 0.f;
+            }
             if (lane == 0) rowa[ridx] = a;
             loss += (double)(m + logf(l) - f);
         } else {
             float t = 0.f;
-            for (int n = lane; n < N; n += kWave) t += softplusf(at(n));
+            if (in_regs) {
+#pragma unroll
+                for (int j = 0; j < kStatRegs; ++j) {
+                    const int n = lane + kWave * j;
+                    if (n < N) t += softplusf(x[j]);
+                    if (n < Npad) s[j * tstride + lane] = n < N ? bp.neg_weight * sigmoidf(x[j]) : 0.f;
+                }
+            } else {
+                for (int n = lane; n < N; n += kWave) t += softplusf(at(n));
+            }
             for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, kWave);
-            for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? bp.neg_weight * sigmoidf(at(n)) : 0.f;
+            if (!in_regs)
+                for (int n = lane; n < Npad; n += kWave) at(n) = n < N ? bp.neg_weight * sigmoidf(at(n)) : 0.f;
             if (lane == 0) rowa[ridx] = -sigmoidf(-f);
             loss += (double)(softplusf(-f) + bp.neg_weight * t);
         }
