@@ -621,13 +621,18 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
         hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
                            ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
 #define LEGEND_GEMM_RB(RB)                                                                                             \
-    case RB:                                                                                                           \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gq<kGColTile, RB>),                             \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)gq_lds);                              \
-        if (e != hipSuccess) return e;                                                                                 \
+    case RB: {                                                                                                         \
+        static PerDeviceFlag gq_configured;                                                                            \
+        if (gq_configured.pending()) {                                                                                 \
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_gq<kGColTile, RB>),                         \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)gq_lds);                          \
+            if (e != hipSuccess) return e;                                                                             \
+            gq_configured.set();                                                                                       \
+        }                                                                                                              \
         hipLaunchKernelGGL((k_gemm_gq<kGColTile, RB>), dim3((unsigned)xcd_grid(coltiles * tiles)), dim3(kGColTile * 4), gq_lds, \
                            st, g, bp, ws.neg_ids, ws.gemm_S, Npad, ws.gemm_G, coltiles, tiles);                        \
-        break;
+        break;                                                                                                         \
+    }
     {
         hipError_t e = hipSuccess;
         switch (rb < 7 ? rb : 7) {

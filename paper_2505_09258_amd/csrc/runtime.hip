@@ -130,6 +130,7 @@ struct legend_ctx {
     int64_t prof_launches[KC_COUNT] = {0};
     int64_t batches_done = 0;
     bool index_after_chunk = false;         // LEGEND_INDEX_AFTER_CHUNK=1: the next batch's index side starts when this batch's chunk kernel has finished, not when it is launched (a measurement knob)
+    bool no_small_update = false;           // LEGEND_NO_SMALL_UPDATE=1: small batches take the general update kernels too (tests compare the two)
     bool serial_sort = false;               // LEGEND_SERIAL_SORT=1: everything on the compute stream, batch after batch (for per-kernel timing)
     bool keep_loss = false;                 // epoch driver: do not reset the device loss sum per bucket
     bool part_tables_dirty = false;         // d_part_emb / d_part_state lag behind part_slot
@@ -532,6 +533,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         c->serial_sort = e && e[0] == '1';
         const char* wc = std::getenv("LEGEND_INDEX_AFTER_CHUNK");
         c->index_after_chunk = wc && wc[0] == '1';
+        const char* ns = std::getenv("LEGEND_NO_SMALL_UPDATE");
+        c->no_small_update = ns && ns[0] == '1';
     }
     c->nrel_rows = std::max(cfg->num_relations, 1);
     c->host_part.assign(c->n, nullptr);
@@ -865,7 +868,7 @@ int legend_train_bucket_range(legend_ctx* c, int32_t i, int32_t j, const int32_t
         const bool aside = ahead && !bp.atomic_mode && g.n_occ > 65536;
         hipStream_t ls = !aside ? c->compute : c->aux2 ? c->aux2 : c->aux;
         // ... and a batch of at most a few thousand has its loss sum and its whole update in one launch
-        const bool small = !bp.atomic_mode && update_is_small(g);
+        const bool small = !bp.atomic_mode && !c->no_small_update && update_is_small(g);
         const int64_t loss_terms = (int64_t)g.sides * g.nchunks * g.T;
         if (!aside && !small) {
             ProfScope ps(c, KC_MISC);

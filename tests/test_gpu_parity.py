@@ -591,6 +591,29 @@ def test_stream_layout_does_not_change_results(monkeypatch):
         assert np.array_equal(a, b)
 
 
+def test_small_batch_update_kernel_is_bit_identical_to_the_general_kernels(monkeypatch):
+    """Batches of at most 4096 gradient rows take one fused launch (loss sum, short rows, long rows); it must
+    give the bits of the general kernels (same sums in the same order).  Skewed sources make long rows."""
+    c = _case("small_update", DISTMULT, SOFTMAX, BOTH, 3_000, 3, 32, 1, 0, 0, 500, 100, 64, 32, 2_300, 0.3)
+    node, rel, edges = _inputs(c)
+    edges = edges.copy()
+    edges[::3, 0] = 7                                    # a hub: hundreds of gradient rows for one table row
+    edges[1::5, 2] = 11
+    outs = []
+    for general in ("0", "1"):
+        monkeypatch.setenv("LEGEND_NO_SMALL_UPDATE", general)
+        L, ctx = _gpu_ctx(c, node, rel)
+        try:
+            L.legend_swap_partition(ctx, -1, 0)
+            st = L.legend_train_bucket(ctx, 0, 0, edges, epoch=1)
+            outs.append((st["loss_sum"], _read_all(L, ctx, c)))
+        finally:
+            L.legend_destroy(ctx)
+    assert outs[0][0] == outs[1][0]
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert np.array_equal(a, b)
+
+
 def _random_cases(seed, count, stds=(0.1, 0.3)):
     """Seeded random shapes: every score, loss and corruption mode over dimensions on both sides of the
     kernels' boundaries (multiples of 4 and not, 100, 128 | 132, 400), chunk sizes from 1 to two row tiles,
