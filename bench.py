@@ -32,10 +32,10 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 # HBM bytes per launch of the dominant kernel and of the update kernel from the rocprofv3 counter runs
 # summarised under profiles/ (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, in KiB per dispatch, calibrated on a copy)
 TRAFFIC_BYTES = {
-    "c4": {"source": "profiles/c4_hbm_traffic.txt", "chunk": int((292959.8 * 2.0 + 442395.1) * 1024),
-           "update": int((702650.1 * 2.0 + 704163.4) * 1024)},
-    "c2": {"source": "profiles/c2_hbm_traffic.txt", "chunk": int((277718.7 * 2.0 + 442198.5) * 1024),
-           "update": int((525109.2 * 2.0 + 473212.5) * 1024)},
+    "c4": {"source": "profiles/c4_hbm_traffic.txt", "chunk": int((292958.9 * 2.0 + 442406.7) * 1024),
+           "update": int((702665.4 * 2.0 + 704152.9) * 1024)},
+    "c2": {"source": "profiles/c2_hbm_traffic.txt", "chunk": int((277714.0 * 2.0 + 442328.0) * 1024),
+           "update": int((525050.1 * 2.0 + 473205.4) * 1024)},
 }
 
 
