@@ -570,19 +570,26 @@ def test_device_resident_edges_give_the_same_result():
     assert np.array_equal(out[0][1], out[1][1])          # deterministic mode: bit-identical reruns
 
 
-def test_stream_layout_does_not_change_results(monkeypatch):
-    """Batches large enough for the three-stream layout (index side one batch ahead, long rows beside the
-    main update kernel) against the same batches with every kernel on one stream: bit-identical tables."""
-    c = _case("streams", DOT, SOFTMAX, DST, 30_000, 0, 100, 2, 0, 1, 5_000, 50, 1_000, 500, 22_000, 0.1)
+@pytest.mark.parametrize("n,capacity", [(2, None), (4, 3)], ids=["all_resident", "staged_three_slots"])
+def test_stream_layout_does_not_change_results(monkeypatch, n, capacity):
+    """Batches large enough for the multi-stream layout (index side up to two batches ahead in three sets of
+    buffers; long rows beside the main update kernel, on a stream of their own when every partition is resident
+    and on the index stream behind the next index side when the buffer is staged) against the same batches with
+    every kernel on one stream: bit-identical tables, and seven batches so that every buffer set is reused twice."""
+    c = _case("streams", DOT, SOFTMAX, DST, 60_000, 0, 100, n, 0, 1, 5_000, 50, 1_000, 500, 32_000, 0.1)
     node, rel, edges = _inputs(c)
+    edges = edges.copy()
+    edges[::4, 0] = 3                                    # a hub on each side: long rows in every batch
+    edges[1::4, 2] = 5
     outs = []
     for serial in ("0", "1"):
         monkeypatch.setenv("LEGEND_SERIAL_SORT", serial)
-        L, ctx = _gpu_ctx(c, node, rel)
+        L, ctx = _gpu_ctx(c, node, rel, capacity=capacity)
         try:
             for p in (0, 1):
                 L.legend_swap_partition(ctx, -1, p)
             st = L.legend_train_bucket(ctx, 0, 1, edges, epoch=2)
+            assert st["batches"] == 7
             outs.append((st["loss_sum"], _read_all(L, ctx, c)))
         finally:
             L.legend_destroy(ctx)
