@@ -374,7 +374,7 @@ def run_resident(args, w, K, W, L, graphs, torch, np, *, kernels_pass=True, cpu_
     Q = sides * (-(-P // w.chunk_size)) * N
     u_b = uniq / max(nbatches, 1)
     alg_bytes = 12 * P + 4 * Q + 4 * d * (2 * P + Q) + 16 * d * u_b
-    single_sweep = (w.dim == 100 and w.loss == graphs.LOSS_SOFTMAX and w.num_negs <= 1024 and args.update_mode != "atomic"
+    single_sweep = (w.dim in (100, 64) and w.loss == graphs.LOSS_SOFTMAX and w.num_negs <= 1024 and args.update_mode != "atomic"
                     and w.score != graphs.SCORE_TRANSE_L1 and os.environ.get("LEGEND_NO_FAST_CHUNK") != "1")
     kname = ("k_gemm_compose/scores/rowstats/gq/gneg/chain (one launch each)" if w.dim > 128
              else ("k_chunk_fast" if single_sweep else "k_chunk"))

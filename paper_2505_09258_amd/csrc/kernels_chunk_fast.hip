@@ -1,4 +1,4 @@
-// Single-sweep batch computation for the paper's large workloads: Eq. 1 loss, dim = 100, at most
+// Single-sweep batch computation for the paper's large workloads: Eq. 1 loss, dim = 100 (also 64), at most
 // 1024 negatives per chunk (paper Sec. 2.1 stage 5, Sec. 6).  The general kernel reads the
 // chunk's negatives twice because the row log-sum-exp must be known before any gradient.  Here
 // the softmax numerators are taken against a reference m_e fixed after the first tile of
@@ -813,7 +813,7 @@ k_chunk_fast(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, 
     }
 }
 
-// Built only for the dimension of the paper's large workloads (the fully unrolled sweep is
+// Built for the dimension of the paper's large workloads and for d = 64 (the fully unrolled sweep is
 // expensive to compile); every other shape takes the general kernel.  Each score function is
 // compiled in a translation unit of its own (this file with LEGEND_FAST_SCORE set), so that the
 // three compile side by side.
@@ -833,34 +833,40 @@ static hipError_t launch_fast_one(hipStream_t st, const BatchGeom& g, const Buck
     return hipGetLastError();
 }
 
-hipError_t launch_fast_dot_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
-hipError_t launch_fast_distmult_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
-hipError_t launch_fast_complex_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+template <int SC>
+static hipError_t launch_fast_score(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    if (bp.dim == 100) return launch_fast_one<SC, 100>(st, g, bp, ws);
+    if (bp.dim == 64) return launch_fast_one<SC, 64>(st, g, bp, ws);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_fast_dot(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_fast_distmult(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
+hipError_t launch_fast_complex(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws);
 
 #if LEGEND_FAST_SCORE == 0
-hipError_t launch_fast_dot_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    return launch_fast_one<LEGEND_SCORE_DOT, 100>(st, g, bp, ws);
+hipError_t launch_fast_dot(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    return launch_fast_score<LEGEND_SCORE_DOT>(st, g, bp, ws);
 }
 
 bool chunk_fast_applies(const BatchGeom& g, const BucketParams& bp) {
     if (bp.loss != LEGEND_LOSS_SOFTMAX || bp.atomic_mode != 0) return false;
     if (g.N > 2 * kFMaxSteps * kFTile || g.N > kIdsLds || g.rows_tile > kFRow) return false;
-    return bp.dim == 100;
+    return bp.dim == 100 || bp.dim == 64;
 }
 
 hipError_t launch_chunks_fast(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    if (bp.dim != 100) return hipErrorInvalidValue;
-    if (bp.score == LEGEND_SCORE_DOT) return launch_fast_dot_100(st, g, bp, ws);
-    if (bp.score == LEGEND_SCORE_DISTMULT) return launch_fast_distmult_100(st, g, bp, ws);
-    return launch_fast_complex_100(st, g, bp, ws);
+    if (bp.score == LEGEND_SCORE_DOT) return launch_fast_dot(st, g, bp, ws);
+    if (bp.score == LEGEND_SCORE_DISTMULT) return launch_fast_distmult(st, g, bp, ws);
+    return launch_fast_complex(st, g, bp, ws);
 }
 #elif LEGEND_FAST_SCORE == 1
-hipError_t launch_fast_distmult_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    return launch_fast_one<LEGEND_SCORE_DISTMULT, 100>(st, g, bp, ws);
+hipError_t launch_fast_distmult(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    return launch_fast_score<LEGEND_SCORE_DISTMULT>(st, g, bp, ws);
 }
 #else
-hipError_t launch_fast_complex_100(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
-    return launch_fast_one<LEGEND_SCORE_COMPLEX, 100>(st, g, bp, ws);
+hipError_t launch_fast_complex(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
+    return launch_fast_score<LEGEND_SCORE_COMPLEX>(st, g, bp, ws);
 }
 #endif
 

@@ -35,6 +35,8 @@ CASES = [
     _case("distmult_d400_both", DISTMULT, SOFTMAX, BOTH, 3_000, 45, 400, 1, 0, 0, 400, 100, 130, 0, 900, 0.15),
     _case("complex_d132_offdiag", COMPLEX, SOFTMAX, BOTH, 2_000, 7, 132, 2, 1, 0, 150, 40, 33, 8, 320, 0.3),
     _case("dot_d512_logistic", DOT, LOGISTIC, SRC, 800, 0, 512, 1, 0, 0, 96, 32, 64, 0, 200, 0.1),
+    # d = 64 through the single-sweep kernel: all eight steps of negatives with a ragged tail, partial last chunk
+    _case("complex_d64_n1000_both", COMPLEX, SOFTMAX, BOTH, 9_000, 5, 64, 2, 0, 1, 700, 50, 1_000, 300, 1_530, 0.3),
     # d = 100 with the largest negative count and full 64-row chunks (single-sweep kernel, all eight steps)
     _case("distmult_d100_n1024", DISTMULT, SOFTMAX, SRC, 8_000, 11, 100, 2, 1, 0, 640, 64, 1_024, 100, 1_500, 0.3),
     # Eq. 1 with the positive score inside the log-sum-exp, through each of the three chunk kernels
@@ -271,6 +273,9 @@ _BEYOND_CASES = [
     dict(_case("complex_d100_n1000_hot_rows", COMPLEX, SOFTMAX, DST, 12_000, 9, 100, 2, 1, 0, 1_000, 50, 1_000, 200, 2_500, 0.75),
          hot_every=64, hot_scale=4.0),
     dict(_case("dot_d100_softmax_pos_hot_rows", DOT, SOFTMAX_POS, DST, 12_000, 0, 100, 2, 0, 1, 1_000, 50, 300, 0, 2_500, 1.05),
+         hot_every=64, hot_scale=4.0),
+    # the single-sweep kernel's other dimension
+    dict(_case("distmult_d64_both_hot_rows", DISTMULT, SOFTMAX, BOTH, 12_000, 7, 64, 2, 0, 1, 1_000, 50, 300, 0, 2_500, 1.15),
          hot_every=64, hot_scale=4.0),
 ]
 
