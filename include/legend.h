@@ -54,7 +54,7 @@ enum { LEGEND_SCORE_DOT = 0, LEGEND_SCORE_DISTMULT = 1, LEGEND_SCORE_COMPLEX = 2
  * variant of Eq. 1 whose log-sum-exp also holds the positive score (sampled
  * cross-entropy: -f + log(exp f + sum_k exp S_k)), or the margin-based ranking
  * loss sum_k max(0, margin - f + S_k) (Sec. 8: other objectives fit the same
- * frame; product scores with dim <= 128 only, LEGEND_E_INVAL otherwise). */
+ * frame; every score function, margin >= 0 or LEGEND_E_INVAL). */
 enum { LEGEND_LOSS_SOFTMAX = 0, LEGEND_LOSS_LOGISTIC = 1, LEGEND_LOSS_SOFTMAX_POS = 2, LEGEND_LOSS_MARGIN = 3 };
 /* Which endpoint of a positive edge is replaced by sampled nodes. */
 enum { LEGEND_CORRUPT_DST = 0, LEGEND_CORRUPT_SRC = 1, LEGEND_CORRUPT_BOTH = 2 };

@@ -259,8 +259,8 @@ k_gemm_scores(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
 // ---- row statistics and weights ------------------------------------------------------------
 // One workgroup (16 waves) per row tile, one wave per row at a time.  A row of at most 1024 scores
 // is read once into registers (16 per lane), reduced, and written back as the weights W = dL/dS:
-// exp(S - lse) for the softmax losses, w sigmoid(S) for the logistic loss, 0 in the padding up to
-// Npad; a longer row is read from the cache-resident buffer once per pass instead.
+// exp(S - lse) for the softmax losses, w sigmoid(S) for the logistic loss, the indicator of
+// margin - f + S > 0 for the margin loss, 0 in the padding up to Npad; a longer row is read from the cache-resident buffer once per pass instead.
 // rowa = dL/df, loss_partial[tile] = sum over the tile's rows.
 constexpr int kStatThreads = 1024;
 constexpr int kStatRegs = 16;                 // scores of a row per lane on the register path
@@ -325,6 +325,32 @@ k_gemm_rowstats(BatchGeom g, BucketParams bp, float* __restrict__ S, const float
             }
             if (lane == 0) rowa[ridx] = a;
             loss += (double)(m + logf(l) - f);
+        } else if (LOSS == LEGEND_LOSS_MARGIN) {
+            // pair (row, negative) pays margin - f + S where that is positive: W is the indicator, dL/df minus their count
+            const float base = bp.margin - f;
+            float t = 0.f, cnt = 0.f;
+            if (in_regs) {
+#pragma unroll
+                for (int j = 0; j < kStatRegs; ++j) {
+                    const int n = lane + kWave * j;
+                    const float sh = n < N ? base + x[j] : 0.f;
+                    const float wv = sh > 0.f ? 1.f : 0.f;
+                    t += fmaxf(sh, 0.f);
+                    cnt += wv;
+                    if (n < Npad) s[j * tstride + lane] = wv;
+                }
+            } else {
+                for (int n = lane; n < Npad; n += kWave) {
+                    const float sh = n < N ? base + at(n) : 0.f;
+                    const float wv = sh > 0.f ? 1.f : 0.f;
+                    t += fmaxf(sh, 0.f);
+                    cnt += wv;
+                    at(n) = wv;
+                }
+            }
+            for (int off = 32; off > 0; off >>= 1) { t += __shfl_xor(t, off, kWave); cnt += __shfl_xor(cnt, off, kWave); }
+            if (lane == 0) rowa[ridx] = -cnt;
+            loss += (double)t;
         } else {
             float t = 0.f;
             if (in_regs) {
@@ -616,6 +642,9 @@ hipError_t launch_chunks_gemm(hipStream_t st, const BatchGeom& g, const BucketPa
 #undef LEGEND_GEMM_RB
     if (softmax)
         hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_SOFTMAX>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
+                           ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
+    else if (bp.loss == LEGEND_LOSS_MARGIN)
+        hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_MARGIN>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,
                            ws.gemm_S, ws.gemm_f, Npad, ws.gemm_a, ws.loss_partial);
     else
         hipLaunchKernelGGL(k_gemm_rowstats<LEGEND_LOSS_LOGISTIC>, dim3((unsigned)tiles), dim3(kStatThreads), 0, st, g, bp,

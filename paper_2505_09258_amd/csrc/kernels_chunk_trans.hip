@@ -5,7 +5,7 @@
 // The negative block is no matrix product, so nothing here uses the matrix pipe: the kernel is
 // bound by vector ALU throughput.  Two sweeps over the chunk's negatives in tiles of 64, as in the
 // general kernel for the product scores: the first takes the row-wise log-sum-exp (skipped for the
-// logistic loss), the second recomputes the scores, forms W = dL/dS and accumulates
+// logistic and margin losses), the second recomputes the scores, forms W = dL/dS and accumulates
 //   G_q[e] -= W[e][k] sign(q_e - n_k),   G_neg[k] += W[e][k] sign(q_e - n_k)
 // from one evaluation of every sign.
 #include <hip/hip_runtime.h>
@@ -205,6 +205,7 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
 #pragma unroll
     for (int i = 0; i < 8; ++i) accq[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     float neg_loss = 0.f;
+    float hinge[4] = {0.f, 0.f, 0.f, 0.f}, viol[4] = {0.f, 0.f, 0.f, 0.f};    // margin loss: rows 4ty..4ty+3 over this lane's columns
     const bool atomic = bp.atomic_mode != 0;
     float* Gn = side == 0 ? bp.G_dst : bp.G_src;
     for (int tile = 0; tile < ntiles; ++tile) {
@@ -226,6 +227,12 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
                     if (valid) {
                         if (LOSS == LEGEND_LOSS_SOFTMAX) {
                             w = expf(S[a][b] - lse_s[4 * ty + a]);
+                        } else if (LOSS == LEGEND_LOSS_MARGIN) {
+                            // the pair pays margin - f + S where that is positive; W is the indicator
+                            const float sh = (bp.margin - pos_s[4 * ty + a]) + S[a][b];
+                            w = sh > 0.f ? 1.f : 0.f;
+                            hinge[a] += fmaxf(sh, 0.f);
+                            viol[a] += w;
                         } else {
                             w = bp.neg_weight * sigmoidf(S[a][b]);
                             neg_loss += bp.neg_weight * softplusf(S[a][b]);
@@ -301,6 +308,21 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
         for (int off = kWave / 2; off > 0; off >>= 1) neg_loss += __shfl_down(neg_loss, off, kWave);
         if ((tid & 63) == 0) lse_s[tid >> 6] = neg_loss;
     }
+    if (LOSS == LEGEND_LOSS_MARGIN) {
+        // the 16 lanes tx = 0..15 of a row group hold disjoint columns of the same four rows
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+            for (int mask = 1; mask < 16; mask <<= 1) {
+                hinge[a] += wave_shfl_xor(hinge[a], mask);
+                viol[a] += wave_shfl_xor(viol[a], mask);
+            }
+            if (tx == 0) {
+                lse_s[4 * ty + a] = hinge[a];         // the row's loss term
+                rowloss_s[4 * ty + a] = viol[a];      // how many of its negatives pay: -dL/df
+            }
+        }
+    }
     __syncthreads();
     auto emit = [&](float* p, float v) {
         if (atomic) unsafeAtomicAdd(p, v);
@@ -320,6 +342,9 @@ k_chunk_trans(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids,
                     row_loss = lse_s[prow] - f;
                     a = -1.f;
                 }
+            } else if (LOSS == LEGEND_LOSS_MARGIN) {
+                a = -rowloss_s[prow];                         // read by the row's four lanes before one of them reuses the slot
+                row_loss = lse_s[prow];
             } else {
                 a = -sigmoidf(-f);
                 row_loss = softplusf(-f);
@@ -358,12 +383,14 @@ template <int LOSS>
 hipError_t launch_trans(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     const int QS = chunk_row_stride(bp.dim);
     const size_t lds = sizeof(float) * ((size_t)(kTRows + kTNeg) * QS + (size_t)kTNeg * kTWS + 3 * kTRows);
-    static size_t lds_allowed = 0;            // dynamic LDS above 64 KB has to be requested per kernel
-    if (lds > lds_allowed) {
+    static size_t lds_allowed[64] = {};       // dynamic LDS above 64 KB has to be requested per kernel and per device
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+    if (dev < 0 || lds > lds_allowed[dev]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_chunk_trans<LOSS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        lds_allowed = lds;
+        if (dev >= 0) lds_allowed[dev] = lds;
     }
     hipLaunchKernelGGL(k_chunk_trans<LOSS>, dim3((unsigned)(g.sides * g.nchunks * g.T)), dim3(kTThreads), lds, st, g, bp,
                        ws.neg_ids, ws.grad, ws.loss_partial);
@@ -375,6 +402,7 @@ hipError_t launch_trans(hipStream_t st, const BatchGeom& g, const BucketParams& 
 hipError_t launch_chunks_trans(hipStream_t st, const BatchGeom& g, const BucketParams& bp, const Workspace& ws) {
     if (bp.dim > kNarrowMaxDim || g.rows_tile > kTRows) return hipErrorInvalidValue;
     if (bp.loss == LEGEND_LOSS_LOGISTIC) return launch_trans<LEGEND_LOSS_LOGISTIC>(st, g, bp, ws);
+    if (bp.loss == LEGEND_LOSS_MARGIN) return launch_trans<LEGEND_LOSS_MARGIN>(st, g, bp, ws);
     return launch_trans<LEGEND_LOSS_SOFTMAX>(st, g, bp, ws);
 }
 

@@ -490,8 +490,8 @@ int legend_init_partitions(const legend_config* cfg, const float* init_node_emb,
         return fail(LEGEND_E_INVAL, "dim %d is not supported (1..%d)", cfg->dim, max_dim_supported());
     if (cfg->score < 0 || cfg->score > 3 || cfg->loss < 0 || cfg->loss > 3 || cfg->corrupt < 0 || cfg->corrupt > 2)
         return fail(LEGEND_E_INVAL, "unknown score, loss or corrupt selector");
-    if (cfg->loss == LEGEND_LOSS_MARGIN && (cfg->score == LEGEND_SCORE_TRANSE_L1 || cfg->dim > 128 || !(cfg->margin >= 0.f)))
-        return fail(LEGEND_E_INVAL, "the margin loss is implemented for the product scores with dim <= 128 and needs margin >= 0");
+    if (cfg->loss == LEGEND_LOSS_MARGIN && !(cfg->margin >= 0.f))
+        return fail(LEGEND_E_INVAL, "the margin loss needs margin >= 0");
     if (cfg->update_mode != LEGEND_UPDATE_DETERMINISTIC && cfg->update_mode != LEGEND_UPDATE_ATOMIC)
         return fail(LEGEND_E_INVAL, "unknown update_mode %d", cfg->update_mode);
     if (cfg->score == LEGEND_SCORE_COMPLEX && (cfg->dim & 1)) return fail(LEGEND_E_INVAL, "ComplEx needs an even dim");

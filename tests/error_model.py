@@ -72,6 +72,25 @@ def chunk_magnitudes(score, side_is_dst, s, r, d, negs, out, loss=None, margin=1
         return dict(m_neg=W.T @ aq, m_r=m_r, m_loss=(W * (A_neg + A_f[:, None])).sum(axis=1) + flip.sum(axis=1) * margin,
                     m_s=m_x if side_is_dst else m_other, m_d=m_other if side_is_dst else m_x,
                     b_neg=flip.T @ aq, b_r=b_r, b_s=b_x if side_is_dst else b_other, b_d=b_other if side_is_dst else b_x)
+    if score == TRANSE and loss == MARGIN_LOSS:
+        # scores are minus sums of absolute differences: their magnitude is their own absolute value; the weights
+        # are 0 or 1 and every gradient term is a sign
+        sg = np.abs(np.sign(q[:, None, :] - negs[None, :, :]))
+        sg_pos = np.abs(np.sign(q - other))
+        A_neg, A_f = np.abs(out["S"]), np.abs(out["f"])
+        short = margin - out["f"][:, None] + out["S"]
+        flip = (np.abs(short) <= BAND * (A_neg + A_f[:, None] + margin)).astype(np.float64)
+        # a gradient element is a sum of a few thousand terms +1, -1 or 0: exact in fp32 and in float64 alike, no
+        # rounding to allow for (the ordinary magnitudes are zero); only the either-way pairs can differ
+        m_q = np.zeros_like(q)
+        m_other = np.zeros_like(q)
+        b_q = flip.sum(axis=1)[:, None] * sg_pos + np.einsum("ck,ckj->cj", flip, sg)
+        b_other = flip.sum(axis=1)[:, None] * sg_pos
+        return dict(m_neg=np.zeros_like(negs), m_r=m_q,
+                    m_loss=(W * (A_neg + A_f[:, None])).sum(axis=1) + flip.sum(axis=1) * margin,
+                    m_s=m_q if side_is_dst else m_other, m_d=m_other if side_is_dst else m_q,
+                    b_neg=np.einsum("ck,ckj->kj", flip, sg), b_r=b_q,
+                    b_s=b_q if side_is_dst else b_other, b_d=b_other if side_is_dst else b_q)
     if score == TRANSE:
         sg = np.abs(np.sign(q[:, None, :] - negs[None, :, :]))        # which terms exist: sign(0) = 0 contributes nothing
         sg_pos = np.abs(np.sign(q - other))

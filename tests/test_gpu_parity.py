@@ -61,6 +61,11 @@ CASES = [
     dict(_case("dot_d100_margin", DOT, MARGIN, DST, 8_000, 0, 100, 2, 0, 1, 600, 50, 300, 60, 1_300, 0.3), margin=1.0),
     dict(_case("distmult_d64_margin_both", DISTMULT, MARGIN, BOTH, 5_000, 9, 64, 2, 1, 1, 500, 64, 130, 0, 1_100, 0.5), margin=0.5),
     dict(_case("complex_d20_margin_src", COMPLEX, MARGIN, SRC, 3_000, 5, 20, 1, 0, 0, 300, 33, 65, 10, 700, 0.6), margin=2.0),
+    # the margin loss with the translational score (the pairing that score was published with) and on the wide path
+    dict(_case("transe_d100_margin_both", TRANSE, MARGIN, BOTH, 6_000, 6, 100, 2, 0, 1, 400, 50, 200, 40, 900, 0.3), margin=1.0),
+    dict(_case("transe_d30_margin_dst", TRANSE, MARGIN, DST, 2_000, 3, 30, 1, 0, 0, 200, 64, 65, 0, 450, 0.5), margin=3.0),
+    dict(_case("distmult_d256_margin_both", DISTMULT, MARGIN, BOTH, 3_000, 8, 256, 1, 0, 0, 300, 100, 130, 20, 700, 0.2), margin=1.0),
+    dict(_case("dot_d132_margin_src", DOT, MARGIN, SRC, 2_500, 0, 132, 2, 1, 0, 200, 40, 64, 0, 450, 0.25), margin=0.5),
 ]
 
 # One node row in 64 is four times larger than the rest, so that some chunks hold a score far
