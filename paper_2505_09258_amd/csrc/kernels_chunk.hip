@@ -161,6 +161,16 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
 #pragma unroll
             for (int s = 0; s < STEPS; ++s)
                 pf[B][s] = *reinterpret_cast<const float4*>(En + (int64_t)idv[s] * d + gcol_ld);
+        } else if ((d & 1) == 0) {
+            // an even dimension that is no multiple of four: rows are 8-byte aligned, two 64-bit loads
+            const bool second = gcol_ld + 2 < d;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const float* p = En + (int64_t)idv[s] * d + gcol_ld;
+                const float2 a = *reinterpret_cast<const float2*>(p);
+                const float2 b = *reinterpret_cast<const float2*>(second ? p + 2 : p);
+                pf[B][s] = make_float4(a.x, a.y, second ? b.x : 0.f, second ? b.y : 0.f);
+            }
         } else {
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
@@ -462,6 +472,10 @@ k_chunk(BatchGeom g, BucketParams bp, const int32_t* __restrict__ neg_ids, float
                     float* dst = grad + (neg_base + neg) * d + gc0;
                     if (vec4) {
                         *reinterpret_cast<float4*>(dst) = lds4(src);
+                    } else if ((d & 1) == 0) {
+                        const float4 v = lds4(src);
+                        *reinterpret_cast<float2*>(dst) = make_float2(v.x, v.y);
+                        if (gc0 + 2 < d) *reinterpret_cast<float2*>(dst + 2) = make_float2(v.z, v.w);
                     } else {
                         dst[0] = src[0];
                         if (gc0 + 1 < d) dst[1] = src[1];

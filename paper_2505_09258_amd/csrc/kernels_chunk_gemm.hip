@@ -158,6 +158,13 @@ struct SliceRegs {                            // [ROWS][WIDTH columns] of row-ma
             if (p && c < d) {
                 if ((d & 3) == 0) {           // rows are 16-byte aligned only then
                     o = *reinterpret_cast<const float4*>(p + c);
+                } else if ((d & 1) == 0) {    // 8-byte aligned rows: two 64-bit loads
+                    const float2 a = *reinterpret_cast<const float2*>(p + c);
+                    o.x = a.x; o.y = a.y;
+                    if (c + 2 < d) {
+                        const float2 b = *reinterpret_cast<const float2*>(p + c + 2);
+                        o.z = b.x; o.w = b.y;
+                    }
                 } else {
                     o.x = p[c];
                     if (c + 1 < d) o.y = p[c + 1];

@@ -67,6 +67,31 @@ __device__ inline void sum_rows(const float* __restrict__ grad, const uint32_t* 
             acc[0] += (double)v1.x; acc[1] += (double)v1.y; acc[2] += (double)v1.z; acc[3] += (double)v1.w;
             acc[0] += (double)v2.x; acc[1] += (double)v2.y; acc[2] += (double)v2.z; acc[3] += (double)v2.w;
         }
+    } else if ((d & 1) == 0) {
+        // an even dimension that is no multiple of four (50 and 150 of the paper's dimension sweep): rows are
+        // 8-byte aligned, two 64-bit loads per gradient row, four rows in flight, added in order
+        const bool second = c0 + 2 < d;
+        auto row2 = [&](uint32_t o, float2& a, float2& b) {
+            const float* gp = grad + (int64_t)o * d + c0;
+            a = *reinterpret_cast<const float2*>(gp);
+            b = second ? *reinterpret_cast<const float2*>(gp + 2) : make_float2(0.f, 0.f);
+        };
+        for (; p + 4 <= hi; p += 4) {
+            float2 a0, b0, a1, b1, a2, b2, a3, b3;
+            row2(sorted_vals[p], a0, b0);
+            row2(sorted_vals[p + 1], a1, b1);
+            row2(sorted_vals[p + 2], a2, b2);
+            row2(sorted_vals[p + 3], a3, b3);
+            acc[0] += (double)a0.x; acc[1] += (double)a0.y; acc[2] += (double)b0.x; acc[3] += (double)b0.y;
+            acc[0] += (double)a1.x; acc[1] += (double)a1.y; acc[2] += (double)b1.x; acc[3] += (double)b1.y;
+            acc[0] += (double)a2.x; acc[1] += (double)a2.y; acc[2] += (double)b2.x; acc[3] += (double)b2.y;
+            acc[0] += (double)a3.x; acc[1] += (double)a3.y; acc[2] += (double)b3.x; acc[3] += (double)b3.y;
+        }
+        for (; p < hi; ++p) {
+            float2 a0, b0;
+            row2(sorted_vals[p], a0, b0);
+            acc[0] += (double)a0.x; acc[1] += (double)a0.y; acc[2] += (double)b0.x; acc[3] += (double)b0.y;
+        }
     } else {
         for (; p < hi; ++p) {
             const float* gp = grad + (int64_t)sorted_vals[p] * d + c0;
@@ -93,6 +118,21 @@ __device__ inline void apply_row(const UpdateTables& tb, uint32_t key, const dou
         adagrad_elem((float)acc[3], th.w, st.w, lr, eps);
         *reinterpret_cast<float4*>(ep) = th;
         *reinterpret_cast<float4*>(sp) = st;
+    } else if ((d & 1) == 0) {
+        const bool second = c0 + 2 < d;
+        float2 ta = *reinterpret_cast<float2*>(ep), sa = *reinterpret_cast<float2*>(sp);
+        float2 tb2 = make_float2(0.f, 0.f), sb2 = make_float2(0.f, 0.f);
+        if (second) { tb2 = *reinterpret_cast<float2*>(ep + 2); sb2 = *reinterpret_cast<float2*>(sp + 2); }
+        adagrad_elem((float)acc[0], ta.x, sa.x, lr, eps);
+        adagrad_elem((float)acc[1], ta.y, sa.y, lr, eps);
+        *reinterpret_cast<float2*>(ep) = ta;
+        *reinterpret_cast<float2*>(sp) = sa;
+        if (second) {
+            adagrad_elem((float)acc[2], tb2.x, sb2.x, lr, eps);
+            adagrad_elem((float)acc[3], tb2.y, sb2.y, lr, eps);
+            *reinterpret_cast<float2*>(ep + 2) = tb2;
+            *reinterpret_cast<float2*>(sp + 2) = sb2;
+        }
     } else {
         for (int j = 0; j < 4 && c0 + j < d; ++j) {
             float th = ep[j], st = sp[j];

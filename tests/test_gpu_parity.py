@@ -31,6 +31,9 @@ CASES = [
     _case("distmult_d6", DISTMULT, SOFTMAX, BOTH, 500, 3, 6, 2, 0, 1, 64, 7, 5, 2, 130, 0.5),
     _case("dot_d70_single_negative", DOT, SOFTMAX, DST, 900, 0, 70, 1, 0, 0, 100, 1, 1, 0, 150, 0.3),
     _case("complex_d34", COMPLEX, SOFTMAX, DST, 900, 4, 34, 1, 0, 0, 120, 33, 65, 0, 250, 0.4),
+    # odd dimensions (rows aligned to 4 bytes only): below and above 128
+    _case("distmult_d33_both", DISTMULT, SOFTMAX, BOTH, 1_200, 5, 33, 2, 1, 0, 150, 40, 70, 10, 330, 0.4),
+    _case("dot_d131_src", DOT, SOFTMAX, SRC, 1_000, 0, 131, 1, 0, 0, 120, 50, 65, 0, 260, 0.25),
     # dimensions above 128 take the chain of tiled contractions (112-row tiles, scores in a device buffer)
     _case("distmult_d400_both", DISTMULT, SOFTMAX, BOTH, 3_000, 45, 400, 1, 0, 0, 400, 100, 130, 0, 900, 0.15),
     _case("complex_d132_offdiag", COMPLEX, SOFTMAX, BOTH, 2_000, 7, 132, 2, 1, 0, 150, 40, 33, 8, 320, 0.3),
@@ -296,7 +299,7 @@ def test_single_sweep_kernel_scores_beyond_the_reference_at_the_real_limit(c):
     assert 0 < seen[0][0] < seen[0][1] and all(k < n for k, n in seen) and sum(k for k, _ in seen[1:]) > 0, seen
 
 
-_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[9:11] + [c for c in CASES if c["name"] in ("transe_d100_both", "distmult_d64_margin_both")]
+_ATOMIC_CASES = CASES[:5] + CASES[6:7] + CASES[11:13] + [c for c in CASES if c["name"] in ("transe_d100_both", "distmult_d64_margin_both")]
 
 
 @pytest.mark.parametrize("c", _ATOMIC_CASES, ids=[c["name"] for c in _ATOMIC_CASES])
